@@ -1,0 +1,112 @@
+"""Seeded synthetic workloads: shapes, seeds and random tensors only.
+
+This module holds none of the method's arithmetic.  It is the one module that
+both the HIP path's callers and the CPU oracle's callers may use, so that the
+two sides see bit-identical stored inputs.
+
+Each workload is one device's share of a sequence-parallel ring (paper Sec. 2.2):
+a resident query slice of `Nq` rows per head and `G` key/value chunks of `Nc`
+rows that arrive one at a time.  Values are i.i.d. N(0,1) drawn in fp32 from a
+seeded generator and rounded once to the storage dtype; the softmax scale is
+1/sqrt(d).  They stand in for LLaMA-7B / 13B attention activations at the
+paper's sequence lengths (Sec. 4.1), which need model weights and text that
+are not available offline.
+"""
+import math
+from dataclasses import dataclass
+
+import torch
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    B: int
+    H: int
+    d: int
+    Nq: int
+    G: int
+    Nc: int
+    dtype: str          # "bf16" | "f32": storage type of Q, K, V, O, dO
+    causal: bool
+    q_off: int          # global position of query row 0
+    seed: int
+
+    @property
+    def scale(self):
+        return 1.0 / math.sqrt(self.d)
+
+    def k_off(self, j):
+        return j * self.Nc
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.dtype == "bf16" else torch.float32
+
+    def visible_pairs_per_head(self):
+        """Number of (query, key) pairs that are not masked, per head."""
+        if not self.causal:
+            return self.Nq * self.G * self.Nc
+        total = 0
+        nk = self.G * self.Nc
+        for r in range(self.Nq):
+            total += max(0, min(nk, self.q_off + r + 1))
+        return total
+
+    def fwd_flops(self):
+        return 4.0 * self.visible_pairs_per_head() * self.d * self.H * self.B
+
+    def bwd_flops(self):
+        return 2.5 * self.fwd_flops()
+
+
+# Index = position in the benchmark's list of configurations.
+WORKLOADS = [
+    Workload("tiny_f32_G4", 1, 1, 64, 256, 4, 256, "f32", False, 0, 1000),
+    Workload("llama7b_32k_G8", 1, 32, 128, 4096, 8, 4096, "bf16", False, 0, 1001),
+    Workload("llama7b_128k_G32_rank31_causal", 1, 32, 128, 4096, 32, 4096, "bf16", True, 31 * 4096, 1002),
+    Workload("llama13b_128k_G8", 1, 40, 128, 16384, 8, 16384, "bf16", False, 0, 1003),
+    Workload("llama7b_1m_G32", 1, 32, 128, 32768, 32, 32768, "bf16", False, 0, 1004),
+]
+
+
+def by_name(name):
+    for w in WORKLOADS:
+        if w.name == name:
+            return w
+    raise KeyError(name)
+
+
+def _randn(shape, gen, device, dtype):
+    return torch.randn(shape, generator=gen, device=device, dtype=torch.float32).to(dtype)
+
+
+def make_inputs(w, device="cpu", seed=None):
+    """Returns dict(Q, K=[G chunks], V=[G chunks], dO); tensors are [B,H,rows,d]."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(w.seed if seed is None else seed)
+    dt = w.torch_dtype
+    Q = _randn((w.B, w.H, w.Nq, w.d), gen, device, dt)
+    K = [_randn((w.B, w.H, w.Nc, w.d), gen, device, dt) for _ in range(w.G)]
+    V = [_randn((w.B, w.H, w.Nc, w.d), gen, device, dt) for _ in range(w.G)]
+    dO = _randn((w.B, w.H, w.Nq, w.d), gen, device, dt)
+    return {"Q": Q, "K": K, "V": V, "dO": dO}
+
+
+def make_case(B, H, d, Nq, chunk_rows, dtype="bf16", seed=0, device="cpu",
+              causal=False, q_off=0, k_offs=None):
+    """Free-form case for parity tests: `chunk_rows` lists the rows of each chunk."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    Q = _randn((B, H, Nq, d), gen, device, dt)
+    K = [_randn((B, H, n, d), gen, device, dt) for n in chunk_rows]
+    V = [_randn((B, H, n, d), gen, device, dt) for n in chunk_rows]
+    dO = _randn((B, H, Nq, d), gen, device, dt)
+    if k_offs is None:
+        k_offs, s = [], 0
+        for n in chunk_rows:
+            k_offs.append(s)
+            s += n
+    return {"Q": Q, "K": K, "V": V, "dO": dO, "k_offs": list(k_offs),
+            "q_off": q_off, "causal": causal, "scale": 1.0 / math.sqrt(d)}
