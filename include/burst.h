@@ -1,0 +1,130 @@
+/*
+ * burst.h -- C ABI of the MI355X (gfx950) local-attention library.
+ *
+ * One device's share of a sequence-parallel attention ring (paper Sec. 2.2-2.4):
+ * a resident query slice Q_i is attended against key/value chunks (K_j, V_j) that
+ * arrive one at a time.  Each chunk's partial result is folded into a running
+ * state (O_acc, m, l) by online softmax (paper Alg. 1); burst_finalize turns the
+ * state into the output O_i and its log-sum-exp lse_i; the backward (paper Alg. 2)
+ * recomputes the attention probabilities of a block pair from lse_i.
+ *
+ * Conventions common to every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     never frees caller memory and never synchronises the stream; every call
+ *     only enqueues kernels on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream).  Pointers must be 16-byte aligned.
+ *   - Tensors are dense, row-major [B, H, rows, d] (d contiguous); per-row
+ *     vectors (m, l, lse, D) are [B, H, rows].
+ *   - Q, K, V, O, dO have element type `dtype` (bf16 or fp32).  The running
+ *     state, lse, D and all gradients are fp32.
+ *   - Scores are S = scale * Q K^T (Eq. 1 has scale = 1/sqrt(d); Alg. 1/2 omit
+ *     it, here it is always applied).  scale must be finite and > 0.
+ *   - Masking (not in the paper): with causal != 0 the key at global position
+ *     k_off + c is visible to the query at global position q_off + r iff
+ *     k_off + c <= q_off + r.  A row that sees no key keeps its state.
+ *   - Return value: 0 on success, a negative burst_status otherwise.  On error
+ *     nothing is enqueued and no output is written.
+ *   - Supported shapes: B, H >= 1; Nq, Nc >= 0 (0 = nothing to do); 1 <= d <= 128
+ *     for the generic kernels; the bf16 MFMA kernels are used when dtype = bf16
+ *     and d = 128.  Any Nq, Nc (ragged tails) are accepted.
+ */
+#ifndef BURST_H
+#define BURST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum burst_dtype { BURST_BF16 = 0, BURST_F32 = 1 };
+
+enum burst_status {
+  BURST_OK = 0,
+  BURST_ERR_NULL = -1,      /* a required pointer is NULL */
+  BURST_ERR_ALIGN = -2,     /* a pointer is not 16-byte aligned */
+  BURST_ERR_SHAPE = -3,     /* unsupported or inconsistent sizes, bad scale */
+  BURST_ERR_DTYPE = -4,     /* unknown dtype */
+  BURST_ERR_ARCH = -5,      /* current device is not gfx950 */
+  BURST_ERR_LAUNCH = -6,    /* the HIP runtime reported a launch error */
+  BURST_ERR_ALLOC = -7      /* internal scratch allocation failed */
+};
+
+typedef struct burst_params {
+  int32_t B;        /* batch */
+  int32_t H;        /* heads (the paper's Z) */
+  int32_t Nq;       /* rows of the resident query slice (the paper's N/G) */
+  int32_t Nc;       /* rows of this key/value chunk */
+  int32_t d;        /* head dimension */
+  int32_t dtype;    /* burst_dtype of Q, K, V, O, dO */
+  int32_t causal;   /* 0 = every key visible, 1 = mask by global position */
+  float   scale;    /* softmax scale, normally 1/sqrt(d) */
+  int64_t q_off;    /* global position of query row 0 */
+  int64_t k_off;    /* global position of row 0 of this chunk */
+} burst_params;
+
+/* Alg. 1, initialisation: O_acc = 0, l = 0, m = -inf.
+ * O_acc [B,H,Nq,d] fp32, m and l [B,H,Nq] fp32 (all written). */
+int burst_state_init(float* O_acc, float* m, float* l, const burst_params* p, void* stream);
+
+/* Alg. 1, body of the loop for one chunk, computed tile by tile (Sec. 2.4):
+ * S = scale Q K_chunk^T (masked), per-row max / exp / sum, P V_chunk, and the
+ * online-softmax merge into the state (m_new = max, rescale of l and O_acc).
+ * Q [B,H,Nq,d], K_chunk and V_chunk [B,H,Nc,d] (read only); O_acc, m, l are
+ * read and updated in place.  The state is any triple for which
+ * m + log l and O_acc / l are the true log-sum-exp and output of the keys seen
+ * so far; m is in natural-log units of the scaled scores and only a reference
+ * point (it need not be the exact running maximum).  No S or P is ever stored. */
+int burst_local_fwd(const void* Q, const void* K_chunk, const void* V_chunk,
+                    float* O_acc, float* m, float* l, const burst_params* p, void* stream);
+
+/* Alg. 1, last two steps: O = diag(l)^-1 O_acc (written as `dtype`),
+ * lse = m + log l (fp32).  Rows with l = 0 give O = 0, lse = -inf. */
+int burst_finalize(const float* O_acc, const float* m, const float* l,
+                   void* O_out, float* lse, const burst_params* p, void* stream);
+
+/* Alg. 1, the merge step on its own: state a <- merge(state a, state b), for
+ * combining two partial walks over disjoint key sets (tree / multi-device
+ * combine).  a is updated in place, b is read only. */
+int burst_merge_state(float* O_a, float* m_a, float* l_a,
+                      const float* O_b, const float* m_b, const float* l_b,
+                      const burst_params* p, void* stream);
+
+/* Alg. 2, pre-step: D = rowsum(dO o O).  O and dO [B,H,Nq,d] of `dtype`,
+ * D [B,H,Nq] fp32 (written). */
+int burst_bwd_prepare(const void* O, const void* dO, float* D, const burst_params* p, void* stream);
+
+/* Alg. 2, one block pair (query slice x one chunk): recompute
+ * S = scale Q K_chunk^T and P = exp(S - lse); dV += P^T dO; dP = dO V^T;
+ * dS = P o (dP - D); dK += scale dS^T Q; dQ += scale dS K.
+ * D may be NULL: it is then computed from O and dO into a scratch buffer that
+ * the library owns (allocated on first use, kept until process exit); with a
+ * non-NULL D, O is not read and may be NULL.
+ * dQ [B,H,Nq,d], dK_chunk and dV_chunk [B,H,Nc,d], all fp32.
+ * accumulate_dq / accumulate_dkv: 1 = add to what the buffer holds (the caller
+ * zero-fills before the first block pair), 0 = the buffer is overwritten with
+ * this block pair's contribution.  Floating-point accumulation order across
+ * workgroups is not fixed (hardware fp32 atomics), so results may differ in the
+ * last bits from run to run. */
+int burst_local_bwd(const void* Q, const void* K_chunk, const void* V_chunk,
+                    const void* O, const void* dO, const float* lse, const float* D,
+                    float* dQ, float* dK_chunk, float* dV_chunk,
+                    int accumulate_dq, int accumulate_dkv,
+                    const burst_params* p, void* stream);
+
+/* Timing helper for harnesses that cannot create HIP events themselves:
+ * records/queries events on the same stream the kernels are launched on.
+ * burst_event_create returns an opaque handle (NULL on failure). */
+void* burst_event_create(void);
+int   burst_event_record(void* event, void* stream);
+int   burst_event_elapsed_ms(void* start, void* stop, float* ms); /* waits for `stop` */
+void  burst_event_destroy(void* event);
+
+const char* burst_strerror(int status);
+int         burst_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BURST_H */

@@ -1,0 +1,164 @@
+"""ctypes binding of libburst.so: same names as the C ABI, argument marshalling only.
+
+Every step of the path runs inside the library's HIP kernels; nothing here computes.
+PyTorch tensors are used as device buffers; kernels are enqueued on torch's current
+stream.  There is no fallback: if the library is missing, loading raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libburst.so")
+
+BURST_BF16, BURST_F32 = 0, 1
+
+EXPORTS = [
+    "burst_state_init", "burst_local_fwd", "burst_finalize", "burst_merge_state",
+    "burst_bwd_prepare", "burst_local_bwd", "burst_event_create", "burst_event_record",
+    "burst_event_elapsed_ms", "burst_event_destroy", "burst_strerror", "burst_version",
+]
+
+
+class BurstParams(ctypes.Structure):
+    _fields_ = [
+        ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("Nq", ctypes.c_int32), ("Nc", ctypes.c_int32),
+        ("d", ctypes.c_int32), ("dtype", ctypes.c_int32), ("causal", ctypes.c_int32),
+        ("scale", ctypes.c_float), ("q_off", ctypes.c_int64), ("k_off", ctypes.c_int64),
+    ]
+
+
+class BurstError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} (status {code})")
+
+
+_lib = None
+
+
+def load():
+    """Loads the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, fp, pp = ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(BurstParams)
+    lib.burst_state_init.argtypes = [fp, fp, fp, pp, vp]
+    lib.burst_local_fwd.argtypes = [vp, vp, vp, fp, fp, fp, pp, vp]
+    lib.burst_finalize.argtypes = [fp, fp, fp, vp, fp, pp, vp]
+    lib.burst_merge_state.argtypes = [fp, fp, fp, fp, fp, fp, pp, vp]
+    lib.burst_bwd_prepare.argtypes = [vp, vp, fp, pp, vp]
+    lib.burst_local_bwd.argtypes = [vp, vp, vp, vp, vp, fp, fp, fp, fp, fp, ctypes.c_int, ctypes.c_int, pp, vp]
+    for name in ("burst_state_init", "burst_local_fwd", "burst_finalize", "burst_merge_state",
+                 "burst_bwd_prepare", "burst_local_bwd", "burst_event_record", "burst_version"):
+        getattr(lib, name).restype = ctypes.c_int
+    lib.burst_event_create.argtypes = []
+    lib.burst_event_create.restype = vp
+    lib.burst_event_record.argtypes = [vp, vp]
+    lib.burst_event_elapsed_ms.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float)]
+    lib.burst_event_elapsed_ms.restype = ctypes.c_int
+    lib.burst_event_destroy.argtypes = [vp]
+    lib.burst_event_destroy.restype = None
+    lib.burst_strerror.argtypes = [ctypes.c_int]
+    lib.burst_strerror.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def strerror(code):
+    return load().burst_strerror(int(code)).decode()
+
+
+def version():
+    return load().burst_version()
+
+
+def params(B, H, Nq, Nc, d, dtype, scale, causal=False, q_off=0, k_off=0):
+    code = {torch.bfloat16: BURST_BF16, torch.float32: BURST_F32, "bf16": BURST_BF16, "f32": BURST_F32}.get(dtype, dtype)
+    return BurstParams(B, H, Nq, Nc, d, code, 1 if causal else 0, scale, q_off, k_off)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    if not t.is_contiguous():
+        raise ValueError("contiguous tensor expected")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _f32(t):
+    if t is not None and t.dtype != torch.float32:
+        raise ValueError("float32 tensor expected")
+    return _ptr(t)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(code, where):
+    if code != 0:
+        raise BurstError(code, where)
+
+
+def burst_state_init(O_acc, m, l, p):
+    _check(load().burst_state_init(_f32(O_acc), _f32(m), _f32(l), ctypes.byref(p), _stream()), "burst_state_init")
+
+
+def burst_local_fwd(Q, K_chunk, V_chunk, O_acc, m, l, p):
+    _check(load().burst_local_fwd(_ptr(Q), _ptr(K_chunk), _ptr(V_chunk), _f32(O_acc), _f32(m), _f32(l),
+                                  ctypes.byref(p), _stream()), "burst_local_fwd")
+
+
+def burst_finalize(O_acc, m, l, O_out, lse, p):
+    _check(load().burst_finalize(_f32(O_acc), _f32(m), _f32(l), _ptr(O_out), _f32(lse),
+                                 ctypes.byref(p), _stream()), "burst_finalize")
+
+
+def burst_merge_state(O_a, m_a, l_a, O_b, m_b, l_b, p):
+    _check(load().burst_merge_state(_f32(O_a), _f32(m_a), _f32(l_a), _f32(O_b), _f32(m_b), _f32(l_b),
+                                    ctypes.byref(p), _stream()), "burst_merge_state")
+
+
+def burst_bwd_prepare(O, dO, D, p):
+    _check(load().burst_bwd_prepare(_ptr(O), _ptr(dO), _f32(D), ctypes.byref(p), _stream()), "burst_bwd_prepare")
+
+
+def burst_local_bwd(Q, K_chunk, V_chunk, O, dO, lse, D, dQ, dK_chunk, dV_chunk, p,
+                    accumulate_dq=True, accumulate_dkv=False):
+    _check(load().burst_local_bwd(_ptr(Q), _ptr(K_chunk), _ptr(V_chunk), _ptr(O), _ptr(dO), _f32(lse), _f32(D),
+                                  _f32(dQ), _f32(dK_chunk), _f32(dV_chunk),
+                                  1 if accumulate_dq else 0, 1 if accumulate_dkv else 0,
+                                  ctypes.byref(p), _stream()), "burst_local_bwd")
+
+
+class Event:
+    """HIP event recorded on the stream the kernels are launched on."""
+
+    def __init__(self):
+        self.h = load().burst_event_create()
+        if not self.h:
+            raise RuntimeError("burst_event_create failed")
+
+    def record(self):
+        _check(load().burst_event_record(self.h, _stream()), "burst_event_record")
+
+    def elapsed_ms_until(self, stop):
+        ms = ctypes.c_float(0.0)
+        _check(load().burst_event_elapsed_ms(self.h, stop.h, ctypes.byref(ms)), "burst_event_elapsed_ms")
+        return ms.value
+
+    def __del__(self):
+        try:
+            if self.h:
+                load().burst_event_destroy(self.h)
+                self.h = None
+        except Exception:
+            pass

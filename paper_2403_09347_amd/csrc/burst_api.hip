@@ -1,0 +1,221 @@
+// C ABI (see include/burst.h): argument validation and dispatch to the kernels.
+#include <hip/hip_runtime.h>
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include "burst_common.h"
+
+namespace burst {
+int launch_state_init(const KParams&, float*, float*, float*, hipStream_t);
+int launch_finalize(const KParams&, int, const float*, const float*, const float*, void*, float*, hipStream_t);
+int launch_merge_state(const KParams&, float*, float*, float*, const float*, const float*, const float*, hipStream_t);
+int launch_bwd_prepare(const KParams&, int, const void*, const void*, float*, hipStream_t);
+int launch_zero_fill(float*, long long, hipStream_t);
+int launch_fwd_mfma(const KParams&, const void*, const void*, const void*, float*, float*, float*, hipStream_t);
+int launch_fwd_generic(const KParams&, int, const void*, const void*, const void*, float*, float*, float*, hipStream_t);
+int launch_bwd_mfma(const KParams&, const void*, const void*, const void*, const void*, const float*, const float*,
+                    float*, float*, float*, int, int, hipStream_t);
+int launch_bwd_generic(const KParams&, int, const void*, const void*, const void*, const void*, const float*,
+                       const float*, float*, float*, float*, int, int, hipStream_t);
+}  // namespace burst
+
+namespace {
+
+using burst::KParams;
+
+constexpr int kMaxDevices = 64;
+int g_arch_ok[kMaxDevices];                 // 0 = unknown, 1 = gfx950, -1 = other
+float* g_d_scratch[kMaxDevices];            // library-owned D buffer for burst_local_bwd(D = NULL)
+size_t g_d_scratch_elems[kMaxDevices];
+std::mutex g_mutex;
+
+int check_arch() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return BURST_ERR_ARCH;
+  std::lock_guard<std::mutex> lock(g_mutex);
+  if (g_arch_ok[dev] == 0) {
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return BURST_ERR_ARCH;
+    g_arch_ok[dev] = (std::strncmp(prop.gcnArchName, "gfx950", 6) == 0) ? 1 : -1;
+  }
+  return g_arch_ok[dev] == 1 ? BURST_OK : BURST_ERR_ARCH;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Validates the parameter block; fills the kernel-side copy.
+int check_params(const burst_params* p, KParams* k) {
+  if (p == nullptr) return BURST_ERR_NULL;
+  if (p->dtype != BURST_BF16 && p->dtype != BURST_F32) return BURST_ERR_DTYPE;
+  if (p->B < 1 || p->H < 1 || p->Nq < 0 || p->Nc < 0 || p->d < 1 || p->d > 128) return BURST_ERR_SHAPE;
+  if (!(p->scale > 0.f) || !std::isfinite(p->scale)) return BURST_ERR_SHAPE;
+  if ((long long)p->B * p->H > 0x7fffffffLL) return BURST_ERR_SHAPE;
+  // rows must be addressable with 16-byte aligned row starts for the vector kernels
+  k->B = p->B; k->H = p->H; k->Nq = p->Nq; k->Nc = p->Nc; k->d = p->d;
+  k->causal = p->causal != 0; k->scale = p->scale; k->q_off = p->q_off; k->k_off = p->k_off;
+  return BURST_OK;
+}
+
+#define REQUIRE_PTR(ptr)                                 \
+  do {                                                   \
+    if ((ptr) == nullptr) return BURST_ERR_NULL;         \
+    if (!aligned16(ptr)) return BURST_ERR_ALIGN;         \
+  } while (0)
+
+bool use_mfma(const burst_params* p) { return p->dtype == BURST_BF16 && p->d == 128; }
+
+int get_d_scratch(size_t elems, float** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return BURST_ERR_ALLOC;
+  std::lock_guard<std::mutex> lock(g_mutex);
+  if (g_d_scratch_elems[dev] < elems) {
+    if (g_d_scratch[dev] != nullptr) {
+      if (hipFree(g_d_scratch[dev]) != hipSuccess) return BURST_ERR_ALLOC;   // waits for users of the old buffer
+      g_d_scratch[dev] = nullptr;
+      g_d_scratch_elems[dev] = 0;
+    }
+    float* ptr = nullptr;
+    if (hipMalloc(&ptr, elems * sizeof(float)) != hipSuccess) return BURST_ERR_ALLOC;
+    g_d_scratch[dev] = ptr;
+    g_d_scratch_elems[dev] = elems;
+  }
+  *out = g_d_scratch[dev];
+  return BURST_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int burst_state_init(float* O_acc, float* m, float* l, const burst_params* p, void* stream) {
+  KParams k;
+  int st = check_params(p, &k);
+  if (st != BURST_OK) return st;
+  if ((long long)k.B * k.H * k.Nq == 0) return BURST_OK;
+  REQUIRE_PTR(O_acc); REQUIRE_PTR(m); REQUIRE_PTR(l);
+  if ((st = check_arch()) != BURST_OK) return st;
+  return burst::launch_state_init(k, O_acc, m, l, (hipStream_t)stream);
+}
+
+int burst_local_fwd(const void* Q, const void* K_chunk, const void* V_chunk,
+                    float* O_acc, float* m, float* l, const burst_params* p, void* stream) {
+  KParams k;
+  int st = check_params(p, &k);
+  if (st != BURST_OK) return st;
+  if ((long long)k.B * k.H * k.Nq == 0 || k.Nc == 0) return BURST_OK;   // an empty chunk is the identity
+  REQUIRE_PTR(Q); REQUIRE_PTR(K_chunk); REQUIRE_PTR(V_chunk);
+  REQUIRE_PTR(O_acc); REQUIRE_PTR(m); REQUIRE_PTR(l);
+  if ((st = check_arch()) != BURST_OK) return st;
+  if (use_mfma(p)) return burst::launch_fwd_mfma(k, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
+  return burst::launch_fwd_generic(k, p->dtype, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
+}
+
+int burst_finalize(const float* O_acc, const float* m, const float* l,
+                   void* O_out, float* lse, const burst_params* p, void* stream) {
+  KParams k;
+  int st = check_params(p, &k);
+  if (st != BURST_OK) return st;
+  if ((long long)k.B * k.H * k.Nq == 0) return BURST_OK;
+  REQUIRE_PTR(O_acc); REQUIRE_PTR(m); REQUIRE_PTR(l); REQUIRE_PTR(O_out); REQUIRE_PTR(lse);
+  if ((st = check_arch()) != BURST_OK) return st;
+  return burst::launch_finalize(k, p->dtype, O_acc, m, l, O_out, lse, (hipStream_t)stream);
+}
+
+int burst_merge_state(float* O_a, float* m_a, float* l_a,
+                      const float* O_b, const float* m_b, const float* l_b,
+                      const burst_params* p, void* stream) {
+  KParams k;
+  int st = check_params(p, &k);
+  if (st != BURST_OK) return st;
+  if ((long long)k.B * k.H * k.Nq == 0) return BURST_OK;
+  REQUIRE_PTR(O_a); REQUIRE_PTR(m_a); REQUIRE_PTR(l_a);
+  REQUIRE_PTR(O_b); REQUIRE_PTR(m_b); REQUIRE_PTR(l_b);
+  if ((st = check_arch()) != BURST_OK) return st;
+  return burst::launch_merge_state(k, O_a, m_a, l_a, O_b, m_b, l_b, (hipStream_t)stream);
+}
+
+int burst_bwd_prepare(const void* O, const void* dO, float* D, const burst_params* p, void* stream) {
+  KParams k;
+  int st = check_params(p, &k);
+  if (st != BURST_OK) return st;
+  if ((long long)k.B * k.H * k.Nq == 0) return BURST_OK;
+  REQUIRE_PTR(O); REQUIRE_PTR(dO); REQUIRE_PTR(D);
+  if ((st = check_arch()) != BURST_OK) return st;
+  return burst::launch_bwd_prepare(k, p->dtype, O, dO, D, (hipStream_t)stream);
+}
+
+int burst_local_bwd(const void* Q, const void* K_chunk, const void* V_chunk,
+                    const void* O, const void* dO, const float* lse, const float* D,
+                    float* dQ, float* dK_chunk, float* dV_chunk,
+                    int accumulate_dq, int accumulate_dkv,
+                    const burst_params* p, void* stream) {
+  KParams k;
+  int st = check_params(p, &k);
+  if (st != BURST_OK) return st;
+  const long long bh = (long long)k.B * k.H;
+  const bool have_q = bh * k.Nq > 0, have_k = bh * k.Nc > 0;
+  if (!have_q && !have_k) return BURST_OK;
+  if (have_q) { REQUIRE_PTR(Q); REQUIRE_PTR(dO); REQUIRE_PTR(lse); REQUIRE_PTR(dQ); }
+  if (have_k) { REQUIRE_PTR(K_chunk); REQUIRE_PTR(V_chunk); REQUIRE_PTR(dK_chunk); REQUIRE_PTR(dV_chunk); }
+  if (D != nullptr && !aligned16(D)) return BURST_ERR_ALIGN;
+  if (D == nullptr && have_q) REQUIRE_PTR(O);
+  if ((st = check_arch()) != BURST_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  // Degenerate sides: nothing to contract over, the contribution is zero.
+  if (!have_q || !have_k) {
+    if (have_q && !accumulate_dq && (st = burst::launch_zero_fill(dQ, bh * k.Nq * k.d, s)) != BURST_OK) return st;
+    if (have_k && !accumulate_dkv) {
+      if ((st = burst::launch_zero_fill(dK_chunk, bh * k.Nc * k.d, s)) != BURST_OK) return st;
+      if ((st = burst::launch_zero_fill(dV_chunk, bh * k.Nc * k.d, s)) != BURST_OK) return st;
+    }
+    return BURST_OK;
+  }
+  const float* Duse = D;
+  if (Duse == nullptr) {
+    float* scratch = nullptr;
+    if ((st = get_d_scratch((size_t)(bh * k.Nq), &scratch)) != BURST_OK) return st;
+    if ((st = burst::launch_bwd_prepare(k, p->dtype, O, dO, scratch, s)) != BURST_OK) return st;
+    Duse = scratch;
+  }
+  if (use_mfma(p))
+    return burst::launch_bwd_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, dK_chunk, dV_chunk,
+                                  accumulate_dq != 0, accumulate_dkv != 0, s);
+  return burst::launch_bwd_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, dK_chunk, dV_chunk,
+                                   accumulate_dq != 0, accumulate_dkv != 0, s);
+}
+
+void* burst_event_create(void) {
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return (void*)e;
+}
+int burst_event_record(void* event, void* stream) {
+  if (event == nullptr) return BURST_ERR_NULL;
+  return hipEventRecord((hipEvent_t)event, (hipStream_t)stream) == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+}
+int burst_event_elapsed_ms(void* start, void* stop, float* ms) {
+  if (start == nullptr || stop == nullptr || ms == nullptr) return BURST_ERR_NULL;
+  if (hipEventSynchronize((hipEvent_t)stop) != hipSuccess) return BURST_ERR_LAUNCH;
+  return hipEventElapsedTime(ms, (hipEvent_t)start, (hipEvent_t)stop) == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+}
+void burst_event_destroy(void* event) {
+  if (event != nullptr) (void)hipEventDestroy((hipEvent_t)event);
+}
+
+const char* burst_strerror(int status) {
+  switch (status) {
+    case BURST_OK: return "ok";
+    case BURST_ERR_NULL: return "a required pointer is NULL";
+    case BURST_ERR_ALIGN: return "a pointer is not 16-byte aligned";
+    case BURST_ERR_SHAPE: return "unsupported or inconsistent sizes or scale";
+    case BURST_ERR_DTYPE: return "unknown dtype";
+    case BURST_ERR_ARCH: return "current device is not gfx950";
+    case BURST_ERR_LAUNCH: return "HIP runtime reported a launch error";
+    case BURST_ERR_ALLOC: return "internal scratch allocation failed";
+    default: return "unknown status";
+  }
+}
+
+int burst_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,513 @@
+// Backward of one block pair (paper Alg. 2 loop body) for bf16, d = 128, as two kernels.
+//
+// Alg. 2 accumulates dK_i, dV_i over query rows and dQ_j over keys.  On this GPU a single
+// kernel that keeps one side in registers has to push the other side through fp32 atomics,
+// whose rate (about one per clock per L2 channel) is far below what d = 128 needs.  So the
+// block pair is done twice, each time with the reduction side held in registers:
+//   * bwd_dq:  query rows stationary (64 per wavefront), keys streamed in 32-key tiles:
+//              S^T = K Q^T, dP^T = V dO^T, dS^T = P^T o (dP^T - D), dQ^T += K^T dS^T
+//   * bwd_dkv: keys stationary (64 per wavefront), query rows streamed in 32-row tiles:
+//              S = Q K^T, dP = dO V^T, P, dS, dV += P^T dO, dK += dS^T Q
+// Both recompute P = exp(S - lse) from the saved log-sum-exp; neither stores S, P or dS.
+// No atomics: results are deterministic.
+#include "burst_common.h"
+
+namespace burst {
+
+struct BwdArgs {
+  const bf16* Q; const bf16* K; const bf16* V; const bf16* dO;
+  const float* lse; const float* D;
+  float* dQ; float* dK; float* dV;
+  int Nq, Nc, H;
+  int causal;
+  float c;               // scale * log2(e)
+  float scale;
+  long long q_off, k_off;
+  int blocks_per_head;
+  int acc_dq, acc_dkv;
+};
+
+// 32 rows x 128 bf16 tile: 512 granules of 16 B, 2 per thread.
+__device__ __forceinline__ void load_tile32_regs(const bf16* __restrict__ base, int row0, int nrows,
+                                                 int tid, i32x4 (&r)[2]) {
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    int gi = i * 256 + tid;
+    int row = gi >> 4, g = gi & 15;
+    i32x4 v = {0, 0, 0, 0};
+    if (row0 + row < nrows)
+      v = *reinterpret_cast<const i32x4*>(base + (size_t)(row0 + row) * 128 + g * 8);
+    r[i] = v;
+  }
+}
+__device__ __forceinline__ void store_tile32_lds(char* lds, int tid, const i32x4 (&r)[2]) {
+#pragma unroll
+  for (int i = 0; i < 2; i++) {
+    int gi = i * 256 + tid;
+    int row = gi >> 4, g = gi & 15;
+    *reinterpret_cast<i32x4*>(lds + tile_off(row, g)) = r[i];
+  }
+}
+
+__device__ __forceinline__ bf16x8 cat4(bf16x4 a, bf16x4 b) {
+  bf16x8 v;
+  v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3];
+  v[4] = b[0]; v[5] = b[1]; v[6] = b[2]; v[7] = b[3];
+  return v;
+}
+
+// ------------------------------------------------------------------------------------ dQ
+constexpr int DQ_BR = 256;            // query rows per workgroup (4 wavefronts x 64)
+constexpr int DQ_BC = 32;             // keys per tile
+constexpr int DQ_TILE_BYTES = DQ_BC * 256;
+
+__global__ void __launch_bounds__(256, 1)
+burst_bwd_dq_kernel(BwdArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  // buffer b: K tile at (2b) * DQ_TILE_BYTES, V tile at (2b + 1) * DQ_TILE_BYTES
+  const int tid = threadIdx.x;
+  const int w = tid >> 6, lane = tid & 63, lr = lane & 31, h = lane >> 5;
+  int head, qb;
+  {
+    int bid = blockIdx.x;
+    int xcd = bid & 7, idx = bid >> 3;
+    int hx = idx / a.blocks_per_head;
+    qb = idx - hx * a.blocks_per_head;
+    head = hx * 8 + xcd;
+    if (head >= a.H) return;
+  }
+  const int q0 = qb * DQ_BR + w * 64;
+  const bf16* Qh = a.Q + (size_t)head * a.Nq * 128;
+  const bf16* Gh = a.dO + (size_t)head * a.Nq * 128;
+  const bf16* Kh = a.K + (size_t)head * a.Nc * 128;
+  const bf16* Vh = a.V + (size_t)head * a.Nc * 128;
+  const float* lseh = a.lse + (size_t)head * a.Nq;
+  const float* Dh = a.D + (size_t)head * a.Nq;
+  float* dQh = a.dQ + (size_t)head * a.Nq * 128;
+
+  int ntiles = (a.Nc + DQ_BC - 1) / DQ_BC;
+  if (a.causal) {
+    long long lim = a.q_off + min(qb * DQ_BR + DQ_BR, a.Nq) - 1 - a.k_off;
+    long long t = lim < 0 ? 0 : lim / DQ_BC + 1;
+    if (t < ntiles) ntiles = (int)t;
+  }
+
+  f32x16 dq[2][4];
+#pragma unroll
+  for (int rb = 0; rb < 2; rb++)
+#pragma unroll
+    for (int db = 0; db < 4; db++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) dq[rb][db][r] = 0.f;
+
+  if (ntiles > 0) {
+    bf16x8 qf[2][8], gf[2][8];
+    float lse2[2], Dv[2];
+#pragma unroll
+    for (int rb = 0; rb < 2; rb++) {
+      int row = q0 + rb * 32 + lr;
+      bool ok = row < a.Nq;
+      float lv = ok ? lseh[row] : BURST_NEG_INF;
+      lse2[rb] = (lv == BURST_NEG_INF) ? __builtin_inff() : lv * kLog2e;   // +inf => P = 0
+      Dv[rb] = ok ? Dh[row] : 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ks++) {
+        bf16x8 z;
+#pragma unroll
+        for (int t = 0; t < 8; t++) z[t] = (bf16)0.0f;
+        qf[rb][ks] = ok ? *reinterpret_cast<const bf16x8*>(Qh + (size_t)row * 128 + ks * 16 + h * 8) : z;
+        gf[rb][ks] = ok ? *reinterpret_cast<const bf16x8*>(Gh + (size_t)row * 128 + ks * 16 + h * 8) : z;
+      }
+    }
+    int kaddr[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) kaddr[ks] = tile_off(lr, 2 * ks + h);
+    int taddr[4][2];
+    {
+      const int j16 = lane & 15, dh = (lane >> 4) & 1;
+#pragma unroll
+      for (int db = 0; db < 4; db++)
+#pragma unroll
+        for (int sx = 0; sx < 2; sx++)
+          taddr[db][sx] = tile_off(8 * sx + 4 * h + (j16 >> 2), db * 4 + 2 * dh + ((j16 & 3) >> 1)) + (j16 & 1) * 8;
+    }
+    i32x4 kreg[2], vreg[2];
+    load_tile32_regs(Kh, 0, a.Nc, tid, kreg);
+    load_tile32_regs(Vh, 0, a.Nc, tid, vreg);
+    store_tile32_lds(smem, tid, kreg);
+    store_tile32_lds(smem + DQ_TILE_BYTES, tid, vreg);
+    if (ntiles > 1) {
+      load_tile32_regs(Kh, DQ_BC, a.Nc, tid, kreg);
+      load_tile32_regs(Vh, DQ_BC, a.Nc, tid, vreg);
+    }
+    __syncthreads();
+    const long long wave_first_q = a.q_off + q0, wave_last_q = a.q_off + q0 + 63;
+    for (int kt = 0; kt < ntiles; kt++) {
+      const int cur = kt & 1;
+      if (kt + 1 < ntiles) {
+        store_tile32_lds(smem + (cur ^ 1) * 2 * DQ_TILE_BYTES, tid, kreg);
+        store_tile32_lds(smem + ((cur ^ 1) * 2 + 1) * DQ_TILE_BYTES, tid, vreg);
+        if (kt + 2 < ntiles) {
+          load_tile32_regs(Kh, (kt + 2) * DQ_BC, a.Nc, tid, kreg);
+          load_tile32_regs(Vh, (kt + 2) * DQ_BC, a.Nc, tid, vreg);
+        }
+      }
+      const long long tile_first_k = a.k_off + (long long)kt * DQ_BC;
+      const bool wave_skips = (a.causal && tile_first_k > wave_last_q) || (q0 >= a.Nq);
+      if (!wave_skips) {
+        const char* kl = smem + cur * 2 * DQ_TILE_BYTES;
+        const char* vl = kl + DQ_TILE_BYTES;
+        f32x16 s[2], dp[2];
+#pragma unroll
+        for (int rb = 0; rb < 2; rb++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) { s[rb][r] = 0.f; dp[rb][r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) {
+          bf16x8 kf = lds_read_b128(kl, kaddr[ks]);
+          bf16x8 vf = lds_read_b128(vl, kaddr[ks]);
+#pragma unroll
+          for (int rb = 0; rb < 2; rb++) {
+            s[rb] = mfma32(kf, qf[rb][ks], s[rb]);
+            dp[rb] = mfma32(vf, gf[rb][ks], dp[rb]);
+          }
+        }
+        const bool need_mask = (a.causal && tile_first_k + DQ_BC - 1 > wave_first_q) ||
+                               ((kt + 1) * DQ_BC > a.Nc);
+        bf16x8 dsf[2][2];
+#pragma unroll
+        for (int rb = 0; rb < 2; rb++) {
+          long long qpos = a.q_off + q0 + rb * 32 + lr;
+          float ds[16];
+#pragma unroll
+          for (int r = 0; r < 16; r++) {
+            float p = fast_exp2(__builtin_fmaf(s[rb][r], a.c, -lse2[rb]));
+            if (need_mask) {
+              int kidx = kt * DQ_BC + 8 * (r >> 2) + 4 * h + (r & 3);
+              bool vis = (kidx < a.Nc) && (!a.causal || (a.k_off + kidx <= qpos));
+              if (!vis) p = 0.f;
+            }
+            ds[r] = p * (dp[rb][r] - Dv[rb]);
+          }
+#pragma unroll
+          for (int u = 0; u < 2; u++) {
+            bf16x8 f;
+#pragma unroll
+            for (int t = 0; t < 8; t++) f[t] = (bf16)ds[8 * u + t];
+            dsf[rb][u] = f;
+          }
+        }
+        // dQ^T += K^T dS^T  (A = K^T via transposing reads: rows = keys, cols = d)
+#pragma unroll
+        for (int kg = 0; kg < 2; kg++) {
+#pragma unroll
+          for (int db = 0; db < 4; db++) {
+            bf16x8 ktf = cat4(lds_read_tr(kl, kg * 16 * 256 + taddr[db][0]),
+                              lds_read_tr(kl, kg * 16 * 256 + taddr[db][1]));
+#pragma unroll
+            for (int rb = 0; rb < 2; rb++) dq[rb][db] = mfma32(ktf, dsf[rb][kg], dq[rb][db]);
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  // epilogue: dQ rows are owned by this wavefront alone
+#pragma unroll
+  for (int rb = 0; rb < 2; rb++) {
+    int row = q0 + rb * 32 + lr;
+    if (row < a.Nq) {
+      float* orow = dQh + (size_t)row * 128;
+#pragma unroll
+      for (int db = 0; db < 4; db++)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; q4++) {
+          float* ptr = orow + db * 32 + 8 * q4 + 4 * h;
+          f32x4 v = {0.f, 0.f, 0.f, 0.f};
+          if (a.acc_dq) v = *reinterpret_cast<f32x4*>(ptr);
+#pragma unroll
+          for (int b = 0; b < 4; b++) v[b] += a.scale * dq[rb][db][4 * q4 + b];
+          *reinterpret_cast<f32x4*>(ptr) = v;
+        }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------ dK, dV
+constexpr int DKV_BC = 256;           // keys per workgroup (4 wavefronts x 64)
+constexpr int DKV_BR = 32;            // query rows per tile
+constexpr int DKV_QTILE_BYTES = DKV_BR * 256;
+// LDS: V block (256 x 256 B) | Q tiles x2 | dO tiles x2 | lse2 x2 | D x2
+constexpr int DKV_LDS_V = 0;
+constexpr int DKV_LDS_Q = DKV_BC * 256;
+constexpr int DKV_LDS_G = DKV_LDS_Q + 2 * DKV_QTILE_BYTES;
+constexpr int DKV_LDS_L = DKV_LDS_G + 2 * DKV_QTILE_BYTES;
+constexpr int DKV_LDS_D = DKV_LDS_L + 2 * DKV_BR * 4;
+constexpr int DKV_LDS_BYTES = DKV_LDS_D + 2 * DKV_BR * 4;
+
+__global__ void __launch_bounds__(256, 1)
+burst_bwd_dkv_kernel(BwdArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int tid = threadIdx.x;
+  const int w = tid >> 6, lane = tid & 63, lr = lane & 31, h = lane >> 5;
+  int head, kblk;
+  {
+    int bid = blockIdx.x;
+    int xcd = bid & 7, idx = bid >> 3;
+    int hx = idx / a.blocks_per_head;
+    kblk = idx - hx * a.blocks_per_head;
+    head = hx * 8 + xcd;
+    if (head >= a.H) return;
+  }
+  const int key_wg = kblk * DKV_BC;
+  const int key0 = key_wg + w * 64;                // first key of this wavefront
+  const bf16* Qh = a.Q + (size_t)head * a.Nq * 128;
+  const bf16* Gh = a.dO + (size_t)head * a.Nq * 128;
+  const bf16* Kh = a.K + (size_t)head * a.Nc * 128;
+  const bf16* Vh = a.V + (size_t)head * a.Nc * 128;
+  const float* lseh = a.lse + (size_t)head * a.Nq;
+  const float* Dh = a.D + (size_t)head * a.Nq;
+
+  // query tiles to visit: causal rows before the first key of the workgroup see none of it
+  const int ntiles_all = (a.Nq + DKV_BR - 1) / DKV_BR;
+  int t_begin = 0;
+  if (a.causal) {
+    long long first_row = a.k_off + key_wg - a.q_off;      // first row index that sees key_wg
+    if (first_row > 0) t_begin = (int)min((long long)ntiles_all, first_row / DKV_BR);
+  }
+
+  f32x16 dk[2][4], dv[2][4];
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int db = 0; db < 4; db++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) { dk[kb][db][r] = 0.f; dv[kb][db][r] = 0.f; }
+
+  if (t_begin < ntiles_all) {
+    // K fragments (B operand of S = Q K^T): lane holds key lr of each 32-key block
+    bf16x8 kf[2][8];
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) {
+      int key = key0 + kb * 32 + lr;
+#pragma unroll
+      for (int ks = 0; ks < 8; ks++) {
+        bf16x8 z;
+#pragma unroll
+        for (int t = 0; t < 8; t++) z[t] = (bf16)0.0f;
+        kf[kb][ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Kh + (size_t)key * 128 + ks * 16 + h * 8) : z;
+      }
+    }
+    // V block of the workgroup -> LDS (16 granules x 256 rows = 4096 granules, 16 per thread)
+#pragma unroll
+    for (int i = 0; i < 16; i++) {
+      int gi = i * 256 + tid;
+      int row = gi >> 4, g = gi & 15;
+      i32x4 v = {0, 0, 0, 0};
+      if (key_wg + row < a.Nc) v = *reinterpret_cast<const i32x4*>(Vh + (size_t)(key_wg + row) * 128 + g * 8);
+      *reinterpret_cast<i32x4*>(smem + DKV_LDS_V + tile_off(row, g)) = v;
+    }
+    int vaddr[8];        // V as B operand: row = w*64 + kb*32 + lr, granule 2*ks + h
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) vaddr[ks] = DKV_LDS_V + tile_off(w * 64 + lr, 2 * ks + h);
+    int qaddr[8];        // Q / dO as A operand: row = lr, granule 2*ks + h
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) qaddr[ks] = tile_off(lr, 2 * ks + h);
+    int taddr[4][2];     // Q / dO as B operand through transposing reads (rows = q, cols = d)
+    {
+      const int j16 = lane & 15, dh = (lane >> 4) & 1;
+#pragma unroll
+      for (int db = 0; db < 4; db++)
+#pragma unroll
+        for (int sx = 0; sx < 2; sx++)
+          taddr[db][sx] = tile_off(8 * sx + 4 * h + (j16 >> 2), db * 4 + 2 * dh + ((j16 & 3) >> 1)) + (j16 & 1) * 8;
+    }
+
+    // lse2 (threads 0..31) and D (threads 32..63) of a tile travel with the Q / dO prefetch
+    auto load_rowstat = [&](int t) -> float {
+      float v = 0.f;
+      if (tid < 64) {
+        int row = t * DKV_BR + (tid & 31);
+        if (tid < 32) {
+          float lv = row < a.Nq ? lseh[row] : BURST_NEG_INF;
+          v = (lv == BURST_NEG_INF) ? __builtin_inff() : lv * kLog2e;      // +inf => P = 0
+        } else {
+          v = row < a.Nq ? Dh[row] : 0.f;
+        }
+      }
+      return v;
+    };
+    auto store_rowstat = [&](float v, int buf) {
+      if (tid < 32) reinterpret_cast<float*>(smem + DKV_LDS_L)[buf * DKV_BR + tid] = v;
+      else if (tid < 64) reinterpret_cast<float*>(smem + DKV_LDS_D)[buf * DKV_BR + tid - 32] = v;
+    };
+
+    i32x4 qreg[2], greg[2];
+    float rstat;
+    load_tile32_regs(Qh, t_begin * DKV_BR, a.Nq, tid, qreg);
+    load_tile32_regs(Gh, t_begin * DKV_BR, a.Nq, tid, greg);
+    rstat = load_rowstat(t_begin);
+    store_tile32_lds(smem + DKV_LDS_Q, tid, qreg);
+    store_tile32_lds(smem + DKV_LDS_G, tid, greg);
+    store_rowstat(rstat, 0);
+    if (t_begin + 1 < ntiles_all) {
+      load_tile32_regs(Qh, (t_begin + 1) * DKV_BR, a.Nq, tid, qreg);
+      load_tile32_regs(Gh, (t_begin + 1) * DKV_BR, a.Nq, tid, greg);
+      rstat = load_rowstat(t_begin + 1);
+    }
+    __syncthreads();
+
+    const long long wave_first_k = a.k_off + key0;
+    const long long wave_last_k = a.k_off + key0 + 63;
+    for (int t = t_begin; t < ntiles_all; t++) {
+      const int cur = (t - t_begin) & 1;
+      if (t + 1 < ntiles_all) {
+        store_tile32_lds(smem + DKV_LDS_Q + (cur ^ 1) * DKV_QTILE_BYTES, tid, qreg);
+        store_tile32_lds(smem + DKV_LDS_G + (cur ^ 1) * DKV_QTILE_BYTES, tid, greg);
+        store_rowstat(rstat, cur ^ 1);
+        if (t + 2 < ntiles_all) {
+          load_tile32_regs(Qh, (t + 2) * DKV_BR, a.Nq, tid, qreg);
+          load_tile32_regs(Gh, (t + 2) * DKV_BR, a.Nq, tid, greg);
+          rstat = load_rowstat(t + 2);
+        }
+      }
+      const long long tile_first_q = a.q_off + (long long)t * DKV_BR;
+      const long long tile_last_q = tile_first_q + DKV_BR - 1;
+      const bool wave_skips = (a.causal && wave_first_k > tile_last_q) || (key0 >= a.Nc);
+      if (!wave_skips) {
+        const char* ql = smem + DKV_LDS_Q + cur * DKV_QTILE_BYTES;
+        const char* gl = smem + DKV_LDS_G + cur * DKV_QTILE_BYTES;
+        f32x16 s[2], dp[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) { s[kb][r] = 0.f; dp[kb][r] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 8; ks++) {
+          bf16x8 qa = lds_read_b128(ql, qaddr[ks]);
+          bf16x8 ga = lds_read_b128(gl, qaddr[ks]);
+#pragma unroll
+          for (int kb = 0; kb < 2; kb++) {
+            bf16x8 vb = lds_read_b128(smem, kb * 32 * 256 + vaddr[ks]);
+            s[kb] = mfma32(qa, kf[kb][ks], s[kb]);
+            dp[kb] = mfma32(ga, vb, dp[kb]);
+          }
+        }
+        // per-register row statistics: row = 8*(r/4) + 4*h + (r%4)
+        float lse2v[16], Dvv[16];
+        {
+          const float* lp = reinterpret_cast<const float*>(smem + DKV_LDS_L) + cur * DKV_BR;
+          const float* dp_ = reinterpret_cast<const float*>(smem + DKV_LDS_D) + cur * DKV_BR;
+#pragma unroll
+          for (int q4 = 0; q4 < 4; q4++) {
+            f32x4 lv = *reinterpret_cast<const f32x4*>(lp + 8 * q4 + 4 * h);
+            f32x4 dv4 = *reinterpret_cast<const f32x4*>(dp_ + 8 * q4 + 4 * h);
+#pragma unroll
+            for (int b = 0; b < 4; b++) { lse2v[4 * q4 + b] = lv[b]; Dvv[4 * q4 + b] = dv4[b]; }
+          }
+        }
+        const bool need_mask = a.causal && (wave_last_k > tile_first_q);
+        bf16x8 pf[2][2], dsf[2][2];
+#pragma unroll
+        for (int kb = 0; kb < 2; kb++) {
+          long long kpos = a.k_off + key0 + kb * 32 + lr;
+          float pv[16], ds[16];
+#pragma unroll
+          for (int r = 0; r < 16; r++) {
+            float p = fast_exp2(__builtin_fmaf(s[kb][r], a.c, -lse2v[r]));
+            if (need_mask) {
+              long long qpos = tile_first_q + 8 * (r >> 2) + 4 * h + (r & 3);
+              if (kpos > qpos) p = 0.f;
+            }
+            pv[r] = p;
+            ds[r] = p * (dp[kb][r] - Dvv[r]);
+          }
+#pragma unroll
+          for (int u = 0; u < 2; u++) {
+            bf16x8 f, g;
+#pragma unroll
+            for (int t8 = 0; t8 < 8; t8++) { f[t8] = (bf16)pv[8 * u + t8]; g[t8] = (bf16)ds[8 * u + t8]; }
+            pf[kb][u] = f; dsf[kb][u] = g;
+          }
+        }
+        // dV += P^T dO ; dK += dS^T Q   (B operands through transposing reads)
+#pragma unroll
+        for (int u = 0; u < 2; u++) {
+#pragma unroll
+          for (int db = 0; db < 4; db++) {
+            bf16x8 gt = cat4(lds_read_tr(gl, u * 16 * 256 + taddr[db][0]),
+                             lds_read_tr(gl, u * 16 * 256 + taddr[db][1]));
+            bf16x8 qt = cat4(lds_read_tr(ql, u * 16 * 256 + taddr[db][0]),
+                             lds_read_tr(ql, u * 16 * 256 + taddr[db][1]));
+#pragma unroll
+            for (int kb = 0; kb < 2; kb++) {
+              dv[kb][db] = mfma32(pf[kb][u], gt, dv[kb][db]);
+              dk[kb][db] = mfma32(dsf[kb][u], qt, dk[kb][db]);
+            }
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  // epilogue: keys are owned by this wavefront alone. C layout: lane = d column, regs = keys.
+  float* dKh = a.dK + (size_t)head * a.Nc * 128;
+  float* dVh = a.dV + (size_t)head * a.Nc * 128;
+#pragma unroll
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+      int key = key0 + kb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+      if (key < a.Nc) {
+#pragma unroll
+        for (int db = 0; db < 4; db++) {
+          size_t off = (size_t)key * 128 + db * 32 + lr;
+          float k_old = 0.f, v_old = 0.f;
+          if (a.acc_dkv) { k_old = dKh[off]; v_old = dVh[off]; }
+          dKh[off] = k_old + a.scale * dk[kb][db][r];
+          dVh[off] = v_old + dv[kb][db][r];
+        }
+      }
+    }
+}
+
+static BwdArgs make_bwd_args(const KParams& p, const void* Q, const void* K, const void* V,
+                             const void* dO, const float* lse, const float* D,
+                             float* dQ, float* dK, float* dV, int acc_dq, int acc_dkv) {
+  BwdArgs a;
+  a.Q = (const bf16*)Q; a.K = (const bf16*)K; a.V = (const bf16*)V; a.dO = (const bf16*)dO;
+  a.lse = lse; a.D = D; a.dQ = dQ; a.dK = dK; a.dV = dV;
+  a.Nq = p.Nq; a.Nc = p.Nc; a.H = p.B * p.H;
+  a.causal = p.causal; a.c = p.scale * kLog2e; a.scale = p.scale;
+  a.q_off = p.q_off; a.k_off = p.k_off;
+  a.blocks_per_head = 0; a.acc_dq = acc_dq; a.acc_dkv = acc_dkv;
+  return a;
+}
+
+int launch_bwd_mfma(const KParams& p, const void* Q, const void* K, const void* V,
+                    const void* dO, const float* lse, const float* D,
+                    float* dQ, float* dK, float* dV, int acc_dq, int acc_dkv, hipStream_t stream) {
+  BwdArgs a = make_bwd_args(p, Q, K, V, dO, lse, D, dQ, dK, dV, acc_dq, acc_dkv);
+  int heads8 = ((a.H + 7) / 8) * 8;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            DKV_LDS_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
+    attr_set = true;
+  }
+  if (p.Nq > 0) {
+    a.blocks_per_head = (p.Nq + DQ_BR - 1) / DQ_BR;
+    long long nb = (long long)heads8 * a.blocks_per_head;
+    if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;
+    hipLaunchKernelGGL(burst_bwd_dq_kernel, dim3((unsigned)nb), dim3(256), 4 * DQ_TILE_BYTES, stream, a);
+  }
+  if (p.Nc > 0) {
+    a.blocks_per_head = (p.Nc + DKV_BC - 1) / DKV_BC;
+    long long nb = (long long)heads8 * a.blocks_per_head;
+    if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;
+    hipLaunchKernelGGL(burst_bwd_dkv_kernel, dim3((unsigned)nb), dim3(256), DKV_LDS_BYTES, stream, a);
+  }
+  return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+}
+
+}  // namespace burst

@@ -1,0 +1,86 @@
+// Shared device-side helpers for the gfx950 local-attention kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/burst.h"
+
+namespace burst {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+#define BURST_NEG_INF (-__builtin_inff())
+
+// Kernel-side copy of the call's parameters (plain data, passed by value).
+struct KParams {
+  int B, H, Nq, Nc, d;
+  int causal;
+  float scale;
+  long long q_off, k_off;
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Cross-half exchange.  v_permlane32_swap exchanges the upper 32 lanes of its first operand
+// with the lower 32 lanes of its second; fed the same value twice, every lane ends up with
+// (value of lane%32, value of lane%32 + 32).  The second operand goes through an opaque
+// register copy: the optimizer otherwise treats the swap of two identical values as the
+// identity and drops the combination of the two results.
+struct HalfPair { float lo, hi; };
+__device__ __forceinline__ HalfPair both_halves(float x) {
+  int a = __builtin_bit_cast(int, x);
+  int b;
+  asm volatile("v_mov_b32 %0, %1\n\ts_nop 1" : "=v"(b) : "v"(a));   // nop: VALU write -> permlane read
+  auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+  HalfPair p;
+  p.lo = __builtin_bit_cast(float, (int)r[0]);
+  p.hi = __builtin_bit_cast(float, (int)r[1]);
+  return p;
+}
+__device__ __forceinline__ float max_both_halves(float x) {
+  HalfPair p = both_halves(x);
+  return fmaxf(p.lo, p.hi);
+}
+__device__ __forceinline__ float sum_both_halves(float x) {
+  HalfPair p = both_halves(x);
+  return p.lo + p.hi;
+}
+
+// LDS tile layout for a [rows][128] bf16 tile: row pitch 256 B, the sixteen 16-byte
+// granules of a row are permuted by XOR with a 4-bit code of the row.  The code makes
+// both access patterns used by the MFMA operand loads bank-conflict free on gfx950:
+// 128-bit reads of one granule column over 32 consecutive rows, and transposing 64-bit
+// reads of 4 consecutive rows x 2 granules.
+__device__ __forceinline__ int row_code(int row) {
+  return ((row & 3) << 1) | ((row >> 2) & 1) | (row & 8);
+}
+__device__ __forceinline__ int tile_off(int row, int granule) {
+  return row * 256 + ((granule ^ row_code(row)) << 4);
+}
+
+__device__ __forceinline__ bf16x8 lds_read_b128(const char* lds, int byte_off) {
+  return *reinterpret_cast<const bf16x8*>(lds + byte_off);
+}
+// Transposing LDS read: within each group of 16 lanes, lane j supplies the address of 4
+// consecutive bf16 of matrix row (j/4), columns 4*(j%4)..+3; lane i receives column i of
+// rows 0..3.
+__device__ __forceinline__ bf16x4 lds_read_tr(const char* lds, int byte_off) {
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (lds_s16x4*)(__attribute__((address_space(3))) char*)(lds + byte_off));
+  return __builtin_bit_cast(bf16x4, v);
+}
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+}  // namespace burst
