@@ -104,14 +104,25 @@ int burst_bwd_prepare(const void* O, const void* dO, float* D, const burst_param
  * dQ [B,H,Nq,d], dK_chunk and dV_chunk [B,H,Nc,d], all fp32.
  * accumulate_dq / accumulate_dkv: 1 = add to what the buffer holds (the caller
  * zero-fills before the first block pair), 0 = the buffer is overwritten with
- * this block pair's contribution.  Floating-point accumulation order across
- * workgroups is not fixed (hardware fp32 atomics), so results may differ in the
- * last bits from run to run. */
+ * this block pair's contribution.  Every output row is owned by one wavefront
+ * (no atomics), so results are bitwise reproducible from run to run. */
 int burst_local_bwd(const void* Q, const void* K_chunk, const void* V_chunk,
                     const void* O, const void* dO, const float* lse, const float* D,
                     float* dQ, float* dK_chunk, float* dV_chunk,
                     int accumulate_dq, int accumulate_dkv,
                     const burst_params* p, void* stream);
+
+/* The two halves of burst_local_bwd on their own, for callers that need only one side
+ * (Alg. 2 with the query side travelling needs dQ_j from every device but dK_i, dV_i only
+ * locally) or that time them separately.  Same arguments and conventions as above; D must
+ * be given.  burst_local_bwd(D != NULL) is exactly _dq followed by _dkv. */
+int burst_local_bwd_dq(const void* Q, const void* K_chunk, const void* V_chunk,
+                       const void* dO, const float* lse, const float* D,
+                       float* dQ, int accumulate_dq, const burst_params* p, void* stream);
+int burst_local_bwd_dkv(const void* Q, const void* K_chunk, const void* V_chunk,
+                        const void* dO, const float* lse, const float* D,
+                        float* dK_chunk, float* dV_chunk, int accumulate_dkv,
+                        const burst_params* p, void* stream);
 
 /* Timing helper for harnesses that cannot create HIP events themselves:
  * records/queries events on the same stream the kernels are launched on.

@@ -16,7 +16,7 @@ BURST_BF16, BURST_F32 = 0, 1
 
 EXPORTS = [
     "burst_state_init", "burst_local_fwd", "burst_finalize", "burst_merge_state",
-    "burst_bwd_prepare", "burst_local_bwd", "burst_event_create", "burst_event_record",
+    "burst_bwd_prepare", "burst_local_bwd", "burst_local_bwd_dq", "burst_local_bwd_dkv", "burst_event_create", "burst_event_record",
     "burst_event_elapsed_ms", "burst_event_destroy", "burst_strerror", "burst_version",
 ]
 
@@ -54,7 +54,9 @@ def load():
     lib.burst_merge_state.argtypes = [fp, fp, fp, fp, fp, fp, pp, vp]
     lib.burst_bwd_prepare.argtypes = [vp, vp, fp, pp, vp]
     lib.burst_local_bwd.argtypes = [vp, vp, vp, vp, vp, fp, fp, fp, fp, fp, ctypes.c_int, ctypes.c_int, pp, vp]
-    for name in ("burst_state_init", "burst_local_fwd", "burst_finalize", "burst_merge_state",
+    lib.burst_local_bwd_dq.argtypes = [vp, vp, vp, vp, fp, fp, fp, ctypes.c_int, pp, vp]
+    lib.burst_local_bwd_dkv.argtypes = [vp, vp, vp, vp, fp, fp, fp, fp, ctypes.c_int, pp, vp]
+    for name in ("burst_local_bwd_dq", "burst_local_bwd_dkv", "burst_state_init", "burst_local_fwd", "burst_finalize", "burst_merge_state",
                  "burst_bwd_prepare", "burst_local_bwd", "burst_event_record", "burst_version"):
         getattr(lib, name).restype = ctypes.c_int
     lib.burst_event_create.argtypes = []
@@ -137,6 +139,18 @@ def burst_local_bwd(Q, K_chunk, V_chunk, O, dO, lse, D, dQ, dK_chunk, dV_chunk, 
                                   _f32(dQ), _f32(dK_chunk), _f32(dV_chunk),
                                   1 if accumulate_dq else 0, 1 if accumulate_dkv else 0,
                                   ctypes.byref(p), _stream()), "burst_local_bwd")
+
+
+def burst_local_bwd_dq(Q, K_chunk, V_chunk, dO, lse, D, dQ, p, accumulate_dq=True):
+    _check(load().burst_local_bwd_dq(_ptr(Q), _ptr(K_chunk), _ptr(V_chunk), _ptr(dO), _f32(lse), _f32(D),
+                                     _f32(dQ), 1 if accumulate_dq else 0, ctypes.byref(p), _stream()),
+           "burst_local_bwd_dq")
+
+
+def burst_local_bwd_dkv(Q, K_chunk, V_chunk, dO, lse, D, dK_chunk, dV_chunk, p, accumulate_dkv=False):
+    _check(load().burst_local_bwd_dkv(_ptr(Q), _ptr(K_chunk), _ptr(V_chunk), _ptr(dO), _f32(lse), _f32(D),
+                                      _f32(dK_chunk), _f32(dV_chunk), 1 if accumulate_dkv else 0,
+                                      ctypes.byref(p), _stream()), "burst_local_bwd_dkv")
 
 
 class Event:

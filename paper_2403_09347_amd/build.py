@@ -10,7 +10,7 @@ SOURCES = ["burst_api.hip", "burst_elementwise.hip", "burst_generic.hip",
            "burst_fwd_mfma.hip", "burst_bwd_mfma.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-ffast-math", "-fno-finite-math-only",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument"]
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1", "-Wno-unused-command-line-argument"]
 
 
 def build(verbose=True, jobs=5):

@@ -13,10 +13,14 @@ int launch_bwd_prepare(const KParams&, int, const void*, const void*, float*, hi
 int launch_zero_fill(float*, long long, hipStream_t);
 int launch_fwd_mfma(const KParams&, const void*, const void*, const void*, float*, float*, float*, hipStream_t);
 int launch_fwd_generic(const KParams&, int, const void*, const void*, const void*, float*, float*, float*, hipStream_t);
-int launch_bwd_mfma(const KParams&, const void*, const void*, const void*, const void*, const float*, const float*,
-                    float*, float*, float*, int, int, hipStream_t);
-int launch_bwd_generic(const KParams&, int, const void*, const void*, const void*, const void*, const float*,
-                       const float*, float*, float*, float*, int, int, hipStream_t);
+int launch_bwd_dq_mfma(const KParams&, const void*, const void*, const void*, const void*, const float*,
+                       const float*, float*, int, hipStream_t);
+int launch_bwd_dkv_mfma(const KParams&, const void*, const void*, const void*, const void*, const float*,
+                        const float*, float*, float*, int, hipStream_t);
+int launch_bwd_dq_generic(const KParams&, int, const void*, const void*, const void*, const void*, const float*,
+                          const float*, float*, int, hipStream_t);
+int launch_bwd_dkv_generic(const KParams&, int, const void*, const void*, const void*, const void*, const float*,
+                           const float*, float*, float*, int, hipStream_t);
 }  // namespace burst
 
 namespace {
@@ -144,27 +148,32 @@ int burst_bwd_prepare(const void* O, const void* dO, float* D, const burst_param
   return burst::launch_bwd_prepare(k, p->dtype, O, dO, D, (hipStream_t)stream);
 }
 
-int burst_local_bwd(const void* Q, const void* K_chunk, const void* V_chunk,
-                    const void* O, const void* dO, const float* lse, const float* D,
-                    float* dQ, float* dK_chunk, float* dV_chunk,
-                    int accumulate_dq, int accumulate_dkv,
-                    const burst_params* p, void* stream) {
+// Shared by the three backward entry points.  which: 1 = dQ, 2 = dK/dV, 3 = both.
+static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const void* V_chunk,
+                          const void* O, const void* dO, const float* lse, const float* D,
+                          float* dQ, float* dK_chunk, float* dV_chunk,
+                          int accumulate_dq, int accumulate_dkv,
+                          const burst_params* p, void* stream) {
   KParams k;
   int st = check_params(p, &k);
   if (st != BURST_OK) return st;
+  const bool want_dq = (which & 1) != 0, want_dkv = (which & 2) != 0;
   const long long bh = (long long)k.B * k.H;
   const bool have_q = bh * k.Nq > 0, have_k = bh * k.Nc > 0;
-  if (!have_q && !have_k) return BURST_OK;
-  if (have_q) { REQUIRE_PTR(Q); REQUIRE_PTR(dO); REQUIRE_PTR(lse); REQUIRE_PTR(dQ); }
-  if (have_k) { REQUIRE_PTR(K_chunk); REQUIRE_PTR(V_chunk); REQUIRE_PTR(dK_chunk); REQUIRE_PTR(dV_chunk); }
+  if (!(want_dq && have_q) && !(want_dkv && have_k)) return BURST_OK;
+  if (have_q) { REQUIRE_PTR(Q); REQUIRE_PTR(dO); REQUIRE_PTR(lse); }
+  if (have_k) { REQUIRE_PTR(K_chunk); REQUIRE_PTR(V_chunk); }
+  if (want_dq && have_q) REQUIRE_PTR(dQ);
+  if (want_dkv && have_k) { REQUIRE_PTR(dK_chunk); REQUIRE_PTR(dV_chunk); }
   if (D != nullptr && !aligned16(D)) return BURST_ERR_ALIGN;
-  if (D == nullptr && have_q) REQUIRE_PTR(O);
+  if (D == nullptr && have_q && have_k) REQUIRE_PTR(O);
   if ((st = check_arch()) != BURST_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   // Degenerate sides: nothing to contract over, the contribution is zero.
   if (!have_q || !have_k) {
-    if (have_q && !accumulate_dq && (st = burst::launch_zero_fill(dQ, bh * k.Nq * k.d, s)) != BURST_OK) return st;
-    if (have_k && !accumulate_dkv) {
+    if (want_dq && have_q && !accumulate_dq &&
+        (st = burst::launch_zero_fill(dQ, bh * k.Nq * k.d, s)) != BURST_OK) return st;
+    if (want_dkv && have_k && !accumulate_dkv) {
       if ((st = burst::launch_zero_fill(dK_chunk, bh * k.Nc * k.d, s)) != BURST_OK) return st;
       if ((st = burst::launch_zero_fill(dV_chunk, bh * k.Nc * k.d, s)) != BURST_OK) return st;
     }
@@ -177,11 +186,47 @@ int burst_local_bwd(const void* Q, const void* K_chunk, const void* V_chunk,
     if ((st = burst::launch_bwd_prepare(k, p->dtype, O, dO, scratch, s)) != BURST_OK) return st;
     Duse = scratch;
   }
-  if (use_mfma(p))
-    return burst::launch_bwd_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, dK_chunk, dV_chunk,
-                                  accumulate_dq != 0, accumulate_dkv != 0, s);
-  return burst::launch_bwd_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, dK_chunk, dV_chunk,
-                                   accumulate_dq != 0, accumulate_dkv != 0, s);
+  const bool mfma = use_mfma(p);
+  if (want_dq) {
+    st = mfma ? burst::launch_bwd_dq_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)
+              : burst::launch_bwd_dq_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dQ,
+                                             accumulate_dq != 0, s);
+    if (st != BURST_OK) return st;
+  }
+  if (want_dkv) {
+    st = mfma ? burst::launch_bwd_dkv_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk,
+                                           accumulate_dkv != 0, s)
+              : burst::launch_bwd_dkv_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk,
+                                              dV_chunk, accumulate_dkv != 0, s);
+    if (st != BURST_OK) return st;
+  }
+  return BURST_OK;
+}
+
+int burst_local_bwd(const void* Q, const void* K_chunk, const void* V_chunk,
+                    const void* O, const void* dO, const float* lse, const float* D,
+                    float* dQ, float* dK_chunk, float* dV_chunk,
+                    int accumulate_dq, int accumulate_dkv,
+                    const burst_params* p, void* stream) {
+  return local_bwd_impl(3, Q, K_chunk, V_chunk, O, dO, lse, D, dQ, dK_chunk, dV_chunk,
+                        accumulate_dq, accumulate_dkv, p, stream);
+}
+
+int burst_local_bwd_dq(const void* Q, const void* K_chunk, const void* V_chunk,
+                       const void* dO, const float* lse, const float* D,
+                       float* dQ, int accumulate_dq, const burst_params* p, void* stream) {
+  if (D == nullptr) return BURST_ERR_NULL;
+  return local_bwd_impl(1, Q, K_chunk, V_chunk, nullptr, dO, lse, D, dQ, nullptr, nullptr,
+                        accumulate_dq, 0, p, stream);
+}
+
+int burst_local_bwd_dkv(const void* Q, const void* K_chunk, const void* V_chunk,
+                        const void* dO, const float* lse, const float* D,
+                        float* dK_chunk, float* dV_chunk, int accumulate_dkv,
+                        const burst_params* p, void* stream) {
+  if (D == nullptr) return BURST_ERR_NULL;
+  return local_bwd_impl(2, Q, K_chunk, V_chunk, nullptr, dO, lse, D, nullptr, dK_chunk, dV_chunk,
+                        0, accumulate_dkv, p, stream);
 }
 
 void* burst_event_create(void) {

@@ -227,24 +227,30 @@ int launch_fwd_generic(const KParams& p, int dtype, const void* Q, const void* K
   return launch_status();
 }
 
-int launch_bwd_generic(const KParams& p, int dtype, const void* Q, const void* K, const void* V,
-                       const void* dO, const float* lse, const float* D,
-                       float* dQ, float* dK, float* dV, int acc_dq, int acc_dkv, hipStream_t s) {
+int launch_bwd_dq_generic(const KParams& p, int dtype, const void* Q, const void* K, const void* V,
+                          const void* dO, const float* lse, const float* D, float* dQ, int acc_dq, hipStream_t s) {
   GenArgs a = make_args(p);
-  a.Q = Q; a.K = K; a.V = V; a.dO = dO; a.lse = lse; a.D = D;
-  a.dQ = dQ; a.dK = dK; a.dV = dV; a.acc_dq = acc_dq; a.acc_dkv = acc_dkv;
-  long long wq = (long long)p.B * p.H * p.Nq, wk = (long long)p.B * p.H * p.Nc;
-  if ((wq + 3) / 4 > 0x7fffffffLL || (wk + 3) / 4 > 0x7fffffffLL) return BURST_ERR_SHAPE;
-  if (wq > 0) {
-    unsigned blocks = (unsigned)((wq + 3) / 4);
-    if (dtype == BURST_BF16) hipLaunchKernelGGL((bwd_dq_generic_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((bwd_dq_generic_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
-  }
-  if (wk > 0) {
-    unsigned blocks = (unsigned)((wk + 3) / 4);
-    if (dtype == BURST_BF16) hipLaunchKernelGGL((bwd_dkv_generic_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((bwd_dkv_generic_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
-  }
+  a.Q = Q; a.K = K; a.V = V; a.dO = dO; a.lse = lse; a.D = D; a.dQ = dQ; a.acc_dq = acc_dq;
+  long long wq = (long long)p.B * p.H * p.Nq;
+  if (wq == 0) return BURST_OK;
+  if ((wq + 3) / 4 > 0x7fffffffLL) return BURST_ERR_SHAPE;
+  unsigned blocks = (unsigned)((wq + 3) / 4);
+  if (dtype == BURST_BF16) hipLaunchKernelGGL((bwd_dq_generic_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((bwd_dq_generic_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
+  return launch_status();
+}
+
+int launch_bwd_dkv_generic(const KParams& p, int dtype, const void* Q, const void* K, const void* V,
+                           const void* dO, const float* lse, const float* D, float* dK, float* dV,
+                           int acc_dkv, hipStream_t s) {
+  GenArgs a = make_args(p);
+  a.Q = Q; a.K = K; a.V = V; a.dO = dO; a.lse = lse; a.D = D; a.dK = dK; a.dV = dV; a.acc_dkv = acc_dkv;
+  long long wk = (long long)p.B * p.H * p.Nc;
+  if (wk == 0) return BURST_OK;
+  if ((wk + 3) / 4 > 0x7fffffffLL) return BURST_ERR_SHAPE;
+  unsigned blocks = (unsigned)((wk + 3) / 4);
+  if (dtype == BURST_BF16) hipLaunchKernelGGL((bwd_dkv_generic_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((bwd_dkv_generic_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
   return launch_status();
 }
 
