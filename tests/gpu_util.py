@@ -1,0 +1,73 @@
+"""Helpers for the GPU parity tests: oracle references per head and tolerance checks."""
+import numpy as np
+import torch
+
+from oracle import burst_oracle as orc
+
+# Tolerances.  The benchmark statement fixes max-abs error <= 2e-2 for bf16 inputs with fp32
+# accumulation and <= 1e-4 for fp32.  For N(0,1) inputs at long sequence lengths outputs are
+# themselves ~1e-2, so an error relative to the largest reference entry is checked as well.
+TOL = {
+    "bf16": {"abs": 2e-2, "rel": 1e-2, "lse": 1e-2},
+    "f32": {"abs": 1e-4, "rel": 1e-5, "lse": 1e-5},
+}
+
+
+def f64(t):
+    return t.detach().double().cpu().numpy()
+
+
+def positions(case):
+    kp = np.concatenate([off + np.arange(k.shape[2]) for off, k in zip(case["k_offs"], case["K"])]) \
+        if case["K"] else np.zeros(0, np.int64)
+    return kp
+
+
+def head_inputs(case, b, h, rows=None):
+    Q, dO = f64(case["Q"][b, h]), f64(case["dO"][b, h])
+    d = Q.shape[1]
+    K = np.concatenate([f64(k[b, h]) for k in case["K"]]) if case["K"] else np.zeros((0, d))
+    V = np.concatenate([f64(v[b, h]) for v in case["V"]]) if case["V"] else np.zeros((0, d))
+    qp = case["q_off"] + np.arange(Q.shape[0])
+    if rows is not None:
+        Q, dO, qp = Q[rows], dO[rows], qp[rows]
+    return Q, K, V, dO, qp, positions(case)
+
+
+def check(name, got, ref, dtype, kind="abs"):
+    """Element-by-element comparison; -inf entries (lse of rows that saw nothing) must match exactly."""
+    tol = TOL[dtype]
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    assert got.shape == ref.shape, (name, got.shape, ref.shape)
+    fin = np.isfinite(ref)
+    assert np.array_equal(got[~fin], ref[~fin]), f"{name}: non-finite entries differ"
+    assert np.all(np.isfinite(got[fin])), f"{name}: non-finite value where the oracle is finite"
+    if not fin.any():
+        return 0.0
+    err = float(np.max(np.abs(got[fin] - ref[fin])))
+    if kind == "lse":
+        assert err <= tol["lse"], f"{name}: max-abs error {err:.3e} > {tol['lse']}"
+        return err
+    scale = float(np.max(np.abs(ref[fin])))
+    assert err <= tol["abs"], f"{name}: max-abs error {err:.3e} > {tol['abs']}"
+    assert err <= tol["rel"] * max(scale, 1e-30) + 1e-30 or scale == 0.0, \
+        f"{name}: max-abs error {err:.3e} > {tol['rel']} x max|ref| {scale:.3e}"
+    return err
+
+
+def compare_all_heads(case, dtype, O, lse, dQ=None, dKs=None, dVs=None, heads=None):
+    Bt, H = case["Q"].shape[:2]
+    for b in range(Bt):
+        for h in (range(H) if heads is None else heads):
+            Q, K, V, dO, qp, kp = head_inputs(case, b, h)
+            O_ref, lse_ref = orc.full_forward(Q, K, V, case["scale"], case["causal"], qp, kp)
+            check(f"O[{b},{h}]", f64(O[b, h]), O_ref, dtype)
+            check(f"lse[{b},{h}]", f64(lse[b, h]), lse_ref, dtype, "lse")
+            if dQ is not None:
+                dQ_ref, dK_ref, dV_ref = orc.full_backward(Q, K, V, dO, case["scale"], case["causal"], qp, kp)
+                check(f"dQ[{b},{h}]", f64(dQ[b, h]), dQ_ref, dtype)
+                d = Q.shape[1]
+                dK = np.concatenate([f64(x[b, h]) for x in dKs]) if dKs else np.zeros((0, d))
+                dV = np.concatenate([f64(x[b, h]) for x in dVs]) if dVs else np.zeros((0, d))
+                check(f"dK[{b},{h}]", dK, dK_ref, dtype)
+                check(f"dV[{b},{h}]", dV, dV_ref, dtype)

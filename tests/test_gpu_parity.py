@@ -1,0 +1,264 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import burst_oracle as orc
+from paper_2403_09347_amd import binding as B
+from paper_2403_09347_amd import workloads
+from paper_2403_09347_amd.harness import RingWalk
+from gpu_util import check, compare_all_heads, f64, head_inputs
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def run_case(case, dtype, backward=True, use_D=True, order=None):
+    walk = RingWalk(case["Q"], case["scale"], case["causal"], case["q_off"])
+    O, lse = walk.forward(case["K"], case["V"], case["k_offs"], order=order)
+    res = (O, lse, None, None, None)
+    if backward:
+        dQ, dKs, dVs = walk.backward(case["K"], case["V"], case["k_offs"], case["dO"], use_D=use_D)
+        res = (O, lse, dQ, dKs, dVs)
+    torch.cuda.synchronize()
+    return walk, res
+
+
+# MFMA path: sizes span several 256-row workgroups, 64-key tiles and ragged tails on both sides.
+BF16_CASES = [
+    dict(B=1, H=2, d=128, Nq=64, chunk_rows=[64]),
+    dict(B=1, H=3, d=128, Nq=300, chunk_rows=[200, 64, 331]),
+    dict(B=2, H=2, d=128, Nq=517, chunk_rows=[256, 1, 390]),
+    dict(B=1, H=9, d=128, Nq=256, chunk_rows=[512]),                       # more heads than XCDs
+    dict(B=1, H=2, d=128, Nq=300, chunk_rows=[256, 192], causal=True, q_off=148),
+    dict(B=1, H=2, d=128, Nq=384, chunk_rows=[128, 128, 128], causal=True, q_off=0),   # self-attention diagonal
+    dict(B=1, H=1, d=128, Nq=200, chunk_rows=[300, 300], causal=True, q_off=250),       # second chunk partly masked
+    dict(B=1, H=2, d=128, Nq=130, chunk_rows=[100, 260], causal=True, q_off=50,
+         k_offs=[0, 400]),                                                 # second chunk fully masked
+    dict(B=1, H=1, d=128, Nq=100, chunk_rows=[64, 64], causal=True, q_off=-30),         # rows that see nothing
+]
+
+
+@pytest.mark.parametrize("spec", BF16_CASES, ids=lambda s: "-".join(f"{k}{v}" for k, v in s.items() if k != "d"))
+def test_bf16_mfma_forward_backward(spec):
+    case = workloads.make_case(dtype="bf16", seed=17, device=DEV, **spec)
+    _, (O, lse, dQ, dKs, dVs) = run_case(case, "bf16")
+    compare_all_heads(case, "bf16", O, lse, dQ, dKs, dVs)
+
+
+def test_config0_tiny_fp32_complete():
+    w = workloads.WORKLOADS[0]
+    inp = workloads.make_inputs(w, DEV)
+    case = dict(inp, k_offs=[w.k_off(j) for j in range(w.G)], q_off=w.q_off, causal=w.causal, scale=w.scale)
+    _, (O, lse, dQ, dKs, dVs) = run_case(case, "f32")
+    compare_all_heads(case, "f32", O, lse, dQ, dKs, dVs)
+
+
+GENERIC_CASES = [
+    ("f32", dict(B=1, H=2, d=40, Nq=70, chunk_rows=[33, 50], causal=True, q_off=20)),
+    ("f32", dict(B=2, H=1, d=128, Nq=65, chunk_rows=[129])),
+    ("f32", dict(B=1, H=1, d=7, Nq=5, chunk_rows=[3, 1])),
+    ("bf16", dict(B=1, H=2, d=64, Nq=100, chunk_rows=[70, 90], causal=True, q_off=60)),
+    ("bf16", dict(B=1, H=1, d=96, Nq=33, chunk_rows=[64])),
+]
+
+
+@pytest.mark.parametrize("dtype,spec", GENERIC_CASES)
+def test_generic_kernels(dtype, spec):
+    case = workloads.make_case(dtype=dtype, seed=23, device=DEV, **spec)
+    _, (O, lse, dQ, dKs, dVs) = run_case(case, dtype)
+    compare_all_heads(case, dtype, O, lse, dQ, dKs, dVs)
+
+
+def test_g1_is_plain_attention():
+    """One device: no global merge is needed and the path is plain tiled attention (Sec. 2.4)."""
+    case = workloads.make_case(B=1, H=2, d=128, Nq=320, chunk_rows=[448], dtype="bf16", seed=5, device=DEV)
+    _, (O, lse, dQ, dKs, dVs) = run_case(case, "bf16")
+    compare_all_heads(case, "bf16", O, lse, dQ, dKs, dVs)
+
+
+# ------------------------------------------------------------------ the HBM-bound steps
+@pytest.mark.parametrize("d,dtype", [(128, "bf16"), (128, "f32"), (64, "f32"), (20, "f32"), (7, "bf16")])
+def test_state_init_finalize_merge_prepare(d, dtype):
+    g = torch.Generator(device=DEV).manual_seed(3)
+    Bt, H, Nq = 2, 3, 77
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    p = B.params(Bt, H, Nq, 0, d, tdt, 0.5)
+    O_acc = torch.full((Bt, H, Nq, d), 7.0, device=DEV)
+    m = torch.full((Bt, H, Nq), 3.0, device=DEV)
+    l = torch.full((Bt, H, Nq), 3.0, device=DEV)
+    B.burst_state_init(O_acc, m, l, p)
+    assert torch.all(O_acc == 0) and torch.all(l == 0) and torch.all(torch.isneginf(m))
+
+    def rand_state():
+        mm = torch.randn((Bt, H, Nq), generator=g, device=DEV) * 5
+        ll = torch.rand((Bt, H, Nq), generator=g, device=DEV) * 10 + 1.0
+        O = torch.randn((Bt, H, Nq, d), generator=g, device=DEV) * ll[..., None]   # O_acc / l ~ N(0,1)
+        dead = torch.rand((Bt, H, Nq), generator=g, device=DEV) < 0.2       # rows that saw nothing
+        O[dead] = 0
+        mm[dead] = float("-inf")
+        ll[dead] = 0
+        return O, mm, ll
+
+    Oa, ma, la = rand_state()
+    Ob, mb, lb = rand_state()
+    # finalize
+    O_out = torch.empty((Bt, H, Nq, d), device=DEV, dtype=tdt)
+    lse = torch.empty((Bt, H, Nq), device=DEV)
+    B.burst_finalize(Oa, ma, la, O_out, lse, p)
+    for b in range(Bt):
+        for h in range(H):
+            O_ref, lse_ref = orc.gao_finalize(f64(Oa[b, h]), f64(ma[b, h]), f64(la[b, h]))
+            check("finalize O", f64(O_out[b, h]), O_ref, dtype)
+            check("finalize lse", f64(lse[b, h]), lse_ref, dtype, "lse")
+    # merge (in place on a); compared through the observable quantities
+    refs = [[orc.gao_merge(f64(Oa[b, h]), f64(ma[b, h]), f64(la[b, h]), f64(Ob[b, h]), f64(mb[b, h]), f64(lb[b, h]))
+             for h in range(H)] for b in range(Bt)]
+    B.burst_merge_state(Oa, ma, la, Ob, mb, lb, p)
+    for b in range(Bt):
+        for h in range(H):
+            O_ref, m_ref, l_ref = refs[b][h]
+            check("merge m", f64(ma[b, h]), m_ref, "f32", "lse")
+            check("merge l", f64(la[b, h]), l_ref, "f32")
+            check("merge O", f64(Oa[b, h]), O_ref, "f32")
+    # D = rowsum(dO o O)
+    Ot = torch.randn((Bt, H, Nq, d), generator=g, device=DEV).to(tdt)
+    dOt = torch.randn((Bt, H, Nq, d), generator=g, device=DEV).to(tdt)
+    D = torch.empty((Bt, H, Nq), device=DEV)
+    B.burst_bwd_prepare(Ot, dOt, D, p)
+    for b in range(Bt):
+        for h in range(H):
+            check("D", f64(D[b, h]), orc.gao_bwd_prepare(f64(Ot[b, h]), f64(dOt[b, h])), "f32")
+
+
+# ------------------------------------------------------------------ properties of the state machine
+def test_empty_and_fully_masked_chunks_leave_the_state_bit_for_bit():
+    case = workloads.make_case(B=1, H=2, d=128, Nq=200, chunk_rows=[192, 100], dtype="bf16", seed=9, device=DEV,
+                               causal=True, q_off=100)
+    walk = RingWalk(case["Q"], case["scale"], True, case["q_off"])
+    walk.init()
+    walk.step(case["K"][0], case["V"][0], 0)
+    snap = [t.clone() for t in (walk.O_acc, walk.m, walk.l)]
+    empty = torch.empty((1, 2, 0, 128), device=DEV, dtype=torch.bfloat16)
+    walk.step(empty, empty, 50)                                  # Nc = 0
+    walk.step(case["K"][1], case["V"][1], 10_000)                # every key lies after every query
+    torch.cuda.synchronize()
+    for a, b in zip(snap, (walk.O_acc, walk.m, walk.l)):
+        assert torch.equal(a, b)
+    # and into a fresh state: it stays fresh
+    walk.init()
+    walk.step(case["K"][1], case["V"][1], 10_000)
+    torch.cuda.synchronize()
+    assert torch.all(walk.O_acc == 0) and torch.all(walk.l == 0) and torch.all(torch.isneginf(walk.m))
+    O, lse = walk.finalize()
+    torch.cuda.synchronize()
+    assert torch.all(O == 0) and torch.all(torch.isneginf(lse))
+
+
+def test_chunk_order_and_split_merge():
+    case = workloads.make_case(B=1, H=2, d=128, Nq=300, chunk_rows=[128, 200, 64, 150], dtype="bf16", seed=31, device=DEV)
+    w0, (O0, lse0, *_r) = run_case(case, "bf16", backward=False)
+    O0, lse0 = O0.clone(), lse0.clone()
+    for order in ([3, 2, 1, 0], [2, 3, 0, 1]):
+        _, (O1, lse1, *_r) = run_case(case, "bf16", backward=False, order=order)
+        compare_all_heads(case, "bf16", O1, lse1)
+        assert float((lse1 - lse0).abs().max()) < 1e-5
+    # two half walks from fresh states, merged, equal the straight walk
+    wa = RingWalk(case["Q"], case["scale"])
+    wb = RingWalk(case["Q"], case["scale"])
+    wa.init(); wb.init()
+    for j in (0, 1):
+        wa.step(case["K"][j], case["V"][j], case["k_offs"][j])
+    for j in (2, 3):
+        wb.step(case["K"][j], case["V"][j], case["k_offs"][j])
+    B.burst_merge_state(wa.O_acc, wa.m, wa.l, wb.O_acc, wb.m, wb.l, wa.params(0, 0))
+    O2, lse2 = wa.finalize()
+    torch.cuda.synchronize()
+    compare_all_heads(case, "bf16", O2, lse2)
+    assert float((lse2 - lse0).abs().max()) < 1e-5
+
+
+def test_checkpoint_resume_and_determinism_are_bitwise():
+    case = workloads.make_case(B=1, H=3, d=128, Nq=260, chunk_rows=[100, 130, 90], dtype="bf16", seed=41, device=DEV,
+                               causal=True, q_off=60)
+    _, (O0, lse0, dQ0, dKs0, dVs0) = run_case(case, "bf16")
+    keep = [t.clone() for t in (O0, lse0, dQ0, *dKs0, *dVs0)]
+    # same call sequence again: every output bit-identical (no atomics anywhere)
+    _, (O1, lse1, dQ1, dKs1, dVs1) = run_case(case, "bf16")
+    for a, b in zip(keep, (O1, lse1, dQ1, *dKs1, *dVs1)):
+        assert torch.equal(a, b)
+    # stop after chunk 0, move the state through host memory into new buffers, continue
+    w1 = RingWalk(case["Q"], case["scale"], True, case["q_off"])
+    w1.init()
+    w1.step(case["K"][0], case["V"][0], case["k_offs"][0])
+    saved = [t.cpu() for t in (w1.O_acc, w1.m, w1.l)]
+    w2 = RingWalk(case["Q"], case["scale"], True, case["q_off"])
+    for dst, src in zip((w2.O_acc, w2.m, w2.l), saved):
+        dst.copy_(src)
+    for j in (1, 2):
+        w2.step(case["K"][j], case["V"][j], case["k_offs"][j])
+    O2, lse2 = w2.finalize()
+    torch.cuda.synchronize()
+    assert torch.equal(O2, keep[0]) and torch.equal(lse2, keep[1])
+
+
+def test_backward_without_D_and_accumulate_flags():
+    case = workloads.make_case(B=1, H=2, d=128, Nq=200, chunk_rows=[150, 170], dtype="bf16", seed=51, device=DEV)
+    walk, (O, lse, dQ, dKs, dVs) = run_case(case, "bf16", use_D=True)
+    dQ, dKs, dVs = dQ.clone(), [t.clone() for t in dKs], [t.clone() for t in dVs]
+    dQ2, dKs2, dVs2 = walk.backward(case["K"], case["V"], case["k_offs"], case["dO"], use_D=False)
+    torch.cuda.synchronize()
+    assert torch.equal(dQ, dQ2)
+    for a, b in zip(dKs + dVs, dKs2 + dVs2):
+        assert torch.equal(a, b)
+    # accumulate_dq = 0 overwrites whatever the buffer held; accumulate_dkv = 1 adds to it
+    junk = torch.full_like(dQ, 123.0)
+    p = walk.params(150, 0)
+    B.burst_local_bwd(case["Q"], case["K"][0], case["V"][0], walk.O, case["dO"], walk.lse, walk.D,
+                      junk, dKs2[0], dVs2[0], p, accumulate_dq=False, accumulate_dkv=True)
+    torch.cuda.synchronize()
+    only0 = torch.zeros_like(dQ)
+    dk_tmp, dv_tmp = torch.empty_like(dKs[0]), torch.empty_like(dVs[0])
+    B.burst_local_bwd(case["Q"], case["K"][0], case["V"][0], walk.O, case["dO"], walk.lse, walk.D,
+                      only0, dk_tmp, dv_tmp, p, accumulate_dq=True, accumulate_dkv=False)
+    torch.cuda.synchronize()
+    assert torch.equal(junk, only0)
+    assert torch.allclose(dKs2[0], 2 * dKs[0], rtol=1e-6, atol=1e-7)
+    assert torch.allclose(dVs2[0], 2 * dVs[0], rtol=1e-6, atol=1e-7)
+
+
+def test_key_side_pinned_orientation():
+    """Alg. 2 as printed: K_i, V_i pinned, query slices (Q_j, dO_j, D_j, lse_j) visit; dK_i, dV_i accumulate."""
+    spec = dict(B=1, H=2, d=128, dtype="bf16", seed=61, device=DEV)
+    full = workloads.make_case(Nq=384, chunk_rows=[200], **spec)
+    walk, (O, lse, dQ, dKs, dVs) = run_case(full, "bf16")
+    dK = torch.zeros_like(dKs[0]); dV = torch.zeros_like(dVs[0])
+    dQ_parts = []
+    for s0, s1 in ((0, 128), (128, 384)):
+        sl = lambda t: t[:, :, s0:s1].contiguous()
+        Qj, dOj, Oj, lsej, Dj = sl(full["Q"]), sl(full["dO"]), sl(walk.O), sl(walk.lse), sl(walk.D)
+        dQj = torch.zeros((1, 2, s1 - s0, 128), device=DEV)
+        p = B.params(1, 2, s1 - s0, 200, 128, torch.bfloat16, full["scale"], False, s0, 0)
+        B.burst_local_bwd(Qj, full["K"][0], full["V"][0], Oj, dOj, lsej, Dj, dQj, dK, dV, p,
+                          accumulate_dq=True, accumulate_dkv=True)
+        dQ_parts.append(dQj)
+    torch.cuda.synchronize()
+    assert torch.equal(torch.cat(dQ_parts, dim=2), dQ)
+    assert torch.allclose(dK, dKs[0], rtol=1e-5, atol=1e-6) and torch.allclose(dV, dVs[0], rtol=1e-5, atol=1e-6)
+    compare_all_heads(full, "bf16", O, lse, torch.cat(dQ_parts, dim=2), [dK], [dV])
+
+
+def test_error_codes_on_device_buffers():
+    x = torch.zeros(4096, device=DEV)
+    p = B.params(1, 1, 16, 16, 128, torch.bfloat16, 0.5)
+    with pytest.raises(B.BurstError) as e:
+        B.burst_state_init(x[1:], x, x, p)                       # 4-byte offset: misaligned
+    assert e.value.code == -2
+    with pytest.raises(B.BurstError) as e:
+        B.burst_local_fwd(None, x, x, x, x, x, p)
+    assert e.value.code == -1
+    bad = B.params(1, 1, 16, 16, 129, torch.bfloat16, 0.5)
+    with pytest.raises(B.BurstError) as e:
+        B.burst_state_init(x, x, x, bad)
+    assert e.value.code == -3
+    assert torch.all(x == 0)                                     # nothing was written
