@@ -1,0 +1,118 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The oracle cannot evaluate these shapes completely in reasonable time, so it computes
+(i) complete heads where a head fits (forward + backward, every output element), and
+(ii) sampled query rows on other heads: O, lse and dQ of a row depend only on that row of Q
+and dO, so the oracle evaluates them one by one over the full key range.  dK / dV of the
+largest shapes are additionally pinned by two identities that hold at any size:
+sum_c dV_c = sum_r dO_r (columns of P sum to one per row) and <Q, dQ> = <K, dK>.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import burst_oracle as orc
+from paper_2403_09347_amd import workloads
+from paper_2403_09347_amd.harness import RingWalk
+from gpu_util import check, f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def run_workload(w, backward=True):
+    inp = workloads.make_inputs(w, DEV)
+    k_offs = [w.k_off(j) for j in range(w.G)]
+    walk = RingWalk(inp["Q"], w.scale, w.causal, w.q_off)
+    O, lse = walk.forward(inp["K"], inp["V"], k_offs)
+    dQ = dKs = dVs = None
+    if backward:
+        # one (dK, dV) pair per chunk is kept only where it is checked; others reuse a scratch pair
+        dQ, dKs, dVs = walk.backward(inp["K"], inp["V"], k_offs, inp["dO"])
+    torch.cuda.synchronize()
+    return inp, k_offs, walk, O, lse, dQ, dKs, dVs
+
+
+def head_arrays(inp, h):
+    K = np.concatenate([f64(k[0, h]) for k in inp["K"]])
+    V = np.concatenate([f64(v[0, h]) for v in inp["V"]])
+    return f64(inp["Q"][0, h]), K, V, f64(inp["dO"][0, h])
+
+
+def check_complete_head(w, inp, h, O, lse, dQ, dKs, dVs):
+    Q, K, V, dO = head_arrays(inp, h)
+    qp, kp = w.q_off + np.arange(w.Nq), np.arange(K.shape[0])
+    O_ref, lse_ref = orc.full_forward(Q, K, V, w.scale, w.causal, qp, kp)
+    check(f"O[h{h}]", f64(O[0, h]), O_ref, w.dtype)
+    check(f"lse[h{h}]", f64(lse[0, h]), lse_ref, w.dtype, "lse")
+    dQ_ref, dK_ref, dV_ref = orc.full_backward(Q, K, V, dO, w.scale, w.causal, qp, kp)
+    check(f"dQ[h{h}]", f64(dQ[0, h]), dQ_ref, w.dtype)
+    check(f"dK[h{h}]", np.concatenate([f64(x[0, h]) for x in dKs]), dK_ref, w.dtype)
+    check(f"dV[h{h}]", np.concatenate([f64(x[0, h]) for x in dVs]), dV_ref, w.dtype)
+
+
+def check_sampled_rows(w, inp, h, O, lse, dQ, n_rows=64, seed=0):
+    Q, K, V, dO = head_arrays(inp, h)
+    rows = np.sort(np.random.default_rng(seed + h).choice(w.Nq, size=n_rows, replace=False))
+    rows[0], rows[-1] = 0, w.Nq - 1                      # always include the first and last row
+    qp, kp = w.q_off + rows, np.arange(K.shape[0])
+    O_ref, lse_ref = orc.full_forward(Q[rows], K, V, w.scale, w.causal, qp, kp)
+    check(f"O[h{h},rows]", f64(O[0, h])[rows], O_ref, w.dtype)
+    check(f"lse[h{h},rows]", f64(lse[0, h])[rows], lse_ref, w.dtype, "lse")
+    if dQ is not None:
+        dQ_ref, _, _ = orc.full_backward(Q[rows], K, V, dO[rows], w.scale, w.causal, qp, kp)
+        check(f"dQ[h{h},rows]", f64(dQ[0, h])[rows], dQ_ref, w.dtype)
+
+
+def check_identities(w, inp, h, dQ, dKs, dVs):
+    Q, K, V, dO = head_arrays(inp, h)
+    dV_sum = sum(f64(x[0, h]).sum(axis=0) for x in dVs)
+    dO_sum = dO.sum(axis=0)
+    # every query row of these workloads sees at least one key, so each row of P sums to one
+    assert np.max(np.abs(dV_sum - dO_sum)) <= 2e-2 * max(1.0, np.max(np.abs(dO_sum)))
+    qdq = float((Q * f64(dQ[0, h])).sum())
+    kdk = float(sum((f64(k[0, h]) * f64(dk[0, h])).sum() for k, dk in zip(inp["K"], dKs)))
+    scale = float(np.abs(Q * f64(dQ[0, h])).sum())
+    assert abs(qdq - kdk) <= 1e-2 * scale, (qdq, kdk, scale)
+
+
+def test_llama7b_32k_G8_two_complete_heads_and_sampled_rows():
+    w = workloads.by_name("llama7b_32k_G8")
+    inp, k_offs, walk, O, lse, dQ, dKs, dVs = run_workload(w)
+    for h in (0, w.H - 1):
+        check_complete_head(w, inp, h, O, lse, dQ, dKs, dVs)
+    for h in (1, 7, 8, 15, 16, 30):
+        check_sampled_rows(w, inp, h, O, lse, dQ)
+    for h in (3, 12):
+        check_identities(w, inp, h, dQ, dKs, dVs)
+
+
+def test_llama7b_128k_rank31_causal_complete_head_and_sampled_rows():
+    w = workloads.by_name("llama7b_128k_G32_rank31_causal")
+    inp, k_offs, walk, O, lse, dQ, dKs, dVs = run_workload(w)
+    check_complete_head(w, inp, w.H - 1, O, lse, dQ, dKs, dVs)
+    for h in (0, 9, 17):
+        check_sampled_rows(w, inp, h, O, lse, dQ)
+    check_identities(w, inp, 5, dQ, dKs, dVs)
+
+
+def test_llama13b_128k_G8_sampled_rows_and_identities():
+    w = workloads.by_name("llama13b_128k_G8")
+    inp, k_offs, walk, O, lse, dQ, dKs, dVs = run_workload(w)
+    for h in (0, 21, w.H - 1):
+        check_sampled_rows(w, inp, h, O, lse, dQ)
+    for h in (0, w.H - 1):
+        check_identities(w, inp, h, dQ, dKs, dVs)
+    # dK / dV element by element on a reduced query slice of the same shape class:
+    # the first 256 query rows against all 128K keys, complete oracle on one head
+    small = workloads.Workload("llama13b_128k_G8_nq256", 1, 2, 128, 256, w.G, w.Nc, "bf16", False, 0, 2003)
+    inp, k_offs, walk, O, lse, dQ, dKs, dVs = run_workload(small)
+    check_complete_head(small, inp, 1, O, lse, dQ, dKs, dVs)
+
+
+def test_llama7b_1m_G32_streaming_sampled_rows_and_identities():
+    w = workloads.by_name("llama7b_1m_G32")
+    inp, k_offs, walk, O, lse, dQ, dKs, dVs = run_workload(w)
+    for h in (0, w.H - 1):
+        check_sampled_rows(w, inp, h, O, lse, dQ, n_rows=32)
+    check_identities(w, inp, 0, dQ, dKs, dVs)
