@@ -79,6 +79,50 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const char* lds, int byte_off) {
   return __builtin_bit_cast(bf16x4, v);
 }
 
+// Raw buffer access: loads beyond `bytes` return 0 without touching memory, so ragged tile
+// tails and prefetches past the end need no branch.  The whole offset goes into the VGPR
+// operand (the range check covers it).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ i32x4 buffer_load_b128(__amdgpu_buffer_rsrc_t rsrc, int byte_off) {
+  return __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0));
+}
+
+// HBM -> LDS DMA: one wave-wide 128-bit buffer load with the LDS modifier.  Lane i's 16
+// bytes land at lds_base + 16*i (lds_base wave-uniform, passed through M0); offsets beyond
+// the buffer's size write zeros.  Issued as inline assembly on purpose: the compiler then
+// does not treat it as an LDS store that every later LDS read must wait for (it would drain
+// the whole memory queue before each read).  Ordering against the readers is the caller's
+// job: s_waitcnt vmcnt(n) followed by a workgroup barrier.
+__device__ __forceinline__ void dma_b128_to_lds(__amdgpu_buffer_rsrc_t rsrc, unsigned lds_base, int voffset) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :: "s"(lds_base), "v"(voffset), "s"(rsrc) : "memory", "m0");
+}
+// LDS byte address of a pointer into the workgroup's dynamic shared memory.
+__device__ __forceinline__ unsigned lds_addr(const void* p) {
+  return (unsigned)(size_t)(__attribute__((address_space(3))) const char*)(const char*)p;
+}
+
+// MFMA with the accumulator pinned to accumulation registers (AGPRs).  Used for the long-lived
+// output accumulators so that the register allocator can never move them through VGPRs.
+// As inline assembly the instruction is invisible to the compiler's hazard recognizer:
+//  - a VGPR written by a vector instruction must not be read by an MFMA in the next two
+//    cycles: the leading s_nop covers the operand copies the compiler may place right before;
+//  - the accumulator must not be touched by other instructions until the MFMA has drained:
+//    callers go through mfma_acc_fence() before reading or rewriting it.
+__device__ __forceinline__ void mfma32_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
+  asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// Waits until every MFMA issued so far has written its accumulator (an MFMA takes at most
+// 16 passes of 4 cycles; 3 x 16 idle cycles cover it with margin) and orders the listed
+// accumulators after it.
+__device__ __forceinline__ void mfma_acc_fence(f32x16 (&acc)[2][4]) {
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15"
+               : "+a"(acc[0][0]), "+a"(acc[0][1]), "+a"(acc[0][2]), "+a"(acc[0][3]),
+                 "+a"(acc[1][0]), "+a"(acc[1][1]), "+a"(acc[1][2]), "+a"(acc[1][3]));
+}
+
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }

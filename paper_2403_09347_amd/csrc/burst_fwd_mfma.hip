@@ -8,6 +8,12 @@
 //               one cross-half exchange; running max, sum and O rescale stay in registers
 //   O^T tile += V_tile^T P^T         (A = V^T through transposing LDS reads, B = P from the
 //               S^T accumulators, which already have the B-operand layout)
+// The wavefront runs at one wave per SIMD (512 registers), so matrix and vector work overlap
+// inside the wave: the loop is software-pipelined, the S^T MFMAs of tile j+1 are issued
+// together with the exp / sum / convert of tile j.  K and V tiles are DMA-ed from HBM straight
+// into LDS (buffer loads with the LDS modifier, no staging registers) into two rings of three
+// tiles each, two tiles ahead of their use (one barrier per tile).  The running max is only raised when a row's new maximum exceeds
+// it by more than 2^8 (P stays <= 2^8, exact in fp32/bf16 range), so the O rescale is rare.
 // The chunk-local (O_ij, m_ij, l_ij) is merged into the state in HBM in the epilogue
 // (Alg. 1: m_new = max, rescale, add).  No S or P tile ever leaves registers.
 #include "burst_common.h"
@@ -17,6 +23,8 @@ namespace burst {
 constexpr int FWD_BR = 256;   // query rows per workgroup
 constexpr int FWD_BC = 64;    // keys per tile
 constexpr int FWD_TILE_BYTES = FWD_BC * 256;
+constexpr int FWD_NBUF = 3;
+constexpr float FWD_LAZY = 8.0f;   // log2 of the largest P allowed before the max is raised
 
 struct FwdArgs {
   const bf16* Q; const bf16* K; const bf16* V;
@@ -28,32 +36,46 @@ struct FwdArgs {
   int q_blocks;          // ceil(Nq / FWD_BR)
 };
 
-// Global -> registers for one 64x128 bf16 tile (K or V): 4 granules of 16 B per thread.
-__device__ __forceinline__ void load_tile_regs(const bf16* __restrict__ base, int row0, int nrows,
-                                               int tid, i32x4 (&r)[4]) {
+// HBM -> LDS for one 64x128 bf16 tile (K or V) without staging registers.  One wave-wide
+// load writes 1024 contiguous LDS bytes (4 tile rows), lane i filling the 16 bytes at i*16;
+// which global granule a lane fetches is free, so lane i asks for the granule that the XOR
+// layout places at its slot.  Each wavefront issues 4 such loads per tile (16 rows).
+// goff[il] is the lane's byte offset inside the tile for load il.
+__device__ __forceinline__ void tile_dma_offsets(int w, int lane, int (&goff)[4]) {
 #pragma unroll
-  for (int i = 0; i < 4; i++) {
-    int gi = i * 256 + tid;
-    int row = gi >> 4, g = gi & 15;
-    i32x4 v = {0, 0, 0, 0};
-    if (row0 + row < nrows)
-      v = *reinterpret_cast<const i32x4*>(base + (size_t)(row0 + row) * 128 + g * 8);
-    r[i] = v;
+  for (int il = 0; il < 4; il++) {
+    int row = 16 * w + 4 * il + (lane >> 4);
+    goff[il] = row * 256 + (((lane & 15) ^ row_code(row)) << 4);
   }
 }
-__device__ __forceinline__ void store_tile_lds(char* lds, int tid, const i32x4 (&r)[4]) {
+__device__ __forceinline__ void tile_dma(__amdgpu_buffer_rsrc_t rsrc, unsigned lds_tile, int w_uniform, int il,
+                                         int voffset) {
+  dma_b128_to_lds(rsrc, lds_tile + (unsigned)(w_uniform * 4 + il) * 1024u, voffset);
+}
+
+// S^T (64 keys x 64 rows) = K_tile Q^T into s[key block][row block].
+__device__ __forceinline__ void qk_tile(const char* kl, const int (&kaddr)[8], const bf16x8 (&qf)[2][8],
+                                        f32x16 (&s)[2][2]) {
 #pragma unroll
-  for (int i = 0; i < 4; i++) {
-    int gi = i * 256 + tid;
-    int row = gi >> 4, g = gi & 15;
-    *reinterpret_cast<i32x4*>(lds + tile_off(row, g)) = r[i];
+  for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+    for (int rb = 0; rb < 2; rb++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) s[kb][rb][r] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 8; ks++) {
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++) {
+      bf16x8 kf = lds_read_b128(kl, kb * 32 * 256 + kaddr[ks]);
+#pragma unroll
+      for (int rb = 0; rb < 2; rb++) s[kb][rb] = mfma32(kf, qf[rb][ks], s[kb][rb]);
+    }
   }
 }
 
 __global__ void __launch_bounds__(256, 1)
 burst_fwd_mfma_kernel(FwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  // buffer b: K tile at (2b) * FWD_TILE_BYTES, V tile at (2b + 1) * FWD_TILE_BYTES
 
   const int tid = threadIdx.x;
   const int w = tid >> 6, lane = tid & 63, lr = lane & 31, h = lane >> 5;
@@ -110,7 +132,7 @@ burst_fwd_mfma_kernel(FwdArgs a) {
     for (int db = 0; db < 4; db++)
 #pragma unroll
       for (int r = 0; r < 16; r++) o[rb][db][r] = 0.f;
-  float m2[2] = {BURST_NEG_INF, BURST_NEG_INF};   // running max, log2 units, per row block
+  float m2[2] = {BURST_NEG_INF, BURST_NEG_INF};   // reference max, log2 units, per row block
   float lsum[2] = {0.f, 0.f};                     // running sum over this lane's keys only
 
   // per-lane LDS byte offsets; tile-relative constants are added at the use site
@@ -130,124 +152,222 @@ burst_fwd_mfma_kernel(FwdArgs a) {
         vaddr[db][sx] = tile_off(8 * sx + 4 * h + (j16 >> 2), db * 4 + 2 * dh + ((j16 & 3) >> 1)) + (j16 & 1) * 8;
   }
 
-  i32x4 kreg[4], vreg[4];
-  load_tile_regs(Kh, 0, a.Nc, tid, kreg);
-  load_tile_regs(Vh, 0, a.Nc, tid, vreg);
-  store_tile_lds(smem, tid, kreg);
-  store_tile_lds(smem + FWD_TILE_BYTES, tid, vreg);
-  if (ntiles > 1) {
-    load_tile_regs(Kh, FWD_BC, a.Nc, tid, kreg);
-    load_tile_regs(Vh, FWD_BC, a.Nc, tid, vreg);
+  // ---- prologue: K tiles 0..2 and V tiles 0..1 into LDS, S of tile 0.
+  // LDS: K ring = tiles 0..2 of the buffer, V ring = tiles 3..5; tile t lives in slot t % 3.
+  // Tiles past the end of the chunk read as zeros (buffer range check) and are never used.
+  const __amdgpu_buffer_rsrc_t krs = make_rsrc(Kh, (unsigned)a.Nc * 256u);
+  const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, (unsigned)a.Nc * 256u);
+  const int wu = __builtin_amdgcn_readfirstlane(w);
+  const unsigned lds0 = lds_addr(smem);
+  int goff[4];
+  tile_dma_offsets(w, lane, goff);
+#pragma unroll
+  for (int t = 0; t < 3; t++)
+#pragma unroll
+    for (int il = 0; il < 4; il++) {
+      tile_dma(krs, lds0 + t * FWD_TILE_BYTES, wu, il, t * FWD_TILE_BYTES + goff[il]);
+      if (t < 2) tile_dma(vrs, lds0 + (3 + t) * FWD_TILE_BYTES, wu, il, t * FWD_TILE_BYTES + goff[il]);
+    }
+  __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): this wavefront's DMA has landed
+  __builtin_amdgcn_s_barrier();                    // ... and everyone else's
+  // Two score buffers that swap roles every tile (the loop body is unrolled twice, so no
+  // register copies): while one holds the tile being exponentiated, the other receives the
+  // S^T of the next tile.
+  f32x16 sA[2][2], sB[2][2];   // [key block][row block]
+  qk_tile(smem, kaddr, qf, sA);
+  float mx[2];                 // row maximum (both lane halves, log2 units) of the tile in flight
+  bool raise = false;          // some row's maximum exceeds the reference max by more than 2^LAZY
+#pragma unroll
+  for (int rb = 0; rb < 2; rb++) {
+    float v = sA[0][rb][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; kb++)
+#pragma unroll
+      for (int r = 0; r < 16; r++) v = fmaxf(v, sA[kb][rb][r]);
+    mx[rb] = max_both_halves(v) * a.c;
+    raise = raise || (mx[rb] > m2[rb] + FWD_LAZY);
   }
-  __syncthreads();
+  __builtin_amdgcn_s_barrier();   // K tile 0 is consumed by every wavefront before its slot is refilled
 
   const long long wave_first_q = a.q_off + q0;
-  const long long wave_last_q = a.q_off + q0 + 63;
+  // last key index of this chunk that each of the lane's two rows may see (-1: none)
+  int klim[2];
+#pragma unroll
+  for (int rb = 0; rb < 2; rb++) {
+    long long v = a.causal ? (a.q_off + q0 + rb * 32 + lr - a.k_off) : (long long)(a.Nc - 1);
+    v = v < -1 ? -1 : v;
+    klim[rb] = (int)(v > (long long)(a.Nc - 1) ? (long long)(a.Nc - 1) : v);
+  }
+  bf16x2 ones;
+  ones[0] = (bf16)1.0f; ones[1] = (bf16)1.0f;
+  constexpr int PF = 4;          // operand fragments are fetched PF MFMA pairs ahead
 
-  for (int kt = 0; kt < ntiles; kt++) {
-    const int cur = kt & 1;
-    if (kt + 1 < ntiles) {
-      store_tile_lds(smem + (cur ^ 1) * 2 * FWD_TILE_BYTES, tid, kreg);
-      store_tile_lds(smem + ((cur ^ 1) * 2 + 1) * FWD_TILE_BYTES, tid, vreg);
-      if (kt + 2 < ntiles) {
-        load_tile_regs(Kh, (kt + 2) * FWD_BC, a.Nc, tid, kreg);
-        load_tile_regs(Vh, (kt + 2) * FWD_BC, a.Nc, tid, vreg);
-      }
-    }
+  // One tile: `sc` holds S^T of tile kt (unmasked), `sx` receives S^T of tile kt + 1.
+  // slot = kt % 3 is the LDS ring slot of tile kt.
+  auto step = [&](f32x16 (&sc)[2][2], f32x16 (&sx)[2][2], int kt, int slot) __attribute__((always_inline)) {
+    const int slot1 = (slot == FWD_NBUF - 1) ? 0 : slot + 1;     // tile kt + 1
+    const int slot2 = (slot1 == FWD_NBUF - 1) ? 0 : slot1 + 1;   // tile kt + 2
+    const char* kl_next = smem + slot1 * FWD_TILE_BYTES;         // K of tile kt + 1
+    const char* vl = smem + (3 + slot) * FWD_TILE_BYTES;         // V of tile kt
+    const unsigned k_dst = lds0 + slot * FWD_TILE_BYTES;         // K of tile kt + 3 replaces K of tile kt
+    const unsigned v_dst = lds0 + (3 + slot2) * FWD_TILE_BYTES;  // V of tile kt + 2 replaces V of tile kt - 1
+    // first K fragments of the next tile: in flight while the rare-path checks run
+    bf16x8 kfq[PF + 1];
+#pragma unroll
+    for (int pn = 0; pn < PF; pn++) kfq[pn] = lds_read_b128(kl_next, (pn & 1) * 32 * 256 + kaddr[pn >> 1]);
     const long long tile_first_k = a.k_off + (long long)kt * FWD_BC;
-    const bool wave_skips = (a.causal && tile_first_k > wave_last_q) || (q0 >= a.Nq);
-    if (!wave_skips) {
-      const char* kl = smem + cur * 2 * FWD_TILE_BYTES;
-      const char* vl = kl + FWD_TILE_BYTES;
-      // ---- S^T = K Q^T
-      f32x16 s[2][2];      // [key block][row block]
-#pragma unroll
-      for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-        for (int rb = 0; rb < 2; rb++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) s[kb][rb][r] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 8; ks++) {
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++) {
-          bf16x8 kf = lds_read_b128(kl, kb * 32 * 256 + kaddr[ks]);
-#pragma unroll
-          for (int rb = 0; rb < 2; rb++) s[kb][rb] = mfma32(kf, qf[rb][ks], s[kb][rb]);
-        }
-      }
-      // ---- masking (diagonal tiles, ragged key tail)
-      const bool need_mask = (a.causal && tile_first_k + FWD_BC - 1 > wave_first_q) ||
-                             ((kt + 1) * FWD_BC > a.Nc);
-      if (need_mask) {
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++)
-#pragma unroll
-          for (int rb = 0; rb < 2; rb++) {
-            long long qpos = a.q_off + q0 + rb * 32 + lr;
-#pragma unroll
-            for (int r = 0; r < 16; r++) {
-              int kidx = kt * FWD_BC + kb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-              bool vis = (kidx < a.Nc) && (!a.causal || (a.k_off + kidx <= qpos));
-              if (!vis) s[kb][rb][r] = BURST_NEG_INF;
-            }
-          }
-      }
-      // ---- online softmax, one query row per lane
-      bf16x8 pf[2][4];     // P^T fragments (B operand): [row block][16-key group]
+    // ---- masking (diagonal tiles, ragged key tail): rare; redo the row maxima afterwards
+    const bool need_mask = (a.causal && tile_first_k + FWD_BC - 1 > wave_first_q) ||
+                           ((kt + 1) * FWD_BC > a.Nc);
+    if (need_mask) {
+      raise = false;
 #pragma unroll
       for (int rb = 0; rb < 2; rb++) {
-        float mx = s[0][rb][0];
+        // score register r of key block kb holds key index kt*64 + 4h + (kb*32 + 8*(r/4) + r%4);
+        // it is visible iff that constant part is <= lim
+        const int lim = klim[rb] - (kt * FWD_BC + 4 * h);
+        float v = BURST_NEG_INF;
 #pragma unroll
         for (int kb = 0; kb < 2; kb++)
 #pragma unroll
-          for (int r = 0; r < 16; r++) mx = fmaxf(mx, s[kb][rb][r]);
-        mx = max_both_halves(mx);
-        float m_new = fmaxf(m2[rb], mx * a.c);
-        float ref = (m_new == BURST_NEG_INF) ? 0.f : m_new;
-        float alpha = fast_exp2(m2[rb] - ref);
-        m2[rb] = m_new;
-        float psum = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; kb++) {
-          float p[16];
-#pragma unroll
           for (int r = 0; r < 16; r++) {
-            p[r] = fast_exp2(__builtin_fmaf(s[kb][rb][r], a.c, -ref));
-            psum += p[r];
+            const int cpart = kb * 32 + 8 * (r >> 2) + (r & 3);
+            float x = (cpart <= lim) ? sc[kb][rb][r] : BURST_NEG_INF;
+            sc[kb][rb][r] = x;
+            v = fmaxf(v, x);
           }
+        mx[rb] = max_both_halves(v) * a.c;
+        raise = raise || (mx[rb] > m2[rb] + FWD_LAZY);
+      }
+    }
+    // ---- raise the reference max only when it is exceeded by 2^LAZY
+    if (__builtin_amdgcn_ballot_w64(raise) != 0) {             // wave-uniform, rare after the first tiles
+      mfma_acc_fence(o);
 #pragma unroll
-          for (int u = 0; u < 2; u++) {
-            bf16x8 f;
-#pragma unroll
-            for (int t = 0; t < 8; t++) f[t] = (bf16)p[8 * u + t];
-            pf[rb][2 * kb + u] = f;
-          }
-        }
-        lsum[rb] = lsum[rb] * alpha + psum;
+      for (int rb = 0; rb < 2; rb++) {
+        float m_new = fmaxf(m2[rb], mx[rb]);
+        float ref = (m_new == BURST_NEG_INF) ? 0.f : m_new;
+        float alpha = fast_exp2(m2[rb] - ref);                 // exp2(-inf) = 0 for a fresh row
+        m2[rb] = m_new;
+        lsum[rb] *= alpha;
 #pragma unroll
         for (int db = 0; db < 4; db++)
 #pragma unroll
           for (int r = 0; r < 16; r++) o[rb][db][r] *= alpha;
       }
-      // ---- O^T += V^T P^T
+      mfma_acc_fence(o);
+    }
+    float nref[2];
 #pragma unroll
-      for (int kg = 0; kg < 4; kg++) {
+    for (int rb = 0; rb < 2; rb++) nref[rb] = (m2[rb] == BURST_NEG_INF) ? 0.f : -m2[rb];
+
+    // The 64 MFMAs of a tile (32 for S^T of the next tile, then 32 for O^T += V^T P^T) are
+    // hand-interleaved with the vector work, one MFMA per slice, scheduling barriers between
+    // slices: the matrix and vector pipes of a SIMD only run concurrently when their
+    // instructions alternate in the wave's instruction stream, and a slice hides about seven
+    // plain vector instructions (an exp counts double).  Vector work per tile: 32 "pairs"
+    // (two scores: 2 fma, 2 exp, convert to packed bf16, row sum by dot product with ones),
+    // ordered by key group so that P is ready when its MFMA comes; 20 pairs ride on the first
+    // 32 slices, 12 on the next 12, then the row maxima of the next tile.
+    bf16x8 pf[2][4];       // P^T fragments (B operand): [row block][16-key group]
+    bf16x4 vfq[PF + 1][2]; // V^T fragment halves
+    auto softmax_pair = [&](int pidx) __attribute__((always_inline)) {           // pidx = kg * 8 + rb * 4 + t / 2
+      const int kg = pidx >> 3, srb = (pidx >> 2) & 1, t = (pidx & 3) * 2;
+      const int skb = kg >> 1, r = 8 * (kg & 1) + t;
+      float p0 = fast_exp2(__builtin_fmaf(sc[skb][srb][r], a.c, nref[srb]));
+      float p1 = fast_exp2(__builtin_fmaf(sc[skb][srb][r + 1], a.c, nref[srb]));
+      bf16x2 pk;
+      pk[0] = (bf16)p0; pk[1] = (bf16)p1;
+      lsum[srb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lsum[srb], false);
+      pf[srb][kg][t] = pk[0];
+      pf[srb][kg][t + 1] = pk[1];
+    };
 #pragma unroll
-        for (int db = 0; db < 4; db++) {
-          bf16x4 va = lds_read_tr(vl, kg * 16 * 256 + vaddr[db][0]);
-          bf16x4 vb = lds_read_tr(vl, kg * 16 * 256 + vaddr[db][1]);
-          bf16x8 vf;
-          vf[0] = va[0]; vf[1] = va[1]; vf[2] = va[2]; vf[3] = va[3];
-          vf[4] = vb[0]; vf[5] = vb[1]; vf[6] = vb[2]; vf[7] = vb[3];
+    for (int kb = 0; kb < 2; kb++)
 #pragma unroll
-          for (int rb = 0; rb < 2; rb++) o[rb][db] = mfma32(vf, pf[rb][kg], o[rb][db]);
+      for (int rb = 0; rb < 2; rb++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) sx[kb][rb][r] = 0.f;
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- slices 0..31: S^T of the next tile.  After the last tile the product reads a stale
+    // buffer and is discarded.
+#pragma unroll
+    for (int i = 0; i < 32; i++) {
+      const int pair = i >> 1;                     // K fragment index: ks = pair / 2, kb = pair % 2
+      const int ks = pair >> 1, kb = pair & 1, rb = i & 1;
+      if ((i & 1) == 0 && pair + PF < 16) {
+        const int pn = pair + PF;
+        kfq[pn % (PF + 1)] = lds_read_b128(kl_next, (pn & 1) * 32 * 256 + kaddr[pn >> 1]);
+      }
+      if ((i & 1) == 0 && pair + PF >= 16) {       // first V fragments of the second half
+        const int pn = pair + PF - 16;
+        vfq[pn][0] = lds_read_tr(vl, vaddr[pn & 3][0]);
+        vfq[pn][1] = lds_read_tr(vl, vaddr[pn & 3][1]);
+      }
+      sx[kb][rb] = mfma32(kfq[pair % (PF + 1)], qf[rb][ks], sx[kb][rb]);
+      // 20 pairs over 32 slices: 5 in every 8
+      {
+        const int i8 = i & 7;
+        if (i8 == 0 || i8 == 2 || i8 == 3 || i8 == 5 || i8 == 6) {
+          const int within = (i8 == 0) ? 0 : (i8 == 2) ? 1 : (i8 == 3) ? 2 : (i8 == 5) ? 3 : 4;
+          softmax_pair((i >> 3) * 5 + within);
         }
       }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __syncthreads();
+    // ---- slices 32..63: O^T += V^T P^T, with the DMA of tile kt + 3 (K) and kt + 2 (V), the
+    // last 12 softmax pairs and the row maxima of the next tile
+    float nmax0 = sx[0][0][0], nmax1 = sx[0][1][0];
+#pragma unroll
+    for (int i = 0; i < 32; i++) {
+      const int pair = i >> 1;                     // V fragment index: kg = pair / 4, db = pair % 4
+      const int kg = pair >> 2, db = pair & 3, rb = i & 1;
+      if ((i & 1) == 0 && pair + PF < 16) {
+        const int pn = pair + PF;
+        vfq[pn % (PF + 1)][0] = lds_read_tr(vl, (pn >> 2) * 16 * 256 + vaddr[pn & 3][0]);
+        vfq[pn % (PF + 1)][1] = lds_read_tr(vl, (pn >> 2) * 16 * 256 + vaddr[pn & 3][1]);
+      }
+      if ((i & 3) == 1) {                          // 8 slots: one DMA of 4 tile rows each
+        const int j = i >> 2;                      // 0..3 -> K of tile kt + 3, 4..7 -> V of tile kt + 2
+        if (j < 4) tile_dma(krs, k_dst, wu, j, (kt + 3) * FWD_TILE_BYTES + goff[j]);
+        else tile_dma(vrs, v_dst, wu, j - 4, (kt + 2) * FWD_TILE_BYTES + goff[j - 4]);
+      }
+      {
+        bf16x8 vf;
+        const bf16x4 va = vfq[pair % (PF + 1)][0], vb = vfq[pair % (PF + 1)][1];
+        vf[0] = va[0]; vf[1] = va[1]; vf[2] = va[2]; vf[3] = va[3];
+        vf[4] = vb[0]; vf[5] = vb[1]; vf[6] = vb[2]; vf[7] = vb[3];
+        mfma32_acc(o[rb][db], vf, pf[rb][kg]);
+      }
+      if (i < 12) softmax_pair(20 + i);
+      if (i >= 12 && i < 28) {                     // row maxima of the next tile: 16 slices x 4 scores
+        const int e = i - 12;                      // 0..15
+        const int kb2 = e >> 3, r = (e & 7) * 2;
+        nmax0 = fmaxf(nmax0, fmaxf(sx[kb2][0][r], sx[kb2][0][r + 1]));
+        nmax1 = fmaxf(nmax1, fmaxf(sx[kb2][1][r], sx[kb2][1][r + 1]));
+      }
+      if (i == 28) mx[0] = max_both_halves(nmax0) * a.c;
+      if (i == 29) mx[1] = max_both_halves(nmax1) * a.c;
+      if (i == 30) raise = (mx[0] > m2[0] + FWD_LAZY) || (mx[1] > m2[1] + FWD_LAZY);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // The 8 DMA loads just issued may stay in flight; everything older (the tiles the next
+    // step reads) must have landed before the barrier publishes it.
+    __builtin_amdgcn_s_waitcnt(0x0F78);            // vmcnt(8), lgkmcnt / expcnt unconstrained
+    __builtin_amdgcn_s_barrier();
+  };
+
+  int slot = 0;
+  for (int kt = 0; kt < ntiles; kt += 2) {
+    step(sA, sB, kt, slot);
+    slot = (slot == FWD_NBUF - 1) ? 0 : slot + 1;
+    if (kt + 1 >= ntiles) break;
+    step(sB, sA, kt + 1, slot);
+    slot = (slot == FWD_NBUF - 1) ? 0 : slot + 1;
   }
 
+  __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): no DMA may outlive the loop
+  mfma_acc_fence(o);
   // ---- epilogue: merge the chunk result into the state in HBM (Alg. 1 merge step)
   float* Oh = a.O_acc + (size_t)head * a.Nq * 128;
   float* mh = a.m + (size_t)head * a.Nq;
@@ -260,9 +380,8 @@ burst_fwd_mfma_kernel(FwdArgs a) {
       float m_old2 = mh[row] * kLog2e;             // stored in natural-log units
       float l_old = lh[row];
       float m_new = fmaxf(m_old2, m2[rb]);
-      float ref = (m_new == BURST_NEG_INF) ? 0.f : m_new;
-      float fa = fast_exp2(m_old2 - ref);          // weight of the stored state
-      float fb = fast_exp2(m2[rb] - ref);          // weight of this chunk
+      float fa = fast_exp2(m_old2 - m_new);        // weight of the stored state
+      float fb = fast_exp2(m2[rb] - m_new);        // weight of this chunk
       float* orow = Oh + (size_t)row * 128;
 #pragma unroll
       for (int db = 0; db < 4; db++)
@@ -299,7 +418,14 @@ int launch_fwd_mfma(const KParams& p, const void* Q, const void* K, const void* 
   int heads8 = ((a.H + 7) / 8) * 8;                // pad the head count to a multiple of 8 ids
   long long nblocks = (long long)heads8 * a.q_blocks;
   if (nblocks > 0x7fffffffLL) return BURST_ERR_SHAPE;
-  hipLaunchKernelGGL(burst_fwd_mfma_kernel, dim3((unsigned)nblocks), dim3(256), 4 * FWD_TILE_BYTES, stream, a);
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)burst_fwd_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            2 * FWD_NBUF * FWD_TILE_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(burst_fwd_mfma_kernel, dim3((unsigned)nblocks), dim3(256),
+                     2 * FWD_NBUF * FWD_TILE_BYTES, stream, a);
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 
