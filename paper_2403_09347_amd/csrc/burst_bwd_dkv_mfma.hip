@@ -10,22 +10,9 @@
 //              S = Q K^T, dP = dO V^T, P, dS, dV += P^T dO, dK += dS^T Q
 // Both recompute P = exp(S - lse) from the saved log-sum-exp; neither stores S, P or dS.
 // No atomics: results are deterministic.
-#include "burst_common.h"
+#include "burst_bwd_common.h"
 
 namespace burst {
-
-struct BwdArgs {
-  const bf16* Q; const bf16* K; const bf16* V; const bf16* dO;
-  const float* lse; const float* D;
-  float* dQ; float* dK; float* dV;
-  int Nq, Nc, H;
-  int causal;
-  float c;               // scale * log2(e)
-  float scale;
-  long long q_off, k_off;
-  int blocks_per_head;
-  int acc_dq, acc_dkv;
-};
 
 // 32 rows x 128 bf16 tile: 512 granules of 16 B, 2 per thread.
 __device__ __forceinline__ void load_tile32_regs(const bf16* __restrict__ base, int row0, int nrows,
@@ -46,190 +33,6 @@ __device__ __forceinline__ void store_tile32_lds(char* lds, int tid, const i32x4
     int gi = i * 256 + tid;
     int row = gi >> 4, g = gi & 15;
     *reinterpret_cast<i32x4*>(lds + tile_off(row, g)) = r[i];
-  }
-}
-
-__device__ __forceinline__ bf16x8 cat4(bf16x4 a, bf16x4 b) {
-  bf16x8 v;
-  v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3];
-  v[4] = b[0]; v[5] = b[1]; v[6] = b[2]; v[7] = b[3];
-  return v;
-}
-
-// ------------------------------------------------------------------------------------ dQ
-constexpr int DQ_BR = 256;            // query rows per workgroup (4 wavefronts x 64)
-constexpr int DQ_BC = 32;             // keys per tile
-constexpr int DQ_TILE_BYTES = DQ_BC * 256;
-
-__global__ void __launch_bounds__(256, 1)
-burst_bwd_dq_kernel(BwdArgs a) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  // buffer b: K tile at (2b) * DQ_TILE_BYTES, V tile at (2b + 1) * DQ_TILE_BYTES
-  const int tid = threadIdx.x;
-  const int w = tid >> 6, lane = tid & 63, lr = lane & 31, h = lane >> 5;
-  int head, qb;
-  {
-    int bid = blockIdx.x;
-    int xcd = bid & 7, idx = bid >> 3;
-    int hx = idx / a.blocks_per_head;
-    qb = idx - hx * a.blocks_per_head;
-    head = hx * 8 + xcd;
-    if (head >= a.H) return;
-  }
-  const int q0 = qb * DQ_BR + w * 64;
-  const bf16* Qh = a.Q + (size_t)head * a.Nq * 128;
-  const bf16* Gh = a.dO + (size_t)head * a.Nq * 128;
-  const bf16* Kh = a.K + (size_t)head * a.Nc * 128;
-  const bf16* Vh = a.V + (size_t)head * a.Nc * 128;
-  const float* lseh = a.lse + (size_t)head * a.Nq;
-  const float* Dh = a.D + (size_t)head * a.Nq;
-  float* dQh = a.dQ + (size_t)head * a.Nq * 128;
-
-  int ntiles = (a.Nc + DQ_BC - 1) / DQ_BC;
-  if (a.causal) {
-    long long lim = a.q_off + min(qb * DQ_BR + DQ_BR, a.Nq) - 1 - a.k_off;
-    long long t = lim < 0 ? 0 : lim / DQ_BC + 1;
-    if (t < ntiles) ntiles = (int)t;
-  }
-
-  f32x16 dq[2][4];
-#pragma unroll
-  for (int rb = 0; rb < 2; rb++)
-#pragma unroll
-    for (int db = 0; db < 4; db++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) dq[rb][db][r] = 0.f;
-
-  if (ntiles > 0) {
-    bf16x8 qf[2][8], gf[2][8];
-    float lse2[2], Dv[2];
-#pragma unroll
-    for (int rb = 0; rb < 2; rb++) {
-      int row = q0 + rb * 32 + lr;
-      bool ok = row < a.Nq;
-      float lv = ok ? lseh[row] : BURST_NEG_INF;
-      lse2[rb] = (lv == BURST_NEG_INF) ? __builtin_inff() : lv * kLog2e;   // +inf => P = 0
-      Dv[rb] = ok ? Dh[row] : 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 8; ks++) {
-        bf16x8 z;
-#pragma unroll
-        for (int t = 0; t < 8; t++) z[t] = (bf16)0.0f;
-        qf[rb][ks] = ok ? *reinterpret_cast<const bf16x8*>(Qh + (size_t)row * 128 + ks * 16 + h * 8) : z;
-        gf[rb][ks] = ok ? *reinterpret_cast<const bf16x8*>(Gh + (size_t)row * 128 + ks * 16 + h * 8) : z;
-      }
-    }
-    int kaddr[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ks++) kaddr[ks] = tile_off(lr, 2 * ks + h);
-    int taddr[4][2];
-    {
-      const int j16 = lane & 15, dh = (lane >> 4) & 1;
-#pragma unroll
-      for (int db = 0; db < 4; db++)
-#pragma unroll
-        for (int sx = 0; sx < 2; sx++)
-          taddr[db][sx] = tile_off(8 * sx + 4 * h + (j16 >> 2), db * 4 + 2 * dh + ((j16 & 3) >> 1)) + (j16 & 1) * 8;
-    }
-    i32x4 kreg[2], vreg[2];
-    load_tile32_regs(Kh, 0, a.Nc, tid, kreg);
-    load_tile32_regs(Vh, 0, a.Nc, tid, vreg);
-    store_tile32_lds(smem, tid, kreg);
-    store_tile32_lds(smem + DQ_TILE_BYTES, tid, vreg);
-    if (ntiles > 1) {
-      load_tile32_regs(Kh, DQ_BC, a.Nc, tid, kreg);
-      load_tile32_regs(Vh, DQ_BC, a.Nc, tid, vreg);
-    }
-    __syncthreads();
-    const long long wave_first_q = a.q_off + q0, wave_last_q = a.q_off + q0 + 63;
-    for (int kt = 0; kt < ntiles; kt++) {
-      const int cur = kt & 1;
-      if (kt + 1 < ntiles) {
-        store_tile32_lds(smem + (cur ^ 1) * 2 * DQ_TILE_BYTES, tid, kreg);
-        store_tile32_lds(smem + ((cur ^ 1) * 2 + 1) * DQ_TILE_BYTES, tid, vreg);
-        if (kt + 2 < ntiles) {
-          load_tile32_regs(Kh, (kt + 2) * DQ_BC, a.Nc, tid, kreg);
-          load_tile32_regs(Vh, (kt + 2) * DQ_BC, a.Nc, tid, vreg);
-        }
-      }
-      const long long tile_first_k = a.k_off + (long long)kt * DQ_BC;
-      const bool wave_skips = (a.causal && tile_first_k > wave_last_q) || (q0 >= a.Nq);
-      if (!wave_skips) {
-        const char* kl = smem + cur * 2 * DQ_TILE_BYTES;
-        const char* vl = kl + DQ_TILE_BYTES;
-        f32x16 s[2], dp[2];
-#pragma unroll
-        for (int rb = 0; rb < 2; rb++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) { s[rb][r] = 0.f; dp[rb][r] = 0.f; }
-#pragma unroll
-        for (int ks = 0; ks < 8; ks++) {
-          bf16x8 kf = lds_read_b128(kl, kaddr[ks]);
-          bf16x8 vf = lds_read_b128(vl, kaddr[ks]);
-#pragma unroll
-          for (int rb = 0; rb < 2; rb++) {
-            s[rb] = mfma32(kf, qf[rb][ks], s[rb]);
-            dp[rb] = mfma32(vf, gf[rb][ks], dp[rb]);
-          }
-        }
-        const bool need_mask = (a.causal && tile_first_k + DQ_BC - 1 > wave_first_q) ||
-                               ((kt + 1) * DQ_BC > a.Nc);
-        bf16x8 dsf[2][2];
-#pragma unroll
-        for (int rb = 0; rb < 2; rb++) {
-          long long qpos = a.q_off + q0 + rb * 32 + lr;
-          float ds[16];
-#pragma unroll
-          for (int r = 0; r < 16; r++) {
-            float p = fast_exp2(__builtin_fmaf(s[rb][r], a.c, -lse2[rb]));
-            if (need_mask) {
-              int kidx = kt * DQ_BC + 8 * (r >> 2) + 4 * h + (r & 3);
-              bool vis = (kidx < a.Nc) && (!a.causal || (a.k_off + kidx <= qpos));
-              if (!vis) p = 0.f;
-            }
-            ds[r] = p * (dp[rb][r] - Dv[rb]);
-          }
-#pragma unroll
-          for (int u = 0; u < 2; u++) {
-            bf16x8 f;
-#pragma unroll
-            for (int t = 0; t < 8; t++) f[t] = (bf16)ds[8 * u + t];
-            dsf[rb][u] = f;
-          }
-        }
-        // dQ^T += K^T dS^T  (A = K^T via transposing reads: rows = keys, cols = d)
-#pragma unroll
-        for (int kg = 0; kg < 2; kg++) {
-#pragma unroll
-          for (int db = 0; db < 4; db++) {
-            bf16x8 ktf = cat4(lds_read_tr(kl, kg * 16 * 256 + taddr[db][0]),
-                              lds_read_tr(kl, kg * 16 * 256 + taddr[db][1]));
-#pragma unroll
-            for (int rb = 0; rb < 2; rb++) dq[rb][db] = mfma32(ktf, dsf[rb][kg], dq[rb][db]);
-          }
-        }
-      }
-      __syncthreads();
-    }
-  }
-  // epilogue: dQ rows are owned by this wavefront alone
-#pragma unroll
-  for (int rb = 0; rb < 2; rb++) {
-    int row = q0 + rb * 32 + lr;
-    if (row < a.Nq) {
-      float* orow = dQh + (size_t)row * 128;
-#pragma unroll
-      for (int db = 0; db < 4; db++)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; q4++) {
-          float* ptr = orow + db * 32 + 8 * q4 + 4 * h;
-          f32x4 v = {0.f, 0.f, 0.f, 0.f};
-          if (a.acc_dq) v = *reinterpret_cast<f32x4*>(ptr);
-#pragma unroll
-          for (int b = 0; b < 4; b++) v[b] += a.scale * dq[rb][db][4 * q4 + b];
-          *reinterpret_cast<f32x4*>(ptr) = v;
-        }
-    }
   }
 }
 
@@ -475,19 +278,6 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     }
 }
 
-static BwdArgs make_bwd_args(const KParams& p, const void* Q, const void* K, const void* V,
-                             const void* dO, const float* lse, const float* D,
-                             float* dQ, float* dK, float* dV, int acc_dq, int acc_dkv) {
-  BwdArgs a;
-  a.Q = (const bf16*)Q; a.K = (const bf16*)K; a.V = (const bf16*)V; a.dO = (const bf16*)dO;
-  a.lse = lse; a.D = D; a.dQ = dQ; a.dK = dK; a.dV = dV;
-  a.Nq = p.Nq; a.Nc = p.Nc; a.H = p.B * p.H;
-  a.causal = p.causal; a.c = p.scale * kLog2e; a.scale = p.scale;
-  a.q_off = p.q_off; a.k_off = p.k_off;
-  a.blocks_per_head = 0; a.acc_dq = acc_dq; a.acc_dkv = acc_dkv;
-  return a;
-}
-
 static int set_dkv_lds_attr() {
   static bool attr_set = false;
   if (!attr_set) {
@@ -496,19 +286,6 @@ static int set_dkv_lds_attr() {
     attr_set = true;
   }
   return BURST_OK;
-}
-
-int launch_bwd_dq_mfma(const KParams& p, const void* Q, const void* K, const void* V,
-                       const void* dO, const float* lse, const float* D, float* dQ, int acc_dq,
-                       hipStream_t stream) {
-  if (p.Nq <= 0) return BURST_OK;
-  BwdArgs a = make_bwd_args(p, Q, K, V, dO, lse, D, dQ, nullptr, nullptr, acc_dq, 0);
-  int heads8 = ((a.H + 7) / 8) * 8;
-  a.blocks_per_head = (p.Nq + DQ_BR - 1) / DQ_BR;
-  long long nb = (long long)heads8 * a.blocks_per_head;
-  if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;
-  hipLaunchKernelGGL(burst_bwd_dq_kernel, dim3((unsigned)nb), dim3(256), 4 * DQ_TILE_BYTES, stream, a);
-  return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 
 int launch_bwd_dkv_mfma(const KParams& p, const void* Q, const void* K, const void* V,
