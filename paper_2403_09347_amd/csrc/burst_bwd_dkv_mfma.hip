@@ -1,55 +1,36 @@
-// Backward of one block pair (paper Alg. 2 loop body) for bf16, d = 128, as two kernels.
+// Backward, dK / dV side of one block pair (paper Alg. 2 loop body) for bf16, d = 128.
 //
-// Alg. 2 accumulates dK_i, dV_i over query rows and dQ_j over keys.  On this GPU a single
-// kernel that keeps one side in registers has to push the other side through fp32 atomics,
-// whose rate (about one per clock per L2 channel) is far below what d = 128 needs.  So the
-// block pair is done twice, each time with the reduction side held in registers:
-//   * bwd_dq:  query rows stationary (64 per wavefront), keys streamed in 32-key tiles:
-//              S^T = K Q^T, dP^T = V dO^T, dS^T = P^T o (dP^T - D), dQ^T += K^T dS^T
-//   * bwd_dkv: keys stationary (64 per wavefront), query rows streamed in 32-row tiles:
-//              S = Q K^T, dP = dO V^T, P, dS, dV += P^T dO, dK += dS^T Q
-// Both recompute P = exp(S - lse) from the saved log-sum-exp; neither stores S, P or dS.
-// No atomics: results are deterministic.
+// Key-stationary half of the split backward (see burst_bwd_dq_mfma.hip for why it is split):
+//     S = Q K^T,  dP = dO V^T,  P = exp(S - lse),  dS = P o (dP - D),
+//     dV += P^T dO,  dK += dS^T Q
+// P is recomputed from the saved log-sum-exp; neither S, P nor dS is ever stored.
+//
+// One workgroup = 4 wavefronts = 128 keys of one (batch, head); a wavefront owns 32 keys:
+// their K and V fragments (B operands of S and dP) and the dK / dV accumulators stay in
+// registers for the whole kernel, the accumulators pinned in AGPRs.  Query rows stream through
+// in tiles of 64 rows (two 32-row blocks): Q and dO tiles are DMA-ed from HBM into LDS rings two
+// tiles ahead.  With S = Q K^T a lane owns one key and its registers run over query rows, so P
+// and dS already have the A-operand layout of P^T dO and dS^T Q (contraction over rows); the B
+// operands dO and Q come through transposing LDS reads.  lse and D are per-row, i.e. per
+// register: they are staged (already scaled) in a small LDS ring and read as broadcasts.
+// The 64 MFMAs of a tile run in four phases of 16, software-pipelined across the two row
+// blocks so that the vector work of one block rides on the MFMAs of the other:
+//   1: S, dP of block 0            2: S, dP of block 1   + P, dS of block 0
+//   3: dV, dK of block 0 + P, dS of block 1              4: dV, dK of block 1 + DMA of tile t+2
+// No atomics: every key row is owned by one wavefront, results are bitwise reproducible.
 #include "burst_bwd_common.h"
 
 namespace burst {
 
-// 32 rows x 128 bf16 tile: 512 granules of 16 B, 2 per thread.
-__device__ __forceinline__ void load_tile32_regs(const bf16* __restrict__ base, int row0, int nrows,
-                                                 int tid, i32x4 (&r)[2]) {
-#pragma unroll
-  for (int i = 0; i < 2; i++) {
-    int gi = i * 256 + tid;
-    int row = gi >> 4, g = gi & 15;
-    i32x4 v = {0, 0, 0, 0};
-    if (row0 + row < nrows)
-      v = *reinterpret_cast<const i32x4*>(base + (size_t)(row0 + row) * 128 + g * 8);
-    r[i] = v;
-  }
-}
-__device__ __forceinline__ void store_tile32_lds(char* lds, int tid, const i32x4 (&r)[2]) {
-#pragma unroll
-  for (int i = 0; i < 2; i++) {
-    int gi = i * 256 + tid;
-    int row = gi >> 4, g = gi & 15;
-    *reinterpret_cast<i32x4*>(lds + tile_off(row, g)) = r[i];
-  }
-}
-
-// ------------------------------------------------------------------------------------ dK, dV
-constexpr int DKV_BC = 256;           // keys per workgroup (4 wavefronts x 64)
-constexpr int DKV_BR = 32;            // query rows per tile
-constexpr int DKV_QTILE_BYTES = DKV_BR * 256;
-// LDS: V block | K block (256 rows x 256 B each) | Q tile | dO tile | lse2 | D
-// The K/V blocks stay for the whole kernel (they are the B operands of every step); the
-// Q / dO tile is single-buffered in LDS and double-buffered through registers.
-constexpr int DKV_LDS_V = 0;
-constexpr int DKV_LDS_K = DKV_BC * 256;
-constexpr int DKV_LDS_Q = 2 * DKV_BC * 256;
-constexpr int DKV_LDS_G = DKV_LDS_Q + DKV_QTILE_BYTES;
-constexpr int DKV_LDS_L = DKV_LDS_G + DKV_QTILE_BYTES;
-constexpr int DKV_LDS_D = DKV_LDS_L + DKV_BR * 4;
-constexpr int DKV_LDS_BYTES = DKV_LDS_D + DKV_BR * 4;
+constexpr int DKV_BC = 128;           // keys per workgroup (4 wavefronts x 32)
+constexpr int DKV_BR = 64;            // query rows per tile
+constexpr int DKV_TILE_BYTES = DKV_BR * 256;
+constexpr int DKV_SLOTS = 3;
+constexpr int DKV_LDS_Q = 0;
+constexpr int DKV_LDS_G = DKV_SLOTS * DKV_TILE_BYTES;
+constexpr int DKV_LDS_L = 2 * DKV_SLOTS * DKV_TILE_BYTES;          // -lse * log2(e) per row, 3 slots
+constexpr int DKV_LDS_D = DKV_LDS_L + DKV_SLOTS * DKV_BR * 4;      // D per row, 3 slots
+constexpr int DKV_LDS_BYTES = DKV_LDS_D + DKV_SLOTS * DKV_BR * 4;
 
 __global__ void __launch_bounds__(256, 1)
 burst_bwd_dkv_kernel(BwdArgs a) {
@@ -66,7 +47,7 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     if (head >= a.H) return;
   }
   const int key_wg = kblk * DKV_BC;
-  const int key0 = key_wg + w * 64;                // first key of this wavefront
+  const int key0 = key_wg + w * 32;                // first key of this wavefront
   const bf16* Qh = a.Q + (size_t)head * a.Nq * 128;
   const bf16* Gh = a.dO + (size_t)head * a.Nq * 128;
   const bf16* Kh = a.K + (size_t)head * a.Nc * 128;
@@ -82,33 +63,31 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     if (first_row > 0) t_begin = (int)min((long long)ntiles_all, first_row / DKV_BR);
   }
 
-  f32x16 dk[2][4], dv[2][4];
+  f32x16 dk[4], dv[4];     // [32-wide d block]: rows = the wavefront's 32 keys; pinned in AGPRs
 #pragma unroll
-  for (int kb = 0; kb < 2; kb++)
+  for (int db = 0; db < 4; db++)
 #pragma unroll
-    for (int db = 0; db < 4; db++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) { dk[kb][db][r] = 0.f; dv[kb][db][r] = 0.f; }
+    for (int r = 0; r < 16; r++) { dk[db][r] = 0.f; dv[db][r] = 0.f; }
 
   if (t_begin < ntiles_all) {
-    // K and V blocks of the workgroup -> LDS (4096 granules each, 16 per thread)
-#pragma unroll 4
-    for (int i = 0; i < 16; i++) {
-      int gi = i * 256 + tid;
-      int row = gi >> 4, g = gi & 15;
-      i32x4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-      if (key_wg + row < a.Nc) {
-        kv = *reinterpret_cast<const i32x4*>(Kh + (size_t)(key_wg + row) * 128 + g * 8);
-        vv = *reinterpret_cast<const i32x4*>(Vh + (size_t)(key_wg + row) * 128 + g * 8);
+    // K, V fragments (B operands: lane = key lr, 8 consecutive d)
+    bf16x8 kf[8], vf[8];
+    {
+      const int key = key0 + lr;
+#pragma unroll
+      for (int ks = 0; ks < 8; ks++) {
+        bf16x8 z;
+#pragma unroll
+        for (int t = 0; t < 8; t++) z[t] = (bf16)0.0f;
+        kf[ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Kh + (size_t)key * 128 + ks * 16 + h * 8) : z;
+        vf[ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Vh + (size_t)key * 128 + ks * 16 + h * 8) : z;
       }
-      *reinterpret_cast<i32x4*>(smem + DKV_LDS_K + tile_off(row, g)) = kv;
-      *reinterpret_cast<i32x4*>(smem + DKV_LDS_V + tile_off(row, g)) = vv;
     }
-    // A / B operand reads (128-bit): row = base row + lr, granule 2*ks + h.  Since 2*ks and
-    // (h ^ row code) occupy different bits, the address of step ks is base ^ (ks << 5).
+    // LDS addressing inside a 64-row tile.  A operands (128-bit): row rb*32 + lr, granule
+    // 2*ks + h -> rb*8192 + (abase ^ (ks << 5)).  B operands through transposing reads:
+    // rows = query rows rb*32 + u*16 + ..., cols = d.
     const int abase = lr * 256 + ((h ^ row_code(lr)) << 4);
-    const int kvbase = (w * 64) * 256 + abase;     // + kb * 32 * 256 at the use site
-    int taddr[4][2];     // Q / dO as B operand through transposing reads (rows = q, cols = d)
+    int taddr[4][2];
     {
       const int j16 = lane & 15, dh = (lane >> 4) & 1;
 #pragma unroll
@@ -117,183 +96,215 @@ burst_bwd_dkv_kernel(BwdArgs a) {
         for (int sx = 0; sx < 2; sx++)
           taddr[db][sx] = tile_off(8 * sx + 4 * h + (j16 >> 2), db * 4 + 2 * dh + ((j16 & 3) >> 1)) + (j16 & 1) * 8;
     }
-
-    // lse2 (threads 0..31) and D (threads 32..63) of a tile travel with the Q / dO prefetch
-    auto load_rowstat = [&](int t) -> float {
+    // DMA: a 64-row tile is 16 wave-loads of 4 rows; wavefront w issues loads 4w .. 4w+3
+    const __amdgpu_buffer_rsrc_t qrs = make_rsrc(Qh, (unsigned)a.Nq * 256u);
+    const __amdgpu_buffer_rsrc_t grs = make_rsrc(Gh, (unsigned)a.Nq * 256u);
+    const int wu = __builtin_amdgcn_readfirstlane(w);
+    const unsigned lds0 = lds_addr(smem);
+    int goff[4];
+#pragma unroll
+    for (int il = 0; il < 4; il++) {
+      int row = 16 * w + 4 * il + (lane >> 4);
+      goff[il] = row * 256 + (((lane & 15) ^ row_code(row)) << 4);
+    }
+    auto dma_tile = [&](__amdgpu_buffer_rsrc_t rs, unsigned lds_tile, int il, int tile) __attribute__((always_inline)) {
+      dma_b128_to_lds(rs, lds_tile + (unsigned)(wu * 4 + il) * 1024u, tile * DKV_TILE_BYTES + goff[il]);
+    };
+    // per-row statistics of a tile, already scaled: threads 0..63 carry -lse*log2(e) (or -inf
+    // for a row that saw nothing: then P = exp2(-inf) = 0), threads 64..127 carry D
+    auto load_rowstat = [&](int t) __attribute__((always_inline)) -> float {
       float v = 0.f;
-      if (tid < 64) {
-        int row = t * DKV_BR + (tid & 31);
-        if (tid < 32) {
+      if (tid < 128) {
+        int row = t * DKV_BR + (tid & 63);
+        if (tid < 64) {
           float lv = row < a.Nq ? lseh[row] : BURST_NEG_INF;
-          v = (lv == BURST_NEG_INF) ? __builtin_inff() : lv * kLog2e;      // +inf => P = 0
+          v = (lv == BURST_NEG_INF) ? BURST_NEG_INF : -lv * kLog2e;
         } else {
           v = row < a.Nq ? Dh[row] : 0.f;
         }
       }
       return v;
     };
-    auto store_rowstat = [&](float v) {
-      if (tid < 32) reinterpret_cast<float*>(smem + DKV_LDS_L)[tid] = v;
-      else if (tid < 64) reinterpret_cast<float*>(smem + DKV_LDS_D)[tid - 32] = v;
+    auto store_rowstat = [&](float v, int slot) __attribute__((always_inline)) {
+      if (tid < 64) reinterpret_cast<float*>(smem + DKV_LDS_L)[slot * DKV_BR + tid] = v;
+      else if (tid < 128) reinterpret_cast<float*>(smem + DKV_LDS_D)[slot * DKV_BR + tid - 64] = v;
     };
 
-    i32x4 qreg[2], greg[2];
-    float rstat;
-    load_tile32_regs(Qh, t_begin * DKV_BR, a.Nq, tid, qreg);
-    load_tile32_regs(Gh, t_begin * DKV_BR, a.Nq, tid, greg);
-    rstat = load_rowstat(t_begin);
+    // ---- prologue: tiles t_begin, t_begin + 1 into slots 0, 1; statistics of the first into
+    // slot 0, of the second into registers
+#pragma unroll
+    for (int t = 0; t < 2; t++)
+#pragma unroll
+      for (int il = 0; il < 4; il++) {
+        dma_tile(qrs, lds0 + DKV_LDS_Q + t * DKV_TILE_BYTES, il, t_begin + t);
+        dma_tile(grs, lds0 + DKV_LDS_G + t * DKV_TILE_BYTES, il, t_begin + t);
+      }
+    store_rowstat(load_rowstat(t_begin), 0);
+    float rstat = load_rowstat(t_begin + 1);
+    __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0), lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
 
     const long long wave_first_k = a.k_off + key0;
-    const long long wave_last_k = a.k_off + key0 + 63;
+    const long long wave_last_k = wave_first_k + 31;
+    const long long kpos = wave_first_k + lr;
+    constexpr int LEAD = 4, RING = LEAD + 2;       // A-operand reads run LEAD slices ahead
+    constexpr int TLEAD = 3, TRING = TLEAD + 1;    // transposed fragments run TLEAD slices ahead
+
+    int slot = 0;
     for (int t = t_begin; t < ntiles_all; t++) {
-      // registers (tile t) -> LDS; the previous step's readers are past the closing barrier
-      store_tile32_lds(smem + DKV_LDS_Q, tid, qreg);
-      store_tile32_lds(smem + DKV_LDS_G, tid, greg);
-      store_rowstat(rstat);
-      if (t + 1 < ntiles_all) {
-        load_tile32_regs(Qh, (t + 1) * DKV_BR, a.Nq, tid, qreg);
-        load_tile32_regs(Gh, (t + 1) * DKV_BR, a.Nq, tid, greg);
-        rstat = load_rowstat(t + 1);
-      }
-      __syncthreads();
+      const int slot1 = (slot == DKV_SLOTS - 1) ? 0 : slot + 1;
+      const int slot2 = (slot1 == DKV_SLOTS - 1) ? 0 : slot1 + 1;
+      const char* ql = smem + DKV_LDS_Q + slot * DKV_TILE_BYTES;
+      const char* gl = smem + DKV_LDS_G + slot * DKV_TILE_BYTES;
+      const float* lp = reinterpret_cast<const float*>(smem + DKV_LDS_L) + slot * DKV_BR;
+      const float* dp_ = reinterpret_cast<const float*>(smem + DKV_LDS_D) + slot * DKV_BR;
       const long long tile_first_q = a.q_off + (long long)t * DKV_BR;
-      const long long tile_last_q = tile_first_q + DKV_BR - 1;
-      const bool wave_skips = (a.causal && wave_first_k > tile_last_q) || (key0 >= a.Nc);
-      if (!wave_skips) {
-        const char* ql = smem + DKV_LDS_Q;
-        const char* gl = smem + DKV_LDS_G;
+      // (no branch around the MFMA phases: the AGPR-pinned accumulators must not become phi
+      // values, the allocator would shuttle them through VGPRs every iteration)
+      const bool need_mask = a.causal && (wave_last_k > tile_first_q);
+      {
         f32x16 s[2], dp[2];
 #pragma unroll
-        for (int kb = 0; kb < 2; kb++)
+        for (int rb = 0; rb < 2; rb++)
 #pragma unroll
-          for (int r = 0; r < 16; r++) { s[kb][r] = 0.f; dp[kb][r] = 0.f; }
-        // S = Q K^T, dP = dO V^T: operand fragments are fetched one k-step ahead; the
-        // scheduling barriers keep the compiler from hoisting all 48 LDS reads (which would
-        // not fit in registers next to the 256 accumulators).
-        bf16x8 qa, ga, kf0, kf1, vf0, vf1;
-        qa = lds_read_b128(ql, abase);
-        ga = lds_read_b128(gl, abase);
-        kf0 = lds_read_b128(smem + DKV_LDS_K, kvbase);
-        kf1 = lds_read_b128(smem + DKV_LDS_K, 32 * 256 + kvbase);
-        vf0 = lds_read_b128(smem + DKV_LDS_V, kvbase);
-        vf1 = lds_read_b128(smem + DKV_LDS_V, 32 * 256 + kvbase);
+          for (int r = 0; r < 16; r++) { s[rb][r] = 0.f; dp[rb][r] = 0.f; }
+        // A-operand read j (0..31): rb = j / 16, then 8 Q fragments, then 8 dO fragments
+        bf16x8 fq[RING];
+        auto issue_read = [&](int j) __attribute__((always_inline)) {
+          const int rb = j >> 4, isg = (j >> 3) & 1, ks = j & 7;
+          fq[j % RING] = lds_read_b128(isg ? gl : ql, rb * 32 * 256 + (abase ^ (ks << 5)));
+        };
+        // transposed fragment j (0..31): rb = j / 16, u = (j / 8) % 2, db = (j / 2) % 4, then
+        // 0: dO (for dV), 1: Q (for dK)
+        bf16x4 tq[TRING][2];
+        auto issue_tread = [&](int j) __attribute__((always_inline)) {
+          const int rb = j >> 4, u = (j >> 3) & 1, db = (j >> 1) & 3, isq = j & 1;
+          const char* base = isq ? ql : gl;
+          const int off = (rb * 32 + u * 16) * 256;
+          tq[j % TRING][0] = lds_read_tr(base, off + taddr[db][0]);
+          tq[j % TRING][1] = lds_read_tr(base, off + taddr[db][1]);
+        };
+        bf16x8 pf[2][2], dsf[2][2];   // [row block][16-row group]: A operands of dV, dK
+        f32x4 lq[2], dq4[2];          // row statistics of 4 consecutive rows, one group ahead
+        auto issue_stat = [&](int rb, int q4) __attribute__((always_inline)) {
+          lq[q4 & 1] = *reinterpret_cast<const f32x4*>(lp + rb * 32 + 8 * q4 + 4 * h);
+          dq4[q4 & 1] = *reinterpret_cast<const f32x4*>(dp_ + rb * 32 + 8 * q4 + 4 * h);
+        };
+        // P and dS of two scores: register pair (r, r+1) of row block rb = rows 8*(r/4)+4h+r%4
+        auto pds_pair = [&](int rb, int pidx) __attribute__((always_inline)) {   // pidx 0..7
+          const int r = 2 * pidx, q4 = r >> 2, u = r >> 3, t8 = r & 7;
+          const float s0 = s[rb][r], s1 = s[rb][r + 1];
+          float p0 = fast_exp2(__builtin_fmaf(s0, a.c, lq[q4 & 1][r & 3]));
+          float p1 = fast_exp2(__builtin_fmaf(s1, a.c, lq[q4 & 1][(r & 3) + 1]));
+          float d0 = p0 * (dp[rb][r] - dq4[q4 & 1][r & 3]);
+          float d1 = p1 * (dp[rb][r + 1] - dq4[q4 & 1][(r & 3) + 1]);
+          bf16x2 pk, dk2;
+          pk[0] = (bf16)p0; pk[1] = (bf16)p1;
+          dk2[0] = (bf16)d0; dk2[1] = (bf16)d1;
+          // keep the pair's arithmetic in this slice (its only consumers are MFMAs two phases
+          // later; without an anchor the compiler sinks it there, behind the mask branches)
+          unsigned pu = __builtin_bit_cast(unsigned, pk), du = __builtin_bit_cast(unsigned, dk2);
+          asm volatile("" : "+v"(pu), "+v"(du));
+          pk = __builtin_bit_cast(bf16x2, pu); dk2 = __builtin_bit_cast(bf16x2, du);
+          pf[rb][u][t8] = pk[0]; pf[rb][u][t8 + 1] = pk[1];
+          dsf[rb][u][t8] = dk2[0]; dsf[rb][u][t8 + 1] = dk2[1];
+        };
+        // causal mask of one row block (rare: tiles that straddle the diagonal).  Register r
+        // belongs to row tile_first_q + rb*32 + 4h + (8*(r/4) + r%4); the key is visible iff its
+        // position <= the row's, i.e. iff the constant part is >= lim.  A masked score becomes
+        // -inf, its P and dS become 0.
+        auto mask_block = [&](int rb) __attribute__((always_inline)) {
+          long long d = kpos - (tile_first_q + rb * 32 + 4 * h);
+          const int lim = (int)(d < -1 ? -1 : (d > 64 ? 64 : d));
 #pragma unroll
-        for (int ks = 0; ks < 8; ks++) {
-          bf16x8 qa_n, ga_n, kf0_n, kf1_n, vf0_n, vf1_n;
-          if (ks < 7) {
-            const int x = (ks + 1) << 5;
-            qa_n = lds_read_b128(ql, abase ^ x);
-            ga_n = lds_read_b128(gl, abase ^ x);
-            kf0_n = lds_read_b128(smem + DKV_LDS_K, kvbase ^ x);
-            kf1_n = lds_read_b128(smem + DKV_LDS_K, 32 * 256 + (kvbase ^ x));
-            vf0_n = lds_read_b128(smem + DKV_LDS_V, kvbase ^ x);
-            vf1_n = lds_read_b128(smem + DKV_LDS_V, 32 * 256 + (kvbase ^ x));
+          for (int r = 0; r < 16; r++) {
+            const int cpart = 8 * (r >> 2) + (r & 3);
+            s[rb][r] = (cpart >= lim) ? s[rb][r] : BURST_NEG_INF;
           }
-          s[0] = mfma32(qa, kf0, s[0]);
-          dp[0] = mfma32(ga, vf0, dp[0]);
-          s[1] = mfma32(qa, kf1, s[1]);
-          dp[1] = mfma32(ga, vf1, dp[1]);
+        };
+#pragma unroll
+        for (int j = 0; j < LEAD; j++) issue_read(j);
+        __builtin_amdgcn_sched_barrier(0);
+        // ---- phases 1, 2: S and dP (slice i: rb = i / 16, first 8 S then 8 dP); in phase 2 the
+        // P / dS pairs of row block 0 ride along (one pair every second slice)
+#pragma unroll
+        for (int i = 0; i < 32; i++) {
+          const int rb = i >> 4, isg = (i >> 3) & 1, ks = i & 7;
+          if (i == 16 && need_mask) mask_block(0);
+          if (i + LEAD < 32) issue_read(i + LEAD);
+          if (i + TLEAD >= 32) issue_tread(i + TLEAD - 32);
+          if (i == 14) issue_stat(0, 0);
+          if (i >= 16 && (i & 3) == 1 && i < 28) issue_stat(0, ((i - 16) >> 2) + 1);
+          if (isg) dp[rb] = mfma32(fq[i % RING], vf[ks], dp[rb]);
+          else s[rb] = mfma32(fq[i % RING], kf[ks], s[rb]);
+          if (i >= 16 && (i & 1)) pds_pair(0, (i - 16) >> 1);
+          if (i == 30) issue_stat(1, 0);
           __builtin_amdgcn_sched_barrier(0);
-          if (ks < 7) { qa = qa_n; ga = ga_n; kf0 = kf0_n; kf1 = kf1_n; vf0 = vf0_n; vf1 = vf1_n; }
         }
-        // P = exp2(S c - lse2), dS = P o (dP - D).  Register r of a lane belongs to query row
-        // 8*(r/4) + 4*h + (r%4) of the tile; the row statistics are broadcast reads from LDS.
-        const bool need_mask = a.causal && (wave_last_k > tile_first_q);
-        bf16x8 pf[2][2], dsf[2][2];
-        const float* lp = reinterpret_cast<const float*>(smem + DKV_LDS_L);
-        const float* dp_ = reinterpret_cast<const float*>(smem + DKV_LDS_D);
+        // ---- phases 3, 4: dV += P^T dO, dK += dS^T Q (slice i: rb = i / 16, u = (i / 8) % 2,
+        // db = (i / 2) % 4, even: dV, odd: dK); in phase 3 the pairs of row block 1 ride along
 #pragma unroll
-        for (int u = 0; u < 2; u++) {
-          float lse2v[8], Dvv[8];
-#pragma unroll
-          for (int q2 = 0; q2 < 2; q2++) {
-            f32x4 lv = *reinterpret_cast<const f32x4*>(lp + 16 * u + 8 * q2 + 4 * h);
-            f32x4 dv4 = *reinterpret_cast<const f32x4*>(dp_ + 16 * u + 8 * q2 + 4 * h);
-#pragma unroll
-            for (int b = 0; b < 4; b++) { lse2v[4 * q2 + b] = lv[b]; Dvv[4 * q2 + b] = dv4[b]; }
-          }
-#pragma unroll
-          for (int kb = 0; kb < 2; kb++) {
-            long long kpos = a.k_off + key0 + kb * 32 + lr;
-            bf16x8 f, g;
-#pragma unroll
-            for (int t8 = 0; t8 < 8; t8++) {
-              const int r = 8 * u + t8;
-              float p = fast_exp2(__builtin_fmaf(s[kb][r], a.c, -lse2v[t8]));
-              if (need_mask) {
-                long long qpos = tile_first_q + 8 * (r >> 2) + 4 * h + (r & 3);
-                if (kpos > qpos) p = 0.f;
-              }
-              f[t8] = (bf16)p;
-              g[t8] = (bf16)(p * (dp[kb][r] - Dvv[t8]));
-            }
-            pf[kb][u] = f; dsf[kb][u] = g;
-          }
+        for (int i = 0; i < 32; i++) {
+          const int rb = i >> 4, u = (i >> 3) & 1, db = (i >> 1) & 3, isk = i & 1;
+          if (i == 0 && need_mask) mask_block(1);
+          if (i + TLEAD < 32) issue_tread(i + TLEAD);
+          if (i < 16 && (i & 3) == 1 && i < 12) issue_stat(1, (i >> 2) + 1);
+          const bf16x8 bt = cat4(tq[i % TRING][0], tq[i % TRING][1]);
+          if (isk) mfma32_acc(dk[db], dsf[rb][u], bt);
+          else mfma32_acc(dv[db], pf[rb][u], bt);
+          if (i < 16 && (i & 1)) pds_pair(1, i >> 1);
           __builtin_amdgcn_sched_barrier(0);
-        }
-        // dV += P^T dO ; dK += dS^T Q   (B operands through transposing reads, one step ahead)
-        bf16x4 g0 = lds_read_tr(gl, taddr[0][0]), g1 = lds_read_tr(gl, taddr[0][1]);
-        bf16x4 q0 = lds_read_tr(ql, taddr[0][0]), q1 = lds_read_tr(ql, taddr[0][1]);
-#pragma unroll
-        for (int it = 0; it < 8; it++) {
-          const int u = it >> 2, db = it & 3;
-          bf16x4 g0n, g1n, q0n, q1n;
-          if (it < 7) {
-            const int un = (it + 1) >> 2, dbn = (it + 1) & 3;
-            g0n = lds_read_tr(gl, un * 16 * 256 + taddr[dbn][0]);
-            g1n = lds_read_tr(gl, un * 16 * 256 + taddr[dbn][1]);
-            q0n = lds_read_tr(ql, un * 16 * 256 + taddr[dbn][0]);
-            q1n = lds_read_tr(ql, un * 16 * 256 + taddr[dbn][1]);
-          }
-          bf16x8 gt = cat4(g0, g1), qt = cat4(q0, q1);
-          dv[0][db] = mfma32(pf[0][u], gt, dv[0][db]);
-          dk[0][db] = mfma32(dsf[0][u], qt, dk[0][db]);
-          dv[1][db] = mfma32(pf[1][u], gt, dv[1][db]);
-          dk[1][db] = mfma32(dsf[1][u], qt, dk[1][db]);
-          __builtin_amdgcn_sched_barrier(0);
-          if (it < 7) { g0 = g0n; g1 = g1n; q0 = q0n; q1 = q1n; }
         }
       }
-      __syncthreads();           // everyone is done with this Q / dO tile
+      // ---- statistics of tile t + 1 -> LDS, DMA of tile t + 2, statistics of tile t + 2 ->
+      // registers.  (The register -> LDS write waits for everything this wavefront loaded
+      // earlier, i.e. the DMA issued one step ago, which has had a whole step to land.)
+      store_rowstat(rstat, slot1);
+#pragma unroll
+      for (int il = 0; il < 4; il++) {
+        dma_tile(qrs, lds0 + DKV_LDS_Q + slot2 * DKV_TILE_BYTES, il, t + 2);
+        dma_tile(grs, lds0 + DKV_LDS_G + slot2 * DKV_TILE_BYTES, il, t + 2);
+      }
+      rstat = load_rowstat(t + 2);
+      slot = slot1;
+      __builtin_amdgcn_s_waitcnt(0x0079);          // vmcnt(9): tile t + 1 has landed; lgkmcnt(0)
+      __builtin_amdgcn_s_barrier();
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): no DMA may outlive the loop
   }
+  // wait for the last MFMAs before reading the accumulators
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15"
+               : "+a"(dk[0]), "+a"(dk[1]), "+a"(dk[2]), "+a"(dk[3]),
+                 "+a"(dv[0]), "+a"(dv[1]), "+a"(dv[2]), "+a"(dv[3]));
   // epilogue: keys are owned by this wavefront alone. C layout: lane = d column, regs = keys.
   float* dKh = a.dK + (size_t)head * a.Nc * 128;
   float* dVh = a.dV + (size_t)head * a.Nc * 128;
 #pragma unroll
-  for (int kb = 0; kb < 2; kb++)
+  for (int r = 0; r < 16; r++) {
+    int key = key0 + 8 * (r >> 2) + 4 * h + (r & 3);
+    if (key < a.Nc) {
 #pragma unroll
-    for (int r = 0; r < 16; r++) {
-      int key = key0 + kb * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-      if (key < a.Nc) {
-#pragma unroll
-        for (int db = 0; db < 4; db++) {
-          size_t off = (size_t)key * 128 + db * 32 + lr;
-          float k_old = 0.f, v_old = 0.f;
-          if (a.acc_dkv) { k_old = dKh[off]; v_old = dVh[off]; }
-          dKh[off] = k_old + a.scale * dk[kb][db][r];
-          dVh[off] = v_old + dv[kb][db][r];
-        }
+      for (int db = 0; db < 4; db++) {
+        size_t off = (size_t)key * 128 + db * 32 + lr;
+        float k_old = 0.f, v_old = 0.f;
+        if (a.acc_dkv) { k_old = dKh[off]; v_old = dVh[off]; }
+        dKh[off] = k_old + a.scale * dk[db][r];
+        dVh[off] = v_old + dv[db][r];
       }
     }
-}
-
-static int set_dkv_lds_attr() {
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            DKV_LDS_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
-    attr_set = true;
   }
-  return BURST_OK;
 }
 
 int launch_bwd_dkv_mfma(const KParams& p, const void* Q, const void* K, const void* V,
                         const void* dO, const float* lse, const float* D, float* dK, float* dV,
                         int acc_dkv, hipStream_t stream) {
   if (p.Nc <= 0) return BURST_OK;
-  int st = set_dkv_lds_attr();
-  if (st != BURST_OK) return st;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            DKV_LDS_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
+    attr_set = true;
+  }
   BwdArgs a = make_bwd_args(p, Q, K, V, dO, lse, D, nullptr, dK, dV, 0, acc_dkv);
   int heads8 = ((a.H + 7) / 8) * 8;
   a.blocks_per_head = (p.Nc + DKV_BC - 1) / DKV_BC;
