@@ -48,6 +48,19 @@ def cpu_baseline(w, inputs):
             "sample": f"1 of {w.H} heads, complete fp64 forward+backward ({dt:.1f} s)"}, (O, lse, dQ, dK, dV)
 
 
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary (None if absent)."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 4 and f[0] == "traffic_bytes_per_launch" and f[1] == kernel and f[2] == workload:
+                return int(f[3])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -55,6 +68,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b_32k_G8")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch a plain elementwise copy kernel of known size (256 MiB read, 256 MiB "
+                         "written) so that HBM counters of a profiler run can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU's share of the ring; run with --gpus 1 "
@@ -99,6 +115,11 @@ def main():
             bracket("dq", lambda: B.burst_local_bwd_dq(Q, Ks[j], Vs[j], dO, walk.lse, walk.D, dQ, p, True))
             bracket("dkv", lambda: B.burst_local_bwd_dkv(Q, Ks[j], Vs[j], dO, walk.lse, walk.D, dKs[j], dVs[j], p, False))
 
+    if args.calibration_copy:
+        src = torch.ones(64 * 1024 * 1024, device=dev, dtype=torch.float32)
+        for _ in range(3):
+            dst = src * 1.0                    # one elementwise kernel: reads 256 MiB, writes 256 MiB
+        del src, dst
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
@@ -118,7 +139,8 @@ def main():
     dom = max(avg, key=lambda k: avg[k])
     names = {"fwd": "burst_fwd_mfma_kernel", "dq": "burst_bwd_dq_kernel", "dkv": "burst_bwd_dkv_kernel"}
     roofline = {"bound": "mfma", "kernel": names[dom], "achieved": kern[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": kern[dom]["tflops"] / PEAK_BF16_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": kern[dom]["tflops"] / PEAK_BF16_TFLOPS,
+                "traffic": measured_traffic(names[dom], w.name),
                 "avg_launch_ms": avg[dom],
                 "all_kernels": {names[k]: {"avg_launch_ms": round(kern[k]["avg_ms"], 4),
                                            "tflops": round(kern[k]["tflops"], 1),
