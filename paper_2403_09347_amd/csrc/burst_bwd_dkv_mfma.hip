@@ -30,7 +30,8 @@ constexpr int DKV_LDS_Q = 0;
 constexpr int DKV_LDS_G = DKV_SLOTS * DKV_TILE_BYTES;
 constexpr int DKV_LDS_L = 2 * DKV_SLOTS * DKV_TILE_BYTES;          // -lse * log2(e) per row, 3 slots
 constexpr int DKV_LDS_D = DKV_LDS_L + DKV_SLOTS * DKV_BR * 4;      // D per row, 3 slots
-constexpr int DKV_LDS_BYTES = DKV_LDS_D + DKV_SLOTS * DKV_BR * 4;
+constexpr int DKV_LDS_DUMMY = DKV_LDS_D + DKV_SLOTS * DKV_BR * 4;  // sink of the padding DMA (256 B)
+constexpr int DKV_LDS_BYTES = DKV_LDS_DUMMY + 256;
 
 __global__ void __launch_bounds__(256, 1)
 burst_bwd_dkv_kernel(BwdArgs a) {
@@ -110,38 +111,43 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     auto dma_tile = [&](__amdgpu_buffer_rsrc_t rs, unsigned lds_tile, int il, int tile) __attribute__((always_inline)) {
       dma_b128_to_lds(rs, lds_tile + (unsigned)(wu * 4 + il) * 1024u, tile * DKV_TILE_BYTES + goff[il]);
     };
-    // per-row statistics of a tile, already scaled: threads 0..63 carry -lse*log2(e) (or -inf
-    // for a row that saw nothing: then P = exp2(-inf) = 0), threads 64..127 carry D
-    auto load_rowstat = [&](int t) __attribute__((always_inline)) -> float {
-      float v = 0.f;
-      if (tid < 128) {
-        int row = t * DKV_BR + (tid & 63);
-        if (tid < 64) {
-          float lv = row < a.Nq ? lseh[row] : BURST_NEG_INF;
-          v = (lv == BURST_NEG_INF) ? BURST_NEG_INF : -lv * kLog2e;
-        } else {
-          v = row < a.Nq ? Dh[row] : 0.f;
-        }
-      }
-      return v;
+    // Per-row statistics of a tile travel like the tiles: wavefront 0 DMAs the 64 lse values,
+    // wavefront 1 the 64 D values (rows past Nq read as 0; their Q and dO rows are 0 too, so they
+    // contribute nothing).  One step before use, wavefront 0 rewrites lse in place as
+    // -lse*log2(e), or -inf for a row that saw nothing (then P = exp2(-inf) = 0).  No
+    // compiler-visible global load is left in the loop: its wait would drain the DMA queue.
+    const __amdgpu_buffer_rsrc_t lrs = make_rsrc(lseh, (unsigned)a.Nq * 4u);
+    const __amdgpu_buffer_rsrc_t drs = make_rsrc(Dh, (unsigned)a.Nq * 4u);
+    auto dma_rowstat = [&](int t, int slot) __attribute__((always_inline)) {
+      // every wavefront issues exactly one such load per tile (the wait counts below rely on
+      // it): 0 -> lse, 1 -> D, 2 and 3 -> a dummy copy of lse that nobody reads
+      const unsigned dst = (wu == 0) ? lds0 + DKV_LDS_L + slot * DKV_BR * 4
+                         : (wu == 1) ? lds0 + DKV_LDS_D + slot * DKV_BR * 4 : lds0 + DKV_LDS_DUMMY;
+      dma_b32_to_lds(wu == 1 ? drs : lrs, dst, (t * DKV_BR + lane) * 4);
     };
-    auto store_rowstat = [&](float v, int slot) __attribute__((always_inline)) {
-      if (tid < 64) reinterpret_cast<float*>(smem + DKV_LDS_L)[slot * DKV_BR + tid] = v;
-      else if (tid < 128) reinterpret_cast<float*>(smem + DKV_LDS_D)[slot * DKV_BR + tid - 64] = v;
+    auto scale_rowstat = [&](int slot) __attribute__((always_inline)) {
+      if (tid < 64) {
+        float* ptr = reinterpret_cast<float*>(smem + DKV_LDS_L) + slot * DKV_BR + tid;
+        float lv = *ptr;
+        *ptr = (lv == BURST_NEG_INF) ? BURST_NEG_INF : -lv * kLog2e;
+      }
     };
 
-    // ---- prologue: tiles t_begin, t_begin + 1 into slots 0, 1; statistics of the first into
-    // slot 0, of the second into registers
+    // ---- prologue: tiles t_begin, t_begin + 1 and their statistics into slots 0, 1; the
+    // statistics of the first are scaled right away
 #pragma unroll
-    for (int t = 0; t < 2; t++)
+    for (int t = 0; t < 2; t++) {
 #pragma unroll
       for (int il = 0; il < 4; il++) {
         dma_tile(qrs, lds0 + DKV_LDS_Q + t * DKV_TILE_BYTES, il, t_begin + t);
         dma_tile(grs, lds0 + DKV_LDS_G + t * DKV_TILE_BYTES, il, t_begin + t);
       }
-    store_rowstat(load_rowstat(t_begin), 0);
-    float rstat = load_rowstat(t_begin + 1);
+      dma_rowstat(t_begin + t, t);
+    }
     __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0), lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    scale_rowstat(0);
+    __builtin_amdgcn_s_waitcnt(0x0070);
     __builtin_amdgcn_s_barrier();
 
     const long long wave_first_k = a.k_off + key0;
@@ -168,10 +174,11 @@ burst_bwd_dkv_kernel(BwdArgs a) {
         for (int rb = 0; rb < 2; rb++)
 #pragma unroll
           for (int r = 0; r < 16; r++) { s[rb][r] = 0.f; dp[rb][r] = 0.f; }
-        // A-operand read j (0..31): rb = j / 16, then 8 Q fragments, then 8 dO fragments
+        // A-operand read j (0..31): rb = j / 16, ks = (j / 2) % 8, even: Q fragment (for S), odd:
+        // dO fragment (for dP).  S and dP alternate so that no MFMA waits for its predecessor.
         bf16x8 fq[RING];
         auto issue_read = [&](int j) __attribute__((always_inline)) {
-          const int rb = j >> 4, isg = (j >> 3) & 1, ks = j & 7;
+          const int rb = j >> 4, isg = j & 1, ks = (j >> 1) & 7;
           fq[j % RING] = lds_read_b128(isg ? gl : ql, rb * 32 * 256 + (abase ^ (ks << 5)));
         };
         // transposed fragment j (0..31): rb = j / 16, u = (j / 8) % 2, db = (j / 2) % 4, then
@@ -225,11 +232,11 @@ burst_bwd_dkv_kernel(BwdArgs a) {
 #pragma unroll
         for (int j = 0; j < LEAD; j++) issue_read(j);
         __builtin_amdgcn_sched_barrier(0);
-        // ---- phases 1, 2: S and dP (slice i: rb = i / 16, first 8 S then 8 dP); in phase 2 the
-        // P / dS pairs of row block 0 ride along (one pair every second slice)
+        // ---- phases 1, 2: S and dP (slice i: rb = i / 16, ks = (i / 2) % 8, even S, odd dP); in
+        // phase 2 the P / dS pairs of row block 0 ride along (one pair every second slice)
 #pragma unroll
         for (int i = 0; i < 32; i++) {
-          const int rb = i >> 4, isg = (i >> 3) & 1, ks = i & 7;
+          const int rb = i >> 4, isg = i & 1, ks = (i >> 1) & 7;
           if (i == 16 && need_mask) mask_block(0);
           if (i + LEAD < 32) issue_read(i + LEAD);
           if (i + TLEAD >= 32) issue_tread(i + TLEAD - 32);
@@ -256,18 +263,18 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-      // ---- statistics of tile t + 1 -> LDS, DMA of tile t + 2, statistics of tile t + 2 ->
-      // registers.  (The register -> LDS write waits for everything this wavefront loaded
-      // earlier, i.e. the DMA issued one step ago, which has had a whole step to land.)
-      store_rowstat(rstat, slot1);
+      // ---- scale the statistics of tile t + 1 (landed during the previous step), DMA tile
+      // t + 2 and its statistics.  The newest loads may stay in flight across the barrier.
+      __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): the previous step's DMA (old by now)
+      scale_rowstat(slot1);
 #pragma unroll
       for (int il = 0; il < 4; il++) {
         dma_tile(qrs, lds0 + DKV_LDS_Q + slot2 * DKV_TILE_BYTES, il, t + 2);
         dma_tile(grs, lds0 + DKV_LDS_G + slot2 * DKV_TILE_BYTES, il, t + 2);
       }
-      rstat = load_rowstat(t + 2);
+      dma_rowstat(t + 2, slot2);
       slot = slot1;
-      __builtin_amdgcn_s_waitcnt(0x0079);          // vmcnt(9): tile t + 1 has landed; lgkmcnt(0)
+      __builtin_amdgcn_s_waitcnt(0x0079);          // vmcnt(9): everything but the 9 loads just issued; lgkmcnt(0)
       __builtin_amdgcn_s_barrier();
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): no DMA may outlive the loop

@@ -101,6 +101,11 @@ __device__ __forceinline__ void dma_b128_to_lds(__amdgpu_buffer_rsrc_t rsrc, uns
   asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                :: "s"(lds_base), "v"(voffset), "s"(rsrc) : "memory", "m0");
 }
+// Same with 32 bits per lane: lane i's dword lands at lds_base + 4*i.
+__device__ __forceinline__ void dma_b32_to_lds(__amdgpu_buffer_rsrc_t rsrc, unsigned lds_base, int voffset) {
+  asm volatile("s_mov_b32 m0, %0\n\tbuffer_load_dword %1, %2, 0 offen lds"
+               :: "s"(lds_base), "v"(voffset), "s"(rsrc) : "memory", "m0");
+}
 // LDS byte address of a pointer into the workgroup's dynamic shared memory.
 __device__ __forceinline__ unsigned lds_addr(const void* p) {
   return (unsigned)(size_t)(__attribute__((address_space(3))) const char*)(const char*)p;
