@@ -1,0 +1,62 @@
+"""Host-side logic that needs no GPU: workload table, FLOP accounting, bench argument handling."""
+import json
+import math
+import os
+import subprocess
+import sys
+
+import numpy as np
+
+from paper_2403_09347_amd import workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_workload_table_matches_the_benchmark_configurations():
+    names = [w.name for w in workloads.WORKLOADS]
+    assert len(names) == 5 and len(set(names)) == 5
+    w0, w1, w2, w3, w4 = workloads.WORKLOADS
+    assert (w0.H, w0.d, w0.Nq, w0.G, w0.Nc, w0.dtype, w0.causal) == (1, 64, 256, 4, 256, "f32", False)
+    assert (w1.H, w1.d, w1.Nq, w1.G, w1.Nc, w1.dtype, w1.causal) == (32, 128, 4096, 8, 4096, "bf16", False)
+    assert (w2.G, w2.causal, w2.q_off) == (32, True, 31 * 4096)
+    assert (w3.H, w3.Nq, w3.G * w3.Nc) == (40, 16384, 131072)
+    assert (w4.Nq, w4.G * w4.Nc) == (32768, 1 << 20)
+    assert all(abs(w.scale - 1 / math.sqrt(w.d)) < 1e-12 for w in workloads.WORKLOADS)
+
+
+def test_flop_accounting():
+    w1 = workloads.by_name("llama7b_32k_G8")
+    assert w1.visible_pairs_per_head() == 4096 * 32768
+    assert abs(w1.fwd_flops() - 2.199e12) / 2.199e12 < 1e-3
+    assert abs(w1.fwd_flops() + w1.bwd_flops() - 7.697e12) / 7.697e12 < 1e-3
+    w2 = workloads.by_name("llama7b_128k_G32_rank31_causal")
+    # rank 31 sees 31 full chunks plus the lower triangle (diagonal included) of its own
+    assert w2.visible_pairs_per_head() == 4096 * 126976 + 4096 * 4097 // 2
+    # brute force on a small causal case
+    small = workloads.Workload("s", 1, 1, 8, 5, 2, 4, "f32", True, 2, 0)
+    vis = sum(1 for r in range(5) for c in range(8) if c <= 2 + r)
+    assert small.visible_pairs_per_head() == vis
+
+
+def test_inputs_are_seeded_and_rounded_once():
+    w0 = workloads.WORKLOADS[0]
+    a = workloads.make_inputs(w0, "cpu")
+    b = workloads.make_inputs(w0, "cpu")
+    assert all((x == y).all() for x, y in zip(a["K"], b["K"])) and (a["Q"] == b["Q"]).all()
+    c = workloads.make_case(1, 2, 128, 10, [3, 4], "bf16", seed=1)
+    assert c["Q"].dtype.__str__() == "torch.bfloat16" and c["k_offs"] == [0, 3]
+    assert abs(float(a["Q"].double().std()) - 1.0) < 0.05
+
+
+def test_bench_refuses_more_than_one_gpu():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_bench_reads_measured_traffic_from_profiles():
+    sys.path.insert(0, ROOT)
+    import bench
+    assert bench.measured_traffic("no_such_kernel", "llama7b_32k_G8") is None
+    v = bench.measured_traffic("burst_bwd_dkv_kernel", "llama7b_32k_G8")
+    assert v is None or v > 100e6
