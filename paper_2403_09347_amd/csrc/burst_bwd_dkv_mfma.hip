@@ -197,19 +197,25 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           lq[q4 & 1] = *reinterpret_cast<const f32x4*>(lp + rb * 32 + 8 * q4 + 4 * h);
           dq4[q4 & 1] = *reinterpret_cast<const f32x4*>(dp_ + rb * 32 + 8 * q4 + 4 * h);
         };
-        // P and dS of two scores: register pair (r, r+1) of row block rb = rows 8*(r/4)+4h+r%4
-        auto pds_pair = [&](int rb, int pidx) __attribute__((always_inline)) {   // pidx 0..7
+        // P and dS of two scores: register pair (r, r+1) of row block rb = rows 8*(r/4)+4h+r%4.
+        // The work is cut in two halves of equal VALU cost, one per MFMA slice: an in-order
+        // wavefront hides only what it issues between two of its own MFMAs.
+        float ph0, ph1;
+        auto pds_half0 = [&](int rb, int pidx) __attribute__((always_inline)) {  // pidx 0..7
+          const int r = 2 * pidx, q4 = r >> 2;
+          ph0 = fast_exp2(__builtin_fmaf(s[rb][r], a.c, lq[q4 & 1][r & 3]));
+          ph1 = fast_exp2(__builtin_fmaf(s[rb][r + 1], a.c, lq[q4 & 1][(r & 3) + 1]));
+          asm volatile("" : "+v"(ph0), "+v"(ph1));   // keep the arithmetic in this slice
+        };
+        auto pds_half1 = [&](int rb, int pidx) __attribute__((always_inline)) {
           const int r = 2 * pidx, q4 = r >> 2, u = r >> 3, t8 = r & 7;
-          const float s0 = s[rb][r], s1 = s[rb][r + 1];
-          float p0 = fast_exp2(__builtin_fmaf(s0, a.c, lq[q4 & 1][r & 3]));
-          float p1 = fast_exp2(__builtin_fmaf(s1, a.c, lq[q4 & 1][(r & 3) + 1]));
-          float d0 = p0 * (dp[rb][r] - dq4[q4 & 1][r & 3]);
-          float d1 = p1 * (dp[rb][r + 1] - dq4[q4 & 1][(r & 3) + 1]);
+          float d0 = ph0 * (dp[rb][r] - dq4[q4 & 1][r & 3]);
+          float d1 = ph1 * (dp[rb][r + 1] - dq4[q4 & 1][(r & 3) + 1]);
           bf16x2 pk, dk2;
-          pk[0] = (bf16)p0; pk[1] = (bf16)p1;
+          pk[0] = (bf16)ph0; pk[1] = (bf16)ph1;
           dk2[0] = (bf16)d0; dk2[1] = (bf16)d1;
-          // keep the pair's arithmetic in this slice (its only consumers are MFMAs two phases
-          // later; without an anchor the compiler sinks it there, behind the mask branches)
+          // (the only consumers are MFMAs two phases later; without an anchor the compiler sinks
+          // the arithmetic there, behind the mask branches)
           unsigned pu = __builtin_bit_cast(unsigned, pk), du = __builtin_bit_cast(unsigned, dk2);
           asm volatile("" : "+v"(pu), "+v"(du));
           pk = __builtin_bit_cast(bf16x2, pu); dk2 = __builtin_bit_cast(bf16x2, du);
@@ -244,7 +250,7 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           if (i >= 16 && (i & 3) == 1 && i < 28) issue_stat(0, ((i - 16) >> 2) + 1);
           if (isg) dp[rb] = mfma32(fq[i % RING], vf[ks], dp[rb]);
           else s[rb] = mfma32(fq[i % RING], kf[ks], s[rb]);
-          if (i >= 16 && (i & 1)) pds_pair(0, (i - 16) >> 1);
+          if (i >= 16) { if (i & 1) pds_half1(0, (i - 16) >> 1); else pds_half0(0, (i - 16) >> 1); }
           if (i == 30) issue_stat(1, 0);
           __builtin_amdgcn_sched_barrier(0);
         }
@@ -259,7 +265,7 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           const bf16x8 bt = cat4(tq[i % TRING][0], tq[i % TRING][1]);
           if (isk) mfma32_acc(dk[db], dsf[rb][u], bt);
           else mfma32_acc(dv[db], pf[rb][u], bt);
-          if (i < 16 && (i & 1)) pds_pair(1, i >> 1);
+          if (i < 16) { if (i & 1) pds_half1(1, i >> 1); else pds_half0(1, i >> 1); }
           __builtin_amdgcn_sched_barrier(0);
         }
       }
