@@ -28,9 +28,10 @@ constexpr int DKV_TILE_BYTES = DKV_BR * 256;
 constexpr int DKV_SLOTS = 3;
 constexpr int DKV_LDS_Q = 0;
 constexpr int DKV_LDS_G = DKV_SLOTS * DKV_TILE_BYTES;
-constexpr int DKV_LDS_L = 2 * DKV_SLOTS * DKV_TILE_BYTES;          // -lse * log2(e) per row, 3 slots
-constexpr int DKV_LDS_D = DKV_LDS_L + DKV_SLOTS * DKV_BR * 4;      // D per row, 3 slots
-constexpr int DKV_LDS_DUMMY = DKV_LDS_D + DKV_SLOTS * DKV_BR * 4;  // sink of the padding DMA (256 B)
+constexpr int DKV_STAT_SLOTS = 4;     // row statistics run one tile further ahead than the tiles
+constexpr int DKV_LDS_L = 2 * DKV_SLOTS * DKV_TILE_BYTES;              // -lse * log2(e) per row
+constexpr int DKV_LDS_D = DKV_LDS_L + DKV_STAT_SLOTS * DKV_BR * 4;     // -D per row
+constexpr int DKV_LDS_DUMMY = DKV_LDS_D + DKV_STAT_SLOTS * DKV_BR * 4; // sink of the padding DMA (256 B)
 constexpr int DKV_LDS_BYTES = DKV_LDS_DUMMY + 256;
 
 __global__ void __launch_bounds__(256, 1)
@@ -71,7 +72,10 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     for (int r = 0; r < 16; r++) { dk[db][r] = 0.f; dv[db][r] = 0.f; }
 
   if (t_begin < ntiles_all) {
-    // K, V fragments (B operands: lane = key lr, 8 consecutive d)
+    // K, V fragments (B operands: lane = key lr, 8 consecutive d).  K is multiplied by
+    // c = scale*log2(e) here, once (rounded to bf16 again: a relative perturbation of 2^-9 per
+    // element, below the rounding P gets anyway), so that the S accumulator, started at
+    // -lse*log2(e), directly holds the exponent of P = exp2(c S - lse log2 e).
     bf16x8 kf[8], vf[8];
     {
       const int key = key0 + lr;
@@ -82,6 +86,8 @@ burst_bwd_dkv_kernel(BwdArgs a) {
         for (int t = 0; t < 8; t++) z[t] = (bf16)0.0f;
         kf[ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Kh + (size_t)key * 128 + ks * 16 + h * 8) : z;
         vf[ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Vh + (size_t)key * 128 + ks * 16 + h * 8) : z;
+#pragma unroll
+        for (int t = 0; t < 8; t++) kf[ks][t] = (bf16)((float)kf[ks][t] * a.c);
       }
     }
     // LDS addressing inside a 64-row tile.  A operands (128-bit): row rb*32 + lr, granule
@@ -113,9 +119,11 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     };
     // Per-row statistics of a tile travel like the tiles: wavefront 0 DMAs the 64 lse values,
     // wavefront 1 the 64 D values (rows past Nq read as 0; their Q and dO rows are 0 too, so they
-    // contribute nothing).  One step before use, wavefront 0 rewrites lse in place as
-    // -lse*log2(e), or -inf for a row that saw nothing (then P = exp2(-inf) = 0).  No
-    // compiler-visible global load is left in the loop: its wait would drain the DMA queue.
+    // contribute nothing).  Two steps before use, wavefront 0 rewrites lse in place as
+    // -lse*log2(e), or -inf for a row that saw nothing (then P = exp2(-inf) = 0), and wavefront
+    // 1 rewrites D as -D: the S and dP accumulators START at these values, which removes the
+    // subtraction from the per-element vector work.  No compiler-visible global load is left
+    // in the loop: its wait would drain the DMA queue.
     const __amdgpu_buffer_rsrc_t lrs = make_rsrc(lseh, (unsigned)a.Nq * 4u);
     const __amdgpu_buffer_rsrc_t drs = make_rsrc(Dh, (unsigned)a.Nq * 4u);
     auto dma_rowstat = [&](int t, int slot) __attribute__((always_inline)) {
@@ -130,11 +138,14 @@ burst_bwd_dkv_kernel(BwdArgs a) {
         float* ptr = reinterpret_cast<float*>(smem + DKV_LDS_L) + slot * DKV_BR + tid;
         float lv = *ptr;
         *ptr = (lv == BURST_NEG_INF) ? BURST_NEG_INF : -lv * kLog2e;
+      } else if (tid < 128) {
+        float* ptr = reinterpret_cast<float*>(smem + DKV_LDS_D) + slot * DKV_BR + (tid - 64);
+        *ptr = -*ptr;
       }
     };
 
-    // ---- prologue: tiles t_begin, t_begin + 1 and their statistics into slots 0, 1; the
-    // statistics of the first are scaled right away
+    // ---- prologue: tiles t_begin, t_begin + 1 into tile slots 0, 1; the statistics of tiles
+    // t_begin .. t_begin + 2 into statistic slots 0 .. 2, the first two scaled right away
 #pragma unroll
     for (int t = 0; t < 2; t++) {
 #pragma unroll
@@ -142,11 +153,13 @@ burst_bwd_dkv_kernel(BwdArgs a) {
         dma_tile(qrs, lds0 + DKV_LDS_Q + t * DKV_TILE_BYTES, il, t_begin + t);
         dma_tile(grs, lds0 + DKV_LDS_G + t * DKV_TILE_BYTES, il, t_begin + t);
       }
-      dma_rowstat(t_begin + t, t);
     }
+#pragma unroll
+    for (int t = 0; t < 3; t++) dma_rowstat(t_begin + t, t);
     __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0), lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
     scale_rowstat(0);
+    scale_rowstat(1);
     __builtin_amdgcn_s_waitcnt(0x0070);
     __builtin_amdgcn_s_barrier();
 
@@ -156,24 +169,38 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     constexpr int LEAD = 4, RING = LEAD + 2;       // A-operand reads run LEAD slices ahead
     constexpr int TLEAD = 3, TRING = TLEAD + 1;    // transposed fragments run TLEAD slices ahead
 
+    // S and dP accumulators of the two row blocks.  They start at -lse*log2(e) and -D of their
+    // rows (register r of a block = row 8*(r/4) + 4h + r%4: four 128-bit broadcast reads per
+    // block and statistic, straight into the accumulator registers).  Block 0 of the next tile is
+    // loaded while the current tile's last phases run.
+    f32x16 s[2], dp[2];
+    auto load_init = [&](int rb, const float* lrow, const float* drow) __attribute__((always_inline)) {
+#pragma unroll
+      for (int q4 = 0; q4 < 4; q4++) {
+        const f32x4 lv = *reinterpret_cast<const f32x4*>(lrow + rb * 32 + 8 * q4 + 4 * h);
+        const f32x4 dv = *reinterpret_cast<const f32x4*>(drow + rb * 32 + 8 * q4 + 4 * h);
+#pragma unroll
+        for (int j = 0; j < 4; j++) { s[rb][4 * q4 + j] = lv[j]; dp[rb][4 * q4 + j] = dv[j]; }
+      }
+    };
+    load_init(0, reinterpret_cast<const float*>(smem + DKV_LDS_L), reinterpret_cast<const float*>(smem + DKV_LDS_D));
+
     int slot = 0;
     for (int t = t_begin; t < ntiles_all; t++) {
       const int slot1 = (slot == DKV_SLOTS - 1) ? 0 : slot + 1;
       const int slot2 = (slot1 == DKV_SLOTS - 1) ? 0 : slot1 + 1;
+      const int n = t - t_begin;                       // statistic slots: n & 3 holds tile t
       const char* ql = smem + DKV_LDS_Q + slot * DKV_TILE_BYTES;
       const char* gl = smem + DKV_LDS_G + slot * DKV_TILE_BYTES;
-      const float* lp = reinterpret_cast<const float*>(smem + DKV_LDS_L) + slot * DKV_BR;
-      const float* dp_ = reinterpret_cast<const float*>(smem + DKV_LDS_D) + slot * DKV_BR;
+      const float* lp = reinterpret_cast<const float*>(smem + DKV_LDS_L) + (n & 3) * DKV_BR;
+      const float* dp_ = reinterpret_cast<const float*>(smem + DKV_LDS_D) + (n & 3) * DKV_BR;
+      const float* lp_next = reinterpret_cast<const float*>(smem + DKV_LDS_L) + ((n + 1) & 3) * DKV_BR;
+      const float* dp_next = reinterpret_cast<const float*>(smem + DKV_LDS_D) + ((n + 1) & 3) * DKV_BR;
       const long long tile_first_q = a.q_off + (long long)t * DKV_BR;
       // (no branch around the MFMA phases: the AGPR-pinned accumulators must not become phi
       // values, the allocator would shuttle them through VGPRs every iteration)
       const bool need_mask = a.causal && (wave_last_k > tile_first_q);
       {
-        f32x16 s[2], dp[2];
-#pragma unroll
-        for (int rb = 0; rb < 2; rb++)
-#pragma unroll
-          for (int r = 0; r < 16; r++) { s[rb][r] = 0.f; dp[rb][r] = 0.f; }
         // A-operand read j (0..31): rb = j / 16, ks = (j / 2) % 8, even: Q fragment (for S), odd:
         // dO fragment (for dP).  S and dP alternate so that no MFMA waits for its predecessor.
         bf16x8 fq[RING];
@@ -192,25 +219,20 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           tq[j % TRING][1] = lds_read_tr(base, off + taddr[db][1]);
         };
         bf16x8 pf[2][2], dsf[2][2];   // [row block][16-row group]: A operands of dV, dK
-        f32x4 lq[2], dq4[2];          // row statistics of 4 consecutive rows, one group ahead
-        auto issue_stat = [&](int rb, int q4) __attribute__((always_inline)) {
-          lq[q4 & 1] = *reinterpret_cast<const f32x4*>(lp + rb * 32 + 8 * q4 + 4 * h);
-          dq4[q4 & 1] = *reinterpret_cast<const f32x4*>(dp_ + rb * 32 + 8 * q4 + 4 * h);
-        };
         // P and dS of two scores: register pair (r, r+1) of row block rb = rows 8*(r/4)+4h+r%4.
-        // The work is cut in two halves of equal VALU cost, one per MFMA slice: an in-order
-        // wavefront hides only what it issues between two of its own MFMAs.
+        // The work is cut in two halves, one per MFMA slice: an in-order wavefront hides only
+        // what it issues between two of its own MFMAs.
         float ph0, ph1;
         auto pds_half0 = [&](int rb, int pidx) __attribute__((always_inline)) {  // pidx 0..7
-          const int r = 2 * pidx, q4 = r >> 2;
-          ph0 = fast_exp2(__builtin_fmaf(s[rb][r], a.c, lq[q4 & 1][r & 3]));
-          ph1 = fast_exp2(__builtin_fmaf(s[rb][r + 1], a.c, lq[q4 & 1][(r & 3) + 1]));
+          const int r = 2 * pidx;
+          ph0 = fast_exp2(s[rb][r]);
+          ph1 = fast_exp2(s[rb][r + 1]);
           asm volatile("" : "+v"(ph0), "+v"(ph1));   // keep the arithmetic in this slice
         };
         auto pds_half1 = [&](int rb, int pidx) __attribute__((always_inline)) {
-          const int r = 2 * pidx, q4 = r >> 2, u = r >> 3, t8 = r & 7;
-          float d0 = ph0 * (dp[rb][r] - dq4[q4 & 1][r & 3]);
-          float d1 = ph1 * (dp[rb][r + 1] - dq4[q4 & 1][(r & 3) + 1]);
+          const int r = 2 * pidx, u = r >> 3, t8 = r & 7;
+          float d0 = ph0 * dp[rb][r];
+          float d1 = ph1 * dp[rb][r + 1];
           bf16x2 pk, dk2;
           pk[0] = (bf16)ph0; pk[1] = (bf16)ph1;
           dk2[0] = (bf16)d0; dk2[1] = (bf16)d1;
@@ -246,12 +268,10 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           if (i == 16 && need_mask) mask_block(0);
           if (i + LEAD < 32) issue_read(i + LEAD);
           if (i + TLEAD >= 32) issue_tread(i + TLEAD - 32);
-          if (i == 14) issue_stat(0, 0);
-          if (i >= 16 && (i & 3) == 1 && i < 28) issue_stat(0, ((i - 16) >> 2) + 1);
+          if (i == 2) load_init(1, lp, dp_);
           if (isg) dp[rb] = mfma32(fq[i % RING], vf[ks], dp[rb]);
           else s[rb] = mfma32(fq[i % RING], kf[ks], s[rb]);
           if (i >= 16) { if (i & 1) pds_half1(0, (i - 16) >> 1); else pds_half0(0, (i - 16) >> 1); }
-          if (i == 30) issue_stat(1, 0);
           __builtin_amdgcn_sched_barrier(0);
         }
         // ---- phases 3, 4: dV += P^T dO, dK += dS^T Q (slice i: rb = i / 16, u = (i / 8) % 2,
@@ -261,7 +281,7 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           const int rb = i >> 4, u = (i >> 3) & 1, db = (i >> 1) & 3, isk = i & 1;
           if (i == 0 && need_mask) mask_block(1);
           if (i + TLEAD < 32) issue_tread(i + TLEAD);
-          if (i < 16 && (i & 3) == 1 && i < 12) issue_stat(1, (i >> 2) + 1);
+          if (i == 4) load_init(0, lp_next, dp_next);     // block 0 of tile t + 1
           const bf16x8 bt = cat4(tq[i % TRING][0], tq[i % TRING][1]);
           if (isk) mfma32_acc(dk[db], dsf[rb][u], bt);
           else mfma32_acc(dv[db], pf[rb][u], bt);
@@ -272,13 +292,13 @@ burst_bwd_dkv_kernel(BwdArgs a) {
       // ---- scale the statistics of tile t + 1 (landed during the previous step), DMA tile
       // t + 2 and its statistics.  The newest loads may stay in flight across the barrier.
       __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): the previous step's DMA (old by now)
-      scale_rowstat(slot1);
+      scale_rowstat((n + 2) & 3);
 #pragma unroll
       for (int il = 0; il < 4; il++) {
         dma_tile(qrs, lds0 + DKV_LDS_Q + slot2 * DKV_TILE_BYTES, il, t + 2);
         dma_tile(grs, lds0 + DKV_LDS_G + slot2 * DKV_TILE_BYTES, il, t + 2);
       }
-      dma_rowstat(t + 2, slot2);
+      dma_rowstat(t + 3, (n + 3) & 3);
       slot = slot1;
       __builtin_amdgcn_s_waitcnt(0x0079);          // vmcnt(9): everything but the 9 loads just issued; lgkmcnt(0)
       __builtin_amdgcn_s_barrier();
