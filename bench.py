@@ -53,6 +53,40 @@ def cpu_baseline(w, inputs, budget_s=15.0, max_heads=8):
             "sample": f"{heads} of {w.H} heads, complete fp64 forward+backward ({dt:.1f} s)"}
 
 
+def overlap_measurement(w, inp, source, reps):
+    """Forward walk of the workload three ways: chunks resident (compute only), the chunk copies
+    alone, and the double-buffered walk that overlaps them.  Times in ms, median of `reps`."""
+    import statistics
+    import torch
+    from paper_2403_09347_amd.harness import DoubleBufferedWalk, RingWalk
+    Q, Ks, Vs = inp["Q"], inp["K"], inp["V"]
+    k_offs = [w.k_off(j) for j in range(w.G)]
+    if source == "pinned_host":
+        src_K = [k.cpu().pin_memory() for k in Ks]
+        src_V = [v.cpu().pin_memory() for v in Vs]
+    else:
+        src_K, src_V = Ks, Vs
+    plain = RingWalk(Q, w.scale, w.causal, w.q_off)
+    db = DoubleBufferedWalk(Q, w.scale, w.causal, w.q_off, max_chunk_rows=w.Nc)
+
+    def timed(fn):
+        ts = []
+        for _ in range(reps + 1):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            ts.append((time.perf_counter() - t0) * 1e3)
+        return statistics.median(ts[1:])
+    t_compute = timed(lambda: plain.forward(Ks, Vs, k_offs))
+    t_copy = timed(lambda: db.copies_only(src_K, src_V))
+    t_pipe = timed(lambda: db.forward(src_K, src_V, k_offs))
+    chunk_bytes = 2 * Ks[0].numel() * Ks[0].element_size()
+    return {"source": source, "compute_only_ms": t_compute, "copies_only_ms": t_copy, "double_buffered_ms": t_pipe,
+            "overlap_efficiency": max(t_compute, t_copy) / t_pipe,
+            "copy_GBps": w.G * chunk_bytes / (t_copy * 1e-3) / 1e9, "chunk_MiB": chunk_bytes / 2**20}
+
+
 def measured_traffic(kernel, workload):
     """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary (None if absent)."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
@@ -73,6 +107,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b_32k_G8")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--overlap", choices=["hbm", "pinned_host"], default=None,
+                    help="also time the double-buffered chunk walk (paper Sec. 2.5): chunks are copied from a source "
+                         "pool of that kind into two receive buffers on a second stream while the previous chunk "
+                         "computes; adds an 'overlap' object to the JSON line")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch a plain elementwise copy kernel of known size (256 MiB read, 256 MiB "
                          "written) so that HBM counters of a profiler run can be scaled")
@@ -168,6 +206,8 @@ def main():
         "fwd_kernels_ms": fwd_ms, "bwd_kernels_ms": bwd_ms,
         "roofline": roofline,
     }
+    if args.overlap:
+        out["overlap"] = overlap_measurement(w, inp, args.overlap, max(3, args.steps // 2))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(out))

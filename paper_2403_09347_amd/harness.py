@@ -1,6 +1,9 @@
-"""Single-GPU harness: walks G key/value chunks resident in HBM, one library call per chunk,
-in the order a device of the ring would receive them (paper Alg. 1 / Alg. 2 loops with the
-ring step replaced by taking the next resident chunk).  Host-side orchestration only."""
+"""Single-GPU harness: walks G key/value chunks, one library call per chunk, in the order a
+device of the ring would receive them (paper Alg. 1 / Alg. 2 loops with the ring step replaced
+by taking the next chunk).  Two walks: chunks already resident (plain), and chunks fetched from
+a source pool through two receive buffers on a second stream while the previous chunk is being
+computed (the double buffer of paper Sec. 2.5 / Alg. 3, with a copy standing in for the ring
+transfer).  Host-side orchestration only: every arithmetic step is a library call."""
 import torch
 
 from . import binding as B
@@ -61,3 +64,102 @@ class RingWalk:
                               dQ, dKs[j], dVs[j], self.params(Ks[j].shape[2], k_offs[j]),
                               accumulate_dq=True, accumulate_dkv=False)
         return dQ, dKs, dVs
+
+
+class DoubleBufferedWalk(RingWalk):
+    """Paper Sec. 2.5 / Alg. 3 on one GPU: chunk j+1 is copied from its source (another HBM
+    allocation, or pinned host memory as a slow link) into the alternate receive buffer on a
+    copy stream while chunk j is computed on the caller's stream.  The copy of chunk j+1
+    starts when the local attention of chunk j starts and may only overwrite a buffer whose
+    chunk (j-1) has been consumed; the computation of chunk j waits for its copy.  All streams
+    have the default priority."""
+
+    def __init__(self, Q, scale, causal=False, q_off=0, max_chunk_rows=None):
+        super().__init__(Q, scale, causal, q_off)
+        self.copy_stream = torch.cuda.Stream(device=Q.device)
+        self.max_rows = max_chunk_rows
+        self._bufs = None
+
+    def _buffers(self, rows):
+        n = self.Bt * self.H * rows * self.d
+        if self._bufs is None or self._bufs[0][0].numel() < n:
+            mk = lambda: torch.empty(n, device=self.Q.device, dtype=self.Q.dtype)
+            self._bufs = [(mk(), mk()), (mk(), mk())]
+        return self._bufs
+
+    def _view(self, flat, rows):
+        return flat[: self.Bt * self.H * rows * self.d].view(self.Bt, self.H, rows, self.d)
+
+    def _fetch(self, j, src_Ks, src_Vs, ready, done):
+        rows = src_Ks[j].shape[2]
+        kb, vb = self._bufs[j % 2]
+        with torch.cuda.stream(self.copy_stream):
+            if j >= 2:
+                self.copy_stream.wait_event(done[j - 2])       # the buffer's previous chunk is consumed
+            self._view(kb, rows).copy_(src_Ks[j], non_blocking=True)
+            self._view(vb, rows).copy_(src_Vs[j], non_blocking=True)
+            ready[j].record(self.copy_stream)
+        return self._view(kb, rows), self._view(vb, rows)
+
+    def forward(self, src_Ks, src_Vs, k_offs, order=None):
+        idx = list(range(len(src_Ks))) if order is None else list(order)
+        Ks, Vs, offs = [src_Ks[j] for j in idx], [src_Vs[j] for j in idx], [k_offs[j] for j in idx]
+        G = len(Ks)
+        main = torch.cuda.current_stream(self.Q.device)
+        self._buffers(self.max_rows or max(k.shape[2] for k in Ks))
+        ready = [torch.cuda.Event() for _ in range(G)]
+        done = [torch.cuda.Event() for _ in range(G)]
+        self.copy_stream.wait_stream(main)                       # sources are complete
+        self.init()
+        nxt = self._fetch(0, Ks, Vs, ready, done) if G else None
+        for j in range(G):
+            cur = nxt
+            if j + 1 < G:
+                nxt = self._fetch(j + 1, Ks, Vs, ready, done)    # issued as chunk j's attention starts
+            main.wait_event(ready[j])
+            self.step(cur[0], cur[1], offs[j])
+            done[j].record(main)
+        return self.finalize()
+
+    def backward(self, src_Ks, src_Vs, k_offs, dO, dQ=None, dKs=None, dVs=None, use_D=True):
+        """Same pipeline for Alg. 2 with the query slice pinned: K/V chunks stream in, each
+        chunk's dK/dV is written to its destination as soon as it is complete."""
+        dev = self.Q.device
+        G = len(src_Ks)
+        main = torch.cuda.current_stream(dev)
+        if dQ is None:
+            dQ = torch.zeros((self.Bt, self.H, self.Nq, self.d), device=dev, dtype=torch.float32)
+        if dKs is None:
+            dKs = [torch.empty(tuple(K.shape), device=dev, dtype=torch.float32) for K in src_Ks]
+            dVs = [torch.empty(tuple(V.shape), device=dev, dtype=torch.float32) for V in src_Vs]
+        self._buffers(self.max_rows or max(k.shape[2] for k in src_Ks))
+        ready = [torch.cuda.Event() for _ in range(G)]
+        done = [torch.cuda.Event() for _ in range(G)]
+        self.copy_stream.wait_stream(main)
+        if use_D:
+            self.prepare(dO)
+        nxt = self._fetch(0, src_Ks, src_Vs, ready, done) if G else None
+        for j in range(G):
+            cur = nxt
+            if j + 1 < G:
+                nxt = self._fetch(j + 1, src_Ks, src_Vs, ready, done)
+            main.wait_event(ready[j])
+            B.burst_local_bwd(self.Q, cur[0], cur[1], self.O, dO, self.lse, self.D if use_D else None,
+                              dQ, dKs[j], dVs[j], self.params(cur[0].shape[2], k_offs[j]),
+                              accumulate_dq=True, accumulate_dkv=False)
+            done[j].record(main)
+        return dQ, dKs, dVs
+
+    def copies_only(self, src_Ks, src_Vs):
+        """The transfers alone, back to back on the copy stream (for the overlap measurement)."""
+        G = len(src_Ks)
+        self._buffers(self.max_rows or max(k.shape[2] for k in src_Ks))
+        ready = [torch.cuda.Event() for _ in range(G)]
+        self.copy_stream.wait_stream(torch.cuda.current_stream(self.Q.device))
+        for j in range(G):
+            rows = src_Ks[j].shape[2]
+            kb, vb = self._bufs[j % 2]
+            with torch.cuda.stream(self.copy_stream):
+                self._view(kb, rows).copy_(src_Ks[j], non_blocking=True)
+                self._view(vb, rows).copy_(src_Vs[j], non_blocking=True)
+        torch.cuda.current_stream(self.Q.device).wait_stream(self.copy_stream)

@@ -6,7 +6,7 @@ import torch
 from oracle import burst_oracle as orc
 from paper_2403_09347_amd import binding as B
 from paper_2403_09347_amd import workloads
-from paper_2403_09347_amd.harness import RingWalk
+from paper_2403_09347_amd.harness import DoubleBufferedWalk, RingWalk
 from gpu_util import check, compare_all_heads, f64, head_inputs
 
 pytestmark = pytest.mark.gpu
@@ -200,6 +200,32 @@ def test_checkpoint_resume_and_determinism_are_bitwise():
     O2, lse2 = w2.finalize()
     torch.cuda.synchronize()
     assert torch.equal(O2, keep[0]) and torch.equal(lse2, keep[1])
+
+
+@pytest.mark.parametrize("source", ["hbm", "pinned_host"])
+def test_double_buffered_walk_is_bitwise_the_plain_walk(source):
+    """Paper Sec. 2.5 / Alg. 3: fetching chunk j+1 into the alternate buffer on a second stream while
+    chunk j computes must not change a single bit of the results (forward and backward)."""
+    case = workloads.make_case(B=1, H=4, d=128, Nq=384, chunk_rows=[256, 192, 256, 128, 256], dtype="bf16", seed=43,
+                               device=DEV, causal=True, q_off=700)
+    plain = RingWalk(case["Q"], case["scale"], True, case["q_off"])
+    O0, lse0 = plain.forward(case["K"], case["V"], case["k_offs"])
+    dQ0, dKs0, dVs0 = plain.backward(case["K"], case["V"], case["k_offs"], case["dO"])
+    torch.cuda.synchronize()
+    if source == "pinned_host":
+        src_K = [k.cpu().pin_memory() for k in case["K"]]
+        src_V = [v.cpu().pin_memory() for v in case["V"]]
+    else:
+        src_K = [k.clone() for k in case["K"]]
+        src_V = [v.clone() for v in case["V"]]
+    for rep in range(2):                                  # second pass reuses the receive buffers
+        db = DoubleBufferedWalk(case["Q"], case["scale"], True, case["q_off"]) if rep == 0 else db
+        O1, lse1 = db.forward(src_K, src_V, case["k_offs"])
+        dQ1, dKs1, dVs1 = db.backward(src_K, src_V, case["k_offs"], case["dO"])
+        torch.cuda.synchronize()
+        assert torch.equal(O1, O0) and torch.equal(lse1, lse0) and torch.equal(dQ1, dQ0)
+        for a, b in zip(dKs1 + dVs1, dKs0 + dVs0):
+            assert torch.equal(a, b)
 
 
 def test_backward_without_D_and_accumulate_flags():
