@@ -66,7 +66,12 @@ int check_params(const burst_params* p, KParams* k) {
     if (!aligned16(ptr)) return BURST_ERR_ALIGN;         \
   } while (0)
 
-bool use_mfma(const burst_params* p) { return p->dtype == BURST_BF16 && p->d == 128; }
+// The MFMA kernels address a head's rows through 32-bit byte offsets (256 B per row, plus a few
+// tiles of prefetch past the end); longer slices or chunks take the generic kernels.
+constexpr int kMaxMfmaRows = 4 * 1024 * 1024;
+bool use_mfma(const burst_params* p) {
+  return p->dtype == BURST_BF16 && p->d == 128 && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows;
+}
 
 int get_d_scratch(size_t elems, float** out) {
   int dev = 0;
