@@ -25,6 +25,11 @@ Readings of the paper taken here (the paper is silent or inconsistent):
 * Masking is not part of the paper.  A key at global position kp is visible to
   a query at global position qp iff kp <= qp when `causal` is set; masked
   scores are -inf.
+* Sec. 2.6 lets local attention skip the similarities a sparse pattern does not
+  need.  The one pattern taken here is a sliding window: with `window` = w > 0
+  a key is visible only if kp > qp - w (the query itself and its w - 1
+  predecessors when combined with `causal`); w = 0 means no window.  Skipped
+  pairs behave exactly like masked ones (score -inf).
 * Alg. 1 initialises m = -inf.  When m_new = -inf (a row sees no key of the
   chunk and has seen none before) both rescale factors are taken as 0, so a
   fully masked chunk leaves the state unchanged.  Finalising a row with l = 0
@@ -44,27 +49,30 @@ def _f64(x):
     return np.ascontiguousarray(np.asarray(x, dtype=F64))
 
 
-def visibility(q_pos, k_pos, causal):
+def visibility(q_pos, k_pos, causal, window=0):
     """Boolean [Nq, Nk]: True where the key may be attended to."""
     q_pos = np.asarray(q_pos, dtype=np.int64)
     k_pos = np.asarray(k_pos, dtype=np.int64)
-    if not causal:
-        return np.ones((q_pos.shape[0], k_pos.shape[0]), dtype=bool)
-    return k_pos[None, :] <= q_pos[:, None]
+    vis = np.ones((q_pos.shape[0], k_pos.shape[0]), dtype=bool)
+    if causal:
+        vis &= k_pos[None, :] <= q_pos[:, None]
+    if window:
+        vis &= k_pos[None, :] > q_pos[:, None] - int(window)
+    return vis
 
 
 # --------------------------------------------------------------------------
 # The definition: Eq. 1 and its gradient
 # --------------------------------------------------------------------------
 def full_forward(Q, K, V, scale, causal=False, q_pos=None, k_pos=None,
-                 return_p=False):
+                 return_p=False, window=0):
     """Eq. 1 on one head.  Returns O [Nq,d], lse [Nq] (and P if asked)."""
     Q, K, V = _f64(Q), _f64(K), _f64(V)
     nq, nk = Q.shape[0], K.shape[0]
     q_pos = np.arange(nq) if q_pos is None else q_pos
     k_pos = np.arange(nk) if k_pos is None else k_pos
     S = scale * (Q @ K.T)
-    vis = visibility(q_pos, k_pos, causal)
+    vis = visibility(q_pos, k_pos, causal, window)
     S = np.where(vis, S, -np.inf)
     if nk == 0:
         row_max = np.full(nq, -np.inf)
@@ -83,14 +91,14 @@ def full_forward(Q, K, V, scale, causal=False, q_pos=None, k_pos=None,
 
 
 def full_backward(Q, K, V, dO, scale, causal=False, q_pos=None, k_pos=None,
-                  return_ds=False):
+                  return_ds=False, window=0):
     """Gradient of L = sum(O o dO) w.r.t. Q, K, V from the softmax Jacobian.
 
     dV = P^T dO;  dP = dO V^T;  dS = P o (dP - rowsum(P o dP));
     dQ = scale dS K;  dK = scale dS^T Q.
     """
     Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
-    _, _, P = full_forward(Q, K, V, scale, causal, q_pos, k_pos, return_p=True)
+    _, _, P = full_forward(Q, K, V, scale, causal, q_pos, k_pos, return_p=True, window=window)
     dV = P.T @ dO
     dP = dO @ V.T
     dS = P * (dP - (P * dP).sum(axis=1, keepdims=True))
@@ -156,7 +164,7 @@ def gao_finalize(O_i, m_i, l_i):
 
 
 def gao_forward(Q, K_chunks, V_chunks, scale, causal=False, q_pos=None,
-                k_pos_chunks=None, order=None):
+                k_pos_chunks=None, order=None, window=0):
     """Alg. 1 on one head over a list of K/V chunks, visited in `order`."""
     Q = _f64(Q)
     nq, d = Q.shape
@@ -169,7 +177,7 @@ def gao_forward(Q, K_chunks, V_chunks, scale, causal=False, q_pos=None,
     order = range(len(K_chunks)) if order is None else order
     O_i, m_i, l_i = gao_state_init(nq, d)
     for j in order:
-        vis = visibility(q_pos, k_pos_chunks[j], causal) if causal else None
+        vis = visibility(q_pos, k_pos_chunks[j], causal, window) if (causal or window) else None
         O_ij, m_ij, l_ij = gao_local_forward(Q, K_chunks[j], V_chunks[j], scale, vis)
         O_i, m_i, l_i = gao_merge(O_i, m_i, l_i, O_ij, m_ij, l_ij)
     return gao_finalize(O_i, m_i, l_i)
@@ -206,7 +214,7 @@ def gao_local_backward(Q, K_c, V_c, dO, lse, D, scale, vis=None):
 
 
 def gao_backward(Q, K_chunks, V_chunks, O, dO, lse, scale, causal=False,
-                 q_pos=None, k_pos_chunks=None):
+                 q_pos=None, k_pos_chunks=None, window=0):
     """Alg. 2 on one head with Q pinned and the K/V chunks walked in order.
 
     Returns dQ [Nq,d] and lists dK_chunks, dV_chunks.
@@ -223,7 +231,7 @@ def gao_backward(Q, K_chunks, V_chunks, O, dO, lse, scale, causal=False,
     dQ = np.zeros_like(Q)
     dKs, dVs = [], []
     for j in range(len(K_chunks)):
-        vis = visibility(q_pos, k_pos_chunks[j], causal) if causal else None
+        vis = visibility(q_pos, k_pos_chunks[j], causal, window) if (causal or window) else None
         dq, dk, dv = gao_local_backward(Q, K_chunks[j], V_chunks[j], dO, lse, D, scale, vis)
         dQ += dq
         dKs.append(dk)
@@ -234,7 +242,7 @@ def gao_backward(Q, K_chunks, V_chunks, O, dO, lse, scale, causal=False,
 # --------------------------------------------------------------------------
 # Multi-head helpers (plain loops over batch and head)
 # --------------------------------------------------------------------------
-def full_forward_bh(Q, K, V, scale, causal=False, q_off=0, k_off=0):
+def full_forward_bh(Q, K, V, scale, causal=False, q_off=0, k_off=0, window=0):
     """Q [B,H,Nq,d], K,V [B,H,Nk,d] -> O [B,H,Nq,d], lse [B,H,Nq]."""
     B, H, nq, d = Q.shape
     nk = K.shape[2]
@@ -243,11 +251,11 @@ def full_forward_bh(Q, K, V, scale, causal=False, q_off=0, k_off=0):
     qp, kp = q_off + np.arange(nq), k_off + np.arange(nk)
     for b in range(B):
         for h in range(H):
-            O[b, h], lse[b, h] = full_forward(Q[b, h], K[b, h], V[b, h], scale, causal, qp, kp)
+            O[b, h], lse[b, h] = full_forward(Q[b, h], K[b, h], V[b, h], scale, causal, qp, kp, window=window)
     return O, lse
 
 
-def full_backward_bh(Q, K, V, dO, scale, causal=False, q_off=0, k_off=0):
+def full_backward_bh(Q, K, V, dO, scale, causal=False, q_off=0, k_off=0, window=0):
     B, H, nq, d = Q.shape
     nk = K.shape[2]
     dQ = np.empty((B, H, nq, d), F64)
@@ -257,5 +265,5 @@ def full_backward_bh(Q, K, V, dO, scale, causal=False, q_off=0, k_off=0):
     for b in range(B):
         for h in range(H):
             dQ[b, h], dK[b, h], dV[b, h] = full_backward(
-                Q[b, h], K[b, h], V[b, h], dO[b, h], scale, causal, qp, kp)
+                Q[b, h], K[b, h], V[b, h], dO[b, h], scale, causal, qp, kp, window=window)
     return dQ, dK, dV

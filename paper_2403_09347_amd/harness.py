@@ -163,3 +163,4 @@ class DoubleBufferedWalk(RingWalk):
                 self._view(kb, rows).copy_(src_Ks[j], non_blocking=True)
                 self._view(vb, rows).copy_(src_Vs[j], non_blocking=True)
         torch.cuda.current_stream(self.Q.device).wait_stream(self.copy_stream)
+

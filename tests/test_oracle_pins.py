@@ -324,3 +324,99 @@ def test_multihead_helpers_loop_over_heads():
     assert np.array_equal(O[1, 2], o) and np.array_equal(lse[1, 2], l)
     dq, dk, dv = orc.full_backward(Q[0, 1], K[0, 1], V[0, 1], dO[0, 1], 0.5, True, 4 + np.arange(nq), 2 + np.arange(nk))
     assert np.array_equal(dQ[0, 1], dq) and np.array_equal(dK[0, 1], dk) and np.array_equal(dV[0, 1], dv)
+
+
+# ---------------------------------------------------------------- sliding window (Sec. 2.6: skipped similarities)
+def test_window_zero_query_gives_means_over_the_window():
+    r = rng(21)
+    nk, d, w = 23, 4, 5
+    K, V = r.normal(size=(nk, d)), r.normal(size=(nk, d))
+    Q = np.zeros((nk, d))
+    csum = np.vstack([np.zeros((1, d)), np.cumsum(V, axis=0)])
+    # causal + window: row r sees keys max(0, r-w+1) .. r
+    lo = np.maximum(0, np.arange(nk) - w + 1)
+    cnt = np.arange(nk) + 1 - lo
+    want = (csum[np.arange(nk) + 1] - csum[lo]) / cnt[:, None]
+    O, lse = orc.full_forward(Q, K, V, 1.0, causal=True, window=w)
+    assert np.allclose(O, want, atol=1e-14) and np.allclose(lse, np.log(cnt), atol=1e-14)
+    O, lse = orc.gao_forward(Q, split(K, [6, 9, 8]), split(V, [6, 9, 8]), 1.0, causal=True, window=w)
+    assert np.allclose(O, want, atol=1e-14) and np.allclose(lse, np.log(cnt), atol=1e-14)
+    # window without causal: row r sees keys max(0, r-w+1) .. nk-1
+    cnt2 = nk - lo
+    want2 = (csum[nk] - csum[lo]) / cnt2[:, None]
+    O, lse = orc.full_forward(Q, K, V, 1.0, causal=False, window=w)
+    assert np.allclose(O, want2, atol=1e-14) and np.allclose(lse, np.log(cnt2), atol=1e-14)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_window_equals_unwindowed_attention_on_the_visible_keys(causal):
+    """Row by row: attention with a window = plain attention (no window argument at all) over
+    exactly the keys the window leaves visible; the gradients scatter back accordingly."""
+    r = rng(22)
+    nq, nk, d, w = 11, 17, 6, 4
+    Q, K, V, dO = (r.normal(size=(n, d)) for n in (nq, nk, nk, nq))
+    scale = 0.3
+    q_pos, k_pos = 4 + np.arange(nq), np.arange(nk)
+    O, lse = orc.full_forward(Q, K, V, scale, causal, q_pos, k_pos, window=w)
+    dQ, dK, dV = orc.full_backward(Q, K, V, dO, scale, causal, q_pos, k_pos, window=w)
+    dK2, dV2 = np.zeros_like(K), np.zeros_like(V)
+    for i in range(nq):
+        keep = [c for c in range(nk) if k_pos[c] > q_pos[i] - w and (not causal or k_pos[c] <= q_pos[i])]
+        Oi, lsei = orc.full_forward(Q[i:i + 1], K[keep], V[keep], scale)
+        dqi, dki, dvi = orc.full_backward(Q[i:i + 1], K[keep], V[keep], dO[i:i + 1], scale)
+        assert np.allclose(O[i], Oi[0], atol=1e-14) and abs(lse[i] - lsei[0]) < 1e-14
+        assert np.allclose(dQ[i], dqi[0], atol=1e-14)
+        dK2[keep] += dki
+        dV2[keep] += dvi
+    assert np.allclose(dK, dK2, atol=1e-13) and np.allclose(dV, dV2, atol=1e-13)
+    # the chunked algorithm agrees, including chunks that some or all rows cannot see
+    sizes = [3, 6, 1, 7]
+    kp = split(k_pos, sizes)
+    Oc, lsec = orc.gao_forward(Q, split(K, sizes), split(V, sizes), scale, causal, q_pos, kp, window=w)
+    dQc, dKs, dVs = orc.gao_backward(Q, split(K, sizes), split(V, sizes), Oc, dO, lsec, scale, causal, q_pos, kp,
+                                     window=w)
+    for a, b in ((O, Oc), (lse, lsec), (dQ, dQc), (dK, np.concatenate(dKs)), (dV, np.concatenate(dVs))):
+        assert np.max(np.abs(a - b)) < 1e-13
+
+
+def test_window_wider_than_everything_changes_nothing_and_window_one_copies_values():
+    r = rng(23)
+    nq, nk, d = 7, 12, 5
+    Q, K, V, dO = (r.normal(size=(n, d)) for n in (nq, nk, nk, nq))
+    q_pos, k_pos = 5 + np.arange(nq), np.arange(nk)
+    for causal in (False, True):
+        a = orc.full_forward(Q, K, V, 0.5, causal, q_pos, k_pos)
+        b = orc.full_forward(Q, K, V, 0.5, causal, q_pos, k_pos, window=10 ** 6)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    # causal, window 1: each query sees only the key at its own position
+    O, lse = orc.full_forward(Q, K, V, 0.5, True, q_pos, k_pos, window=1)
+    assert np.allclose(O, V[5:12], atol=1e-15)
+    assert np.allclose(lse, 0.5 * np.einsum("rd,rd->r", Q, K[5:12]), atol=1e-14)
+    dQ, dK, dV = orc.full_backward(Q, K, V, dO, 0.5, True, q_pos, k_pos, window=1)
+    assert np.allclose(dQ, 0) and np.allclose(dK, 0)
+    assert np.allclose(dV[5:12], dO, atol=1e-15) and np.allclose(dV[:5], 0)
+
+
+def test_window_backward_matches_central_differences():
+    r = rng(24)
+    nq, nk, d, w = 6, 10, 3, 4
+    Q, K, V, dO = (r.normal(size=(n, d)) for n in (nq, nk, nk, nq))
+    scale, q_pos, k_pos = 0.6, 3 + np.arange(nq), np.arange(nk)
+
+    def loss(Q_, K_, V_):
+        O, _ = orc.full_forward(Q_, K_, V_, scale, True, q_pos, k_pos, window=w)
+        return (O * dO).sum()
+    sizes = [4, 6]
+    O, lse = orc.gao_forward(Q, split(K, sizes), split(V, sizes), scale, True, q_pos, split(k_pos, sizes), window=w)
+    dQ, dKs, dVs = orc.gao_backward(Q, split(K, sizes), split(V, sizes), O, dO, lse, scale, True, q_pos,
+                                    split(k_pos, sizes), window=w)
+    grads = (dQ, np.concatenate(dKs), np.concatenate(dVs))
+    h = 1e-5
+    for idx, X in enumerate((Q, K, V)):
+        for (i, t) in [(0, 0), (X.shape[0] - 1, d - 1), (X.shape[0] // 2, 1)]:
+            args = [Q.copy(), K.copy(), V.copy()]
+            args[idx][i, t] += h
+            up = loss(*args)
+            args[idx][i, t] -= 2 * h
+            fd = (up - loss(*args)) / (2 * h)
+            assert abs(fd - grads[idx][i, t]) < 1e-8 * max(1.0, abs(fd)), (idx, i, t)
