@@ -21,7 +21,12 @@
  *     it, here it is always applied).  scale must be finite and > 0.
  *   - Masking (not in the paper): with causal != 0 the key at global position
  *     k_off + c is visible to the query at global position q_off + r iff
- *     k_off + c <= q_off + r.  A row that sees no key keeps its state.
+ *     k_off + c <= q_off + r.  With window = w > 0 (paper Sec. 2.6: similarities
+ *     a sparse pattern does not need are skipped) the key is visible only if
+ *     k_off + c > q_off + r - w: a sliding window, the query itself and its w - 1
+ *     predecessors when combined with causal; w = 0 means no window.  Key tiles and
+ *     whole chunks outside the window are skipped, not computed and masked.
+ *     A row that sees no key keeps its state.
  *   - Return value: 0 on success, a negative burst_status otherwise.  On error
  *     nothing is enqueued and no output is written.
  *   - Supported shapes: B, H >= 1; Nq, Nc >= 0 (0 = nothing to do); 1 <= d <= 128
@@ -62,6 +67,7 @@ typedef struct burst_params {
   float   scale;    /* softmax scale, normally 1/sqrt(d) */
   int64_t q_off;    /* global position of query row 0 */
   int64_t k_off;    /* global position of row 0 of this chunk */
+  int64_t window;   /* 0 = none; w > 0: keys at positions <= query position - w are hidden */
 } burst_params;
 
 /* Alg. 1, initialisation: O_acc = 0, l = 0, m = -inf.

@@ -26,6 +26,7 @@ class BurstParams(ctypes.Structure):
         ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("Nq", ctypes.c_int32), ("Nc", ctypes.c_int32),
         ("d", ctypes.c_int32), ("dtype", ctypes.c_int32), ("causal", ctypes.c_int32),
         ("scale", ctypes.c_float), ("q_off", ctypes.c_int64), ("k_off", ctypes.c_int64),
+        ("window", ctypes.c_int64),
     ]
 
 
@@ -80,9 +81,9 @@ def version():
     return load().burst_version()
 
 
-def params(B, H, Nq, Nc, d, dtype, scale, causal=False, q_off=0, k_off=0):
+def params(B, H, Nq, Nc, d, dtype, scale, causal=False, q_off=0, k_off=0, window=0):
     code = {torch.bfloat16: BURST_BF16, torch.float32: BURST_F32, "bf16": BURST_BF16, "f32": BURST_F32}.get(dtype, dtype)
-    return BurstParams(B, H, Nq, Nc, d, code, 1 if causal else 0, scale, q_off, k_off)
+    return BurstParams(B, H, Nq, Nc, d, code, 1 if causal else 0, scale, q_off, k_off, window)
 
 
 def _ptr(t):

@@ -57,6 +57,8 @@ int check_params(const burst_params* p, KParams* k) {
   // rows must be addressable with 16-byte aligned row starts for the vector kernels
   k->B = p->B; k->H = p->H; k->Nq = p->Nq; k->Nc = p->Nc; k->d = p->d;
   k->causal = p->causal != 0; k->scale = p->scale; k->q_off = p->q_off; k->k_off = p->k_off;
+  if (p->window < 0) return BURST_ERR_SHAPE;
+  k->window = p->window;
   return BURST_OK;
 }
 
@@ -266,6 +268,6 @@ const char* burst_strerror(int status) {
   }
 }
 
-int burst_version(void) { return 100; }
+int burst_version(void) { return 101; }
 
 }  // extern "C"

@@ -13,6 +13,7 @@ struct BwdArgs {
   float c;               // scale * log2(e)
   float scale;
   long long q_off, k_off;
+  long long window;      // 0 = none; else keys at positions <= query position - window are hidden
   int blocks_per_head;
   int acc_dq, acc_dkv;
 };
@@ -25,7 +26,7 @@ inline BwdArgs make_bwd_args(const KParams& p, const void* Q, const void* K, con
   a.lse = lse; a.D = D; a.dQ = dQ; a.dK = dK; a.dV = dV;
   a.Nq = p.Nq; a.Nc = p.Nc; a.H = p.B * p.H;
   a.causal = p.causal; a.c = p.scale * kLog2e; a.scale = p.scale;
-  a.q_off = p.q_off; a.k_off = p.k_off;
+  a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
   a.blocks_per_head = 0; a.acc_dq = acc_dq; a.acc_dkv = acc_dkv;
   return a;
 }

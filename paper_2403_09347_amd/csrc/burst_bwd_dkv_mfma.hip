@@ -58,11 +58,16 @@ burst_bwd_dkv_kernel(BwdArgs a) {
   const float* Dh = a.D + (size_t)head * a.Nq;
 
   // query tiles to visit: causal rows before the first key of the workgroup see none of it
-  const int ntiles_all = (a.Nq + DKV_BR - 1) / DKV_BR;
+  int ntiles_all = (a.Nq + DKV_BR - 1) / DKV_BR;
   int t_begin = 0;
   if (a.causal) {
     long long first_row = a.k_off + key_wg - a.q_off;      // first row index that sees key_wg
     if (first_row > 0) t_begin = (int)min((long long)ntiles_all, first_row / DKV_BR);
+  }
+  if (a.window > 0) {
+    // sliding window: rows at positions >= key position + window no longer see the key
+    long long last_row = a.k_off + min(key_wg + DKV_BC, a.Nc) - 1 + a.window - 1 - a.q_off;
+    ntiles_all = last_row < 0 ? 0 : (int)min((long long)ntiles_all, last_row / DKV_BR + 1);
   }
 
   f32x16 dk[4], dv[4];     // [32-wide d block]: rows = the wavefront's 32 keys; pinned in AGPRs
@@ -199,7 +204,8 @@ burst_bwd_dkv_kernel(BwdArgs a) {
       const long long tile_first_q = a.q_off + (long long)t * DKV_BR;
       // (no branch around the MFMA phases: the AGPR-pinned accumulators must not become phi
       // values, the allocator would shuttle them through VGPRs every iteration)
-      const bool need_mask = a.causal && (wave_last_k > tile_first_q);
+      const bool need_mask = (a.causal && wave_last_k > tile_first_q) ||
+                             (a.window > 0 && tile_first_q + DKV_BR - 1 >= wave_first_k + a.window);
       {
         // A-operand read j (0..31): rb = j / 16, ks = (j / 2) % 8, even: Q fragment (for S), odd:
         // dO fragment (for dP).  S and dP alternate so that no MFMA waits for its predecessor.
@@ -244,17 +250,20 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           pf[rb][u][t8] = pk[0]; pf[rb][u][t8 + 1] = pk[1];
           dsf[rb][u][t8] = dk2[0]; dsf[rb][u][t8 + 1] = dk2[1];
         };
-        // causal mask of one row block (rare: tiles that straddle the diagonal).  Register r
-        // belongs to row tile_first_q + rb*32 + 4h + (8*(r/4) + r%4); the key is visible iff its
-        // position <= the row's, i.e. iff the constant part is >= lim.  A masked score becomes
-        // -inf, its P and dS become 0.
+        // mask of one row block (rare: tiles that straddle the diagonal or the far edge of the
+        // sliding window).  Register r belongs to row tile_first_q + rb*32 + 4h + (8*(r/4) + r%4);
+        // causal: the key is visible iff its position <= the row's, i.e. iff the constant part is
+        // >= lim; window: iff the row's position < the key's + window, i.e. constant part <= lim2.
+        // A masked score becomes -inf, its P and dS become 0.
         auto mask_block = [&](int rb) __attribute__((always_inline)) {
-          long long d = kpos - (tile_first_q + rb * 32 + 4 * h);
-          const int lim = (int)(d < -1 ? -1 : (d > 64 ? 64 : d));
+          const long long d = kpos - (tile_first_q + rb * 32 + 4 * h);
+          const int lim = a.causal ? (int)(d < -1 ? -1 : (d > 64 ? 64 : d)) : -1;
+          const long long d2 = d + a.window - 1;
+          const int lim2 = a.window > 0 ? (int)(d2 < -1 ? -1 : (d2 > 64 ? 64 : d2)) : 64;
 #pragma unroll
           for (int r = 0; r < 16; r++) {
             const int cpart = 8 * (r >> 2) + (r & 3);
-            s[rb][r] = (cpart >= lim) ? s[rb][r] : BURST_NEG_INF;
+            s[rb][r] = (cpart >= lim && cpart <= lim2) ? s[rb][r] : BURST_NEG_INF;
           }
         };
 #pragma unroll

@@ -29,9 +29,13 @@ constexpr int DQ_VSLOTS = 3;
 constexpr int DQ_GBASE = (DQ_KSLOTS + DQ_VSLOTS) * DQ_TILE_BYTES;   // dO block of the workgroup: 256 rows
 constexpr int DQ_LDS_BYTES = DQ_GBASE + DQ_BR * 256;
 
+// WINDOW = false compiles the sliding-window code away: this kernel uses every register of the
+// file, and the few values the window logic keeps alive would otherwise push others to scratch.
+template <bool WINDOW>
 __global__ void __launch_bounds__(256, 1)
 burst_bwd_dq_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  const long long window = WINDOW ? a.window : 0;
   const int tid = threadIdx.x;
   const int w = tid >> 6, lane = tid & 63, lr = lane & 31, h = lane >> 5;
   int head, qb;
@@ -52,9 +56,23 @@ burst_bwd_dq_kernel(BwdArgs a) {
   const float* Dh = a.D + (size_t)head * a.Nq;
   float* dQh = a.dQ + (size_t)head * a.Nq * 128;
 
-  int ntiles = (a.Nc + DQ_BC - 1) / DQ_BC;
+  // Sliding window: key tiles before the first one that the workgroup's first row can see are
+  // skipped by moving the start of the chunk (pointers, length, global offset) forward by whole
+  // tiles; everything below works on that shortened chunk.
+  int Nc = a.Nc;
+  long long k_off = a.k_off;
+  if (window > 0) {
+    long long lo = a.q_off + (long long)qb * DQ_BR - window + 1 - a.k_off;   // first visible key index
+    if (lo >= a.Nc) Nc = 0;                        // nothing visible: contribution 0
+    else if (lo > 0) {
+      const int skip = (int)(lo / DQ_BC) * DQ_BC;
+      Kh += (size_t)skip * 128; Vh += (size_t)skip * 128;
+      Nc -= skip; k_off += skip;
+    }
+  }
+  int ntiles = (Nc + DQ_BC - 1) / DQ_BC;
   if (a.causal) {
-    long long lim = a.q_off + min(qb * DQ_BR + DQ_BR, a.Nq) - 1 - a.k_off;
+    long long lim = a.q_off + min(qb * DQ_BR + DQ_BR, a.Nq) - 1 - k_off;
     long long t = lim < 0 ? 0 : lim / DQ_BC + 1;
     if (t < ntiles) ntiles = (int)t;
   }
@@ -70,7 +88,6 @@ burst_bwd_dq_kernel(BwdArgs a) {
   if (ntiles > 0) {
     bf16x8 qf[2][8];
     float nlse2[2], Dv[2];
-    int klim[2];           // last key index of this chunk that the lane's row may see (-1: none)
 #pragma unroll
     for (int rb = 0; rb < 2; rb++) {
       int row = q0 + rb * 32 + lr;
@@ -78,9 +95,6 @@ burst_bwd_dq_kernel(BwdArgs a) {
       float lv = ok ? lseh[row] : BURST_NEG_INF;
       nlse2[rb] = (lv == BURST_NEG_INF) ? BURST_NEG_INF : -lv * kLog2e;   // -inf => P = exp2(-inf) = 0
       Dv[rb] = ok ? Dh[row] : 0.f;
-      long long v = a.causal ? (a.q_off + row - a.k_off) : (long long)(a.Nc - 1);
-      v = v < -1 ? -1 : v;
-      klim[rb] = (int)(v > (long long)(a.Nc - 1) ? (long long)(a.Nc - 1) : v);
 #pragma unroll
       for (int ks = 0; ks < 8; ks++) {
         bf16x8 z;
@@ -102,8 +116,8 @@ burst_bwd_dq_kernel(BwdArgs a) {
           taddr[db][sx] = tile_off(8 * sx + 4 * h + (j16 >> 2), db * 4 + 2 * dh + ((j16 & 3) >> 1)) + (j16 & 1) * 8;
     }
     // DMA: a 32-key tile is 8 wave-loads of 4 rows; wavefront w issues loads 2w and 2w + 1
-    const __amdgpu_buffer_rsrc_t krs = make_rsrc(Kh, (unsigned)a.Nc * 256u);
-    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, (unsigned)a.Nc * 256u);
+    const __amdgpu_buffer_rsrc_t krs = make_rsrc(Kh, (unsigned)Nc * 256u);
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, (unsigned)Nc * 256u);
     const int wu = __builtin_amdgcn_readfirstlane(w);
     const unsigned lds0 = lds_addr(smem);
     int goff[2];
@@ -188,17 +202,29 @@ burst_bwd_dq_kernel(BwdArgs a) {
       for (int j = 0; j < LEAD; j++) issue_read(j);
       // ---- masking (diagonal tiles, ragged key tail): rare.  A masked score becomes -inf,
       // its P and dS become 0.
-      const long long tile_first_k = a.k_off + (long long)kt * DQ_BC;
+      const long long tile_first_k = k_off + (long long)kt * DQ_BC;
       const bool need_mask = (a.causal && tile_first_k + DQ_BC - 1 > wave_first_q) ||
-                             ((kt + 1) * DQ_BC > a.Nc);
+                             (window > 0 && tile_first_k < wave_first_q + 63 - window + 1) ||
+                             ((kt + 1) * DQ_BC > Nc);
       if (need_mask) {
 #pragma unroll
         for (int rb = 0; rb < 2; rb++) {
-          const int lim = klim[rb] - (kt * DQ_BC + 4 * h);
+          // score register r holds key index kt*32 + 4h + (8*(r/4) + r%4) of the chunk; with
+          // dd = (row position) - (position of key kt*32 + 4h) the key of register r is visible
+          // iff cpart <= dd (causal), cpart > dd - window, and it exists (ragged tail).
+          // Computed here, in the rare path, so that nothing of it stays live in the main loop.
+          const int ln = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));   // lane id, recomputed
+          const int mlr = ln & 31, mh = ln >> 5;
+          const long long dd = (a.q_off - k_off) + (q0 + rb * 32 + mlr) - ((long long)kt * DQ_BC + 4 * mh);
+          const int tail = Nc - 1 - (kt * DQ_BC + 4 * mh);
+          int lim = a.causal ? (int)(dd < -1 ? -1 : (dd > 64 ? 64 : dd)) : 64;
+          lim = lim < tail ? lim : tail;
+          const long long dl = dd - window + 1;
+          const int lim_lo = window > 0 ? (int)(dl < -1 ? -1 : (dl > 64 ? 64 : dl)) : -1;
 #pragma unroll
           for (int r = 0; r < 16; r++) {
             const int cpart = 8 * (r >> 2) + (r & 3);
-            sc[rb][r] = (cpart <= lim) ? sc[rb][r] : BURST_NEG_INF;
+            sc[rb][r] = (cpart <= lim && cpart >= lim_lo) ? sc[rb][r] : BURST_NEG_INF;
           }
         }
       }
@@ -304,11 +330,16 @@ int launch_bwd_dq_mfma(const KParams& p, const void* Q, const void* K, const voi
   if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)burst_bwd_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            DQ_LDS_BYTES) != hipSuccess ||
+        hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             DQ_LDS_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
     attr_set = true;
   }
-  hipLaunchKernelGGL(burst_bwd_dq_kernel, dim3((unsigned)nb), dim3(256), DQ_LDS_BYTES, stream, a);
+  if (a.window > 0)
+    hipLaunchKernelGGL(burst_bwd_dq_kernel<true>, dim3((unsigned)nb), dim3(256), DQ_LDS_BYTES, stream, a);
+  else
+    hipLaunchKernelGGL(burst_bwd_dq_kernel<false>, dim3((unsigned)nb), dim3(256), DQ_LDS_BYTES, stream, a);
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 

@@ -25,6 +25,7 @@ struct KParams {
   int causal;
   float scale;
   long long q_off, k_off;
+  long long window;      // 0 = none
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

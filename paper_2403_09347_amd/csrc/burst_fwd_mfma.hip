@@ -33,6 +33,7 @@ struct FwdArgs {
   int causal;
   float c;               // scale * log2(e)
   long long q_off, k_off;
+  long long window;      // 0 = none; else keys at positions <= query position - window are hidden
   int q_blocks;          // ceil(Nq / FWD_BR)
 };
 
@@ -98,12 +99,27 @@ burst_fwd_mfma_kernel(FwdArgs a) {
   const bf16* Kh = a.K + (size_t)head * a.Nc * 128;
   const bf16* Vh = a.V + (size_t)head * a.Nc * 128;
 
+  // Sliding window: key tiles before the first one that the workgroup's first row can see are
+  // skipped by moving the start of the chunk (pointers, length, global offset) forward by whole
+  // tiles; everything below works on that shortened chunk.
+  int Nc = a.Nc;
+  long long k_off = a.k_off;
+  if (a.window > 0) {
+    long long lo = a.q_off + (long long)qb * FWD_BR - a.window + 1 - a.k_off;   // first visible key index
+    if (lo >= a.Nc) return;                        // nothing visible: state unchanged
+    if (lo > 0) {
+      const int skip = (int)(lo / FWD_BC) * FWD_BC;
+      Kh += (size_t)skip * 128; Vh += (size_t)skip * 128;
+      Nc -= skip; k_off += skip;
+    }
+  }
+
   // Number of key tiles this workgroup must visit (causal: stop after the last tile that
   // any of its rows can see).
-  int ntiles = (a.Nc + FWD_BC - 1) / FWD_BC;
+  int ntiles = (Nc + FWD_BC - 1) / FWD_BC;
   const long long wg_last_q = a.q_off + min(qb * FWD_BR + FWD_BR, a.Nq) - 1;
   if (a.causal) {
-    long long lim = wg_last_q - a.k_off;           // last visible key index in this chunk
+    long long lim = wg_last_q - k_off;             // last visible key index in this chunk
     if (lim < 0) return;                           // nothing visible: state unchanged
     long long t = lim / FWD_BC + 1;
     if (t < ntiles) ntiles = (int)t;
@@ -155,8 +171,8 @@ burst_fwd_mfma_kernel(FwdArgs a) {
   // ---- prologue: K tiles 0..2 and V tiles 0..1 into LDS, S of tile 0.
   // LDS: K ring = tiles 0..2 of the buffer, V ring = tiles 3..5; tile t lives in slot t % 3.
   // Tiles past the end of the chunk read as zeros (buffer range check) and are never used.
-  const __amdgpu_buffer_rsrc_t krs = make_rsrc(Kh, (unsigned)a.Nc * 256u);
-  const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, (unsigned)a.Nc * 256u);
+  const __amdgpu_buffer_rsrc_t krs = make_rsrc(Kh, (unsigned)Nc * 256u);
+  const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, (unsigned)Nc * 256u);
   const int wu = __builtin_amdgcn_readfirstlane(w);
   const unsigned lds0 = lds_addr(smem);
   int goff[4];
@@ -190,14 +206,7 @@ burst_fwd_mfma_kernel(FwdArgs a) {
   __builtin_amdgcn_s_barrier();   // K tile 0 is consumed by every wavefront before its slot is refilled
 
   const long long wave_first_q = a.q_off + q0;
-  // last key index of this chunk that each of the lane's two rows may see (-1: none)
-  int klim[2];
-#pragma unroll
-  for (int rb = 0; rb < 2; rb++) {
-    long long v = a.causal ? (a.q_off + q0 + rb * 32 + lr - a.k_off) : (long long)(a.Nc - 1);
-    v = v < -1 ? -1 : v;
-    klim[rb] = (int)(v > (long long)(a.Nc - 1) ? (long long)(a.Nc - 1) : v);
-  }
+  const long long wave_last_q = wave_first_q + 63;
   bf16x2 ones;
   ones[0] = (bf16)1.0f; ones[1] = (bf16)1.0f;
   constexpr int PF = 4;          // operand fragments are fetched PF MFMA pairs ahead
@@ -215,24 +224,34 @@ burst_fwd_mfma_kernel(FwdArgs a) {
     bf16x8 kfq[PF + 1];
 #pragma unroll
     for (int pn = 0; pn < PF; pn++) kfq[pn] = lds_read_b128(kl_next, (pn & 1) * 32 * 256 + kaddr[pn >> 1]);
-    const long long tile_first_k = a.k_off + (long long)kt * FWD_BC;
+    const long long tile_first_k = k_off + (long long)kt * FWD_BC;
     // ---- masking (diagonal tiles, ragged key tail): rare; redo the row maxima afterwards
     const bool need_mask = (a.causal && tile_first_k + FWD_BC - 1 > wave_first_q) ||
-                           ((kt + 1) * FWD_BC > a.Nc);
+                           (a.window > 0 && tile_first_k < wave_last_q - a.window + 1) ||
+                           ((kt + 1) * FWD_BC > Nc);
     if (need_mask) {
       raise = false;
 #pragma unroll
       for (int rb = 0; rb < 2; rb++) {
-        // score register r of key block kb holds key index kt*64 + 4h + (kb*32 + 8*(r/4) + r%4);
-        // it is visible iff that constant part is <= lim
-        const int lim = klim[rb] - (kt * FWD_BC + 4 * h);
+        // score register r of key block kb holds key index kt*64 + 4h + (kb*32 + 8*(r/4) + r%4)
+        // of the chunk; with dd = (row position) - (position of key kt*64 + 4h) the key of
+        // register r is visible iff cpart <= dd (causal), cpart > dd - window, and it exists
+        // (ragged tail).  Computed here, in the rare path: nothing of it stays live in the loop.
+        const int ln = __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));   // lane id, recomputed
+        const int mlr = ln & 31, mh = ln >> 5;
+        const long long dd = (a.q_off - k_off) + (q0 + rb * 32 + mlr) - ((long long)kt * FWD_BC + 4 * mh);
+        const int tail = Nc - 1 - (kt * FWD_BC + 4 * mh);
+        int lim = a.causal ? (int)(dd < -1 ? -1 : (dd > 64 ? 64 : dd)) : 64;
+        lim = lim < tail ? lim : tail;
+        const long long dl = dd - a.window + 1;
+        const int lim_lo = a.window > 0 ? (int)(dl < -1 ? -1 : (dl > 64 ? 64 : dl)) : -1;
         float v = BURST_NEG_INF;
 #pragma unroll
         for (int kb = 0; kb < 2; kb++)
 #pragma unroll
           for (int r = 0; r < 16; r++) {
             const int cpart = kb * 32 + 8 * (r >> 2) + (r & 3);
-            float x = (cpart <= lim) ? sc[kb][rb][r] : BURST_NEG_INF;
+            float x = (cpart <= lim && cpart >= lim_lo) ? sc[kb][rb][r] : BURST_NEG_INF;
             sc[kb][rb][r] = x;
             v = fmaxf(v, x);
           }
@@ -413,7 +432,7 @@ int launch_fwd_mfma(const KParams& p, const void* Q, const void* K, const void* 
   a.Nq = p.Nq; a.Nc = p.Nc; a.H = p.B * p.H;
   a.causal = p.causal;
   a.c = p.scale * kLog2e;
-  a.q_off = p.q_off; a.k_off = p.k_off;
+  a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
   a.q_blocks = (p.Nq + FWD_BR - 1) / FWD_BR;
   int heads8 = ((a.H + 7) / 8) * 8;                // pad the head count to a multiple of 8 ids
   long long nblocks = (long long)heads8 * a.q_blocks;

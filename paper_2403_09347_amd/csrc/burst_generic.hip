@@ -17,6 +17,7 @@ struct GenArgs {
   int causal;
   float scale;
   long long q_off, k_off;
+  long long window;
   int acc_dq, acc_dkv;
 };
 
@@ -52,7 +53,7 @@ fwd_generic_kernel(GenArgs a) {
   float m_run = BURST_NEG_INF, l_run = 0.f, o0 = 0.f, o1 = 0.f;   // dims lane and lane + 64
   for (int k0 = 0; k0 < a.Nc; k0 += 64) {
     int key = k0 + lane;
-    bool vis = key < a.Nc && (!a.causal || a.k_off + key <= qpos);
+    bool vis = key < a.Nc && (!a.causal || a.k_off + key <= qpos) && (a.window == 0 || a.k_off + key > qpos - a.window);
     float s = BURST_NEG_INF;
     if (vis) {
       float acc = 0.f;
@@ -117,7 +118,7 @@ bwd_dq_generic_kernel(GenArgs a) {
   float q0 = 0.f, q1 = 0.f;
   for (int k0 = 0; k0 < a.Nc; k0 += 64) {
     int key = k0 + lane;
-    bool vis = key < a.Nc && (!a.causal || a.k_off + key <= qpos) && lse != BURST_NEG_INF;
+    bool vis = key < a.Nc && (!a.causal || a.k_off + key <= qpos) && (a.window == 0 || a.k_off + key > qpos - a.window) && lse != BURST_NEG_INF;
     float ds = 0.f;
     if (vis) {
       float sa = 0.f, dp = 0.f;
@@ -171,7 +172,7 @@ bwd_dkv_generic_kernel(GenArgs a) {
   for (int r0 = 0; r0 < a.Nq; r0 += 64) {
     int row = r0 + lane;
     float p = 0.f, ds = 0.f;
-    if (row < a.Nq && (!a.causal || kpos <= a.q_off + row)) {
+    if (row < a.Nq && (!a.causal || kpos <= a.q_off + row) && (a.window == 0 || kpos > a.q_off + row - a.window)) {
       float lse = lseh[row];
       if (lse != BURST_NEG_INF) {
         float sa = 0.f, dp = 0.f;
@@ -209,7 +210,7 @@ bwd_dkv_generic_kernel(GenArgs a) {
 static GenArgs make_args(const KParams& p) {
   GenArgs a = {};
   a.Nq = p.Nq; a.Nc = p.Nc; a.d = p.d; a.BH = p.B * p.H;
-  a.causal = p.causal; a.scale = p.scale; a.q_off = p.q_off; a.k_off = p.k_off;
+  a.causal = p.causal; a.scale = p.scale; a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
   return a;
 }
 static inline int launch_status() { return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH; }

@@ -12,11 +12,11 @@ from . import binding as B
 class RingWalk:
     """Buffers and call sequence for one query slice against a list of chunks."""
 
-    def __init__(self, Q, scale, causal=False, q_off=0):
+    def __init__(self, Q, scale, causal=False, q_off=0, window=0):
         assert Q.dim() == 4
         self.Q = Q
         self.Bt, self.H, self.Nq, self.d = Q.shape
-        self.scale, self.causal, self.q_off = float(scale), bool(causal), int(q_off)
+        self.scale, self.causal, self.q_off, self.window = float(scale), bool(causal), int(q_off), int(window)
         dev = Q.device
         self.O_acc = torch.empty((self.Bt, self.H, self.Nq, self.d), device=dev, dtype=torch.float32)
         self.m = torch.empty((self.Bt, self.H, self.Nq), device=dev, dtype=torch.float32)
@@ -27,7 +27,7 @@ class RingWalk:
 
     def params(self, Nc, k_off):
         return B.params(self.Bt, self.H, self.Nq, Nc, self.d, self.Q.dtype, self.scale,
-                        self.causal, self.q_off, k_off)
+                        self.causal, self.q_off, k_off, self.window)
 
     # ---- forward (Alg. 1)
     def init(self):
@@ -74,8 +74,8 @@ class DoubleBufferedWalk(RingWalk):
     chunk (j-1) has been consumed; the computation of chunk j waits for its copy.  All streams
     have the default priority."""
 
-    def __init__(self, Q, scale, causal=False, q_off=0, max_chunk_rows=None):
-        super().__init__(Q, scale, causal, q_off)
+    def __init__(self, Q, scale, causal=False, q_off=0, max_chunk_rows=None, window=0):
+        super().__init__(Q, scale, causal, q_off, window)
         self.copy_stream = torch.cuda.Stream(device=Q.device)
         self.max_rows = max_chunk_rows
         self._bufs = None

@@ -31,6 +31,7 @@ class Workload:
     causal: bool
     q_off: int          # global position of query row 0
     seed: int
+    window: int = 0     # sliding window (0 = none): keys at positions <= query position - window are hidden
 
     @property
     def scale(self):
@@ -45,12 +46,14 @@ class Workload:
 
     def visible_pairs_per_head(self):
         """Number of (query, key) pairs that are not masked, per head."""
-        if not self.causal:
+        if not self.causal and not self.window:
             return self.Nq * self.G * self.Nc
         total = 0
         nk = self.G * self.Nc
         for r in range(self.Nq):
-            total += max(0, min(nk, self.q_off + r + 1))
+            hi = min(nk, self.q_off + r + 1) if self.causal else nk          # keys [lo, hi) are visible
+            lo = max(0, self.q_off + r - self.window + 1) if self.window else 0
+            total += max(0, hi - lo)
         return total
 
     def fwd_flops(self):
@@ -94,7 +97,7 @@ def make_inputs(w, device="cpu", seed=None):
 
 
 def make_case(B, H, d, Nq, chunk_rows, dtype="bf16", seed=0, device="cpu",
-              causal=False, q_off=0, k_offs=None):
+              causal=False, q_off=0, k_offs=None, window=0):
     """Free-form case for parity tests: `chunk_rows` lists the rows of each chunk."""
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)
@@ -109,4 +112,4 @@ def make_case(B, H, d, Nq, chunk_rows, dtype="bf16", seed=0, device="cpu",
             k_offs.append(s)
             s += n
     return {"Q": Q, "K": K, "V": V, "dO": dO, "k_offs": list(k_offs),
-            "q_off": q_off, "causal": causal, "scale": 1.0 / math.sqrt(d)}
+            "q_off": q_off, "causal": causal, "window": window, "scale": 1.0 / math.sqrt(d)}

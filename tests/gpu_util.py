@@ -60,11 +60,13 @@ def compare_all_heads(case, dtype, O, lse, dQ=None, dKs=None, dVs=None, heads=No
     for b in range(Bt):
         for h in (range(H) if heads is None else heads):
             Q, K, V, dO, qp, kp = head_inputs(case, b, h)
-            O_ref, lse_ref = orc.full_forward(Q, K, V, case["scale"], case["causal"], qp, kp)
+            O_ref, lse_ref = orc.full_forward(Q, K, V, case["scale"], case["causal"], qp, kp,
+                                              window=case.get("window", 0))
             check(f"O[{b},{h}]", f64(O[b, h]), O_ref, dtype)
             check(f"lse[{b},{h}]", f64(lse[b, h]), lse_ref, dtype, "lse")
             if dQ is not None:
-                dQ_ref, dK_ref, dV_ref = orc.full_backward(Q, K, V, dO, case["scale"], case["causal"], qp, kp)
+                dQ_ref, dK_ref, dV_ref = orc.full_backward(Q, K, V, dO, case["scale"], case["causal"], qp, kp,
+                                                           window=case.get("window", 0))
                 check(f"dQ[{b},{h}]", f64(dQ[b, h]), dQ_ref, dtype)
                 d = Q.shape[1]
                 dK = np.concatenate([f64(x[b, h]) for x in dKs]) if dKs else np.zeros((0, d))

@@ -23,7 +23,7 @@ DEV = "cuda:0"
 def run_workload(w, backward=True):
     inp = workloads.make_inputs(w, DEV)
     k_offs = [w.k_off(j) for j in range(w.G)]
-    walk = RingWalk(inp["Q"], w.scale, w.causal, w.q_off)
+    walk = RingWalk(inp["Q"], w.scale, w.causal, w.q_off, w.window)
     O, lse = walk.forward(inp["K"], inp["V"], k_offs)
     dQ = dKs = dVs = None
     if backward:
@@ -42,10 +42,10 @@ def head_arrays(inp, h):
 def check_complete_head(w, inp, h, O, lse, dQ, dKs, dVs):
     Q, K, V, dO = head_arrays(inp, h)
     qp, kp = w.q_off + np.arange(w.Nq), np.arange(K.shape[0])
-    O_ref, lse_ref = orc.full_forward(Q, K, V, w.scale, w.causal, qp, kp)
+    O_ref, lse_ref = orc.full_forward(Q, K, V, w.scale, w.causal, qp, kp, window=w.window)
     check(f"O[h{h}]", f64(O[0, h]), O_ref, w.dtype)
     check(f"lse[h{h}]", f64(lse[0, h]), lse_ref, w.dtype, "lse")
-    dQ_ref, dK_ref, dV_ref = orc.full_backward(Q, K, V, dO, w.scale, w.causal, qp, kp)
+    dQ_ref, dK_ref, dV_ref = orc.full_backward(Q, K, V, dO, w.scale, w.causal, qp, kp, window=w.window)
     check(f"dQ[h{h}]", f64(dQ[0, h]), dQ_ref, w.dtype)
     check(f"dK[h{h}]", np.concatenate([f64(x[0, h]) for x in dKs]), dK_ref, w.dtype)
     check(f"dV[h{h}]", np.concatenate([f64(x[0, h]) for x in dVs]), dV_ref, w.dtype)
@@ -56,11 +56,11 @@ def check_sampled_rows(w, inp, h, O, lse, dQ, n_rows=64, seed=0):
     rows = np.sort(np.random.default_rng(seed + h).choice(w.Nq, size=n_rows, replace=False))
     rows[0], rows[-1] = 0, w.Nq - 1                      # always include the first and last row
     qp, kp = w.q_off + rows, np.arange(K.shape[0])
-    O_ref, lse_ref = orc.full_forward(Q[rows], K, V, w.scale, w.causal, qp, kp)
+    O_ref, lse_ref = orc.full_forward(Q[rows], K, V, w.scale, w.causal, qp, kp, window=w.window)
     check(f"O[h{h},rows]", f64(O[0, h])[rows], O_ref, w.dtype)
     check(f"lse[h{h},rows]", f64(lse[0, h])[rows], lse_ref, w.dtype, "lse")
     if dQ is not None:
-        dQ_ref, _, _ = orc.full_backward(Q[rows], K, V, dO[rows], w.scale, w.causal, qp, kp)
+        dQ_ref, _, _ = orc.full_backward(Q[rows], K, V, dO[rows], w.scale, w.causal, qp, kp, window=w.window)
         check(f"dQ[h{h},rows]", f64(dQ[0, h])[rows], dQ_ref, w.dtype)
 
 
@@ -116,3 +116,19 @@ def test_llama7b_1m_G32_streaming_sampled_rows_and_identities():
     for h in (0, w.H - 1):
         check_sampled_rows(w, inp, h, O, lse, dQ, n_rows=32)
     check_identities(w, inp, 0, dQ, dKs, dVs)
+
+
+def test_llama7b_32k_last_rank_causal_sliding_window():
+    """Sec. 2.6 at full shape: the 7B slice of the last rank of a 32K ring, causal, window 6000:
+    five of the eight chunks lie outside every row's window and are skipped, the others are cut
+    by the window's far edge and by the diagonal."""
+    w = workloads.Workload("llama7b_32k_G8_rank7_causal_window6000", 1, 32, 128, 4096, 8, 4096, "bf16", True,
+                           7 * 4096, 2011, window=6000)
+    assert w.visible_pairs_per_head() == sum(min(6000, 7 * 4096 + r + 1) for r in range(4096))
+    inp, k_offs, walk, O, lse, dQ, dKs, dVs = run_workload(w)
+    check_complete_head(w, inp, w.H - 1, O, lse, dQ, dKs, dVs)
+    for h in (0, 13):
+        check_sampled_rows(w, inp, h, O, lse, dQ)
+    check_identities(w, inp, 6, dQ, dKs, dVs)
+    for j in range(5):                                     # chunks 0..4 are out of every window
+        assert float(dKs[j].abs().max()) == 0.0 and float(dVs[j].abs().max()) == 0.0

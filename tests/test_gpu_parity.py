@@ -14,7 +14,7 @@ DEV = "cuda:0"
 
 
 def run_case(case, dtype, backward=True, use_D=True, order=None):
-    walk = RingWalk(case["Q"], case["scale"], case["causal"], case["q_off"])
+    walk = RingWalk(case["Q"], case["scale"], case["causal"], case["q_off"], case.get("window", 0))
     O, lse = walk.forward(case["K"], case["V"], case["k_offs"], order=order)
     res = (O, lse, None, None, None)
     if backward:
@@ -36,6 +36,13 @@ BF16_CASES = [
     dict(B=1, H=2, d=128, Nq=130, chunk_rows=[100, 260], causal=True, q_off=50,
          k_offs=[0, 400]),                                                 # second chunk fully masked
     dict(B=1, H=1, d=128, Nq=100, chunk_rows=[64, 64], causal=True, q_off=-30),         # rows that see nothing
+    # sliding window (Sec. 2.6): band narrower than a tile, wider than a workgroup, chunks fully outside it
+    dict(B=1, H=2, d=128, Nq=600, chunk_rows=[256, 200, 344], causal=True, q_off=200, window=40),
+    dict(B=1, H=2, d=128, Nq=700, chunk_rows=[512, 512], causal=True, q_off=324, window=300),
+    dict(B=1, H=1, d=128, Nq=520, chunk_rows=[300, 300, 300], causal=False, q_off=100, window=130),
+    dict(B=1, H=1, d=128, Nq=300, chunk_rows=[128, 128, 128, 128], causal=True, q_off=2000, window=64,
+         k_offs=[0, 1800, 1928, 2200]),                                    # first chunk out of every window
+    dict(B=2, H=1, d=128, Nq=130, chunk_rows=[257], causal=True, q_off=60, window=1),   # each row sees one key
 ]
 
 
@@ -60,6 +67,8 @@ GENERIC_CASES = [
     ("f32", dict(B=1, H=1, d=7, Nq=5, chunk_rows=[3, 1])),
     ("bf16", dict(B=1, H=2, d=64, Nq=100, chunk_rows=[70, 90], causal=True, q_off=60)),
     ("bf16", dict(B=1, H=1, d=96, Nq=33, chunk_rows=[64])),
+    ("f32", dict(B=1, H=2, d=64, Nq=90, chunk_rows=[50, 70], causal=True, q_off=30, window=17)),
+    ("bf16", dict(B=1, H=1, d=64, Nq=80, chunk_rows=[100], causal=False, q_off=10, window=25)),
 ]
 
 
