@@ -13,10 +13,14 @@
 // rows (their Q fragments stay in registers as B operands, their dO rows stay in LDS for the
 // whole kernel) and walks the chunk in tiles of 32 keys.  With S^T = K Q^T every lane owns one query row, so lse and D are
 // per-lane scalars, and the dS^T accumulators already have the B-operand layout that
-// dQ^T += K^T dS^T needs (K^T comes through transposing LDS reads).  Same machinery as the
-// forward kernel: dQ^T accumulators pinned in AGPRs, two (S, dP) buffers that swap roles
-// each tile, the 48 MFMAs of a tile hand-interleaved with the vector work, K/V tiles DMA-ed
-// from HBM into LDS rings two tiles ahead, one barrier per tile.
+// dQ^T += K^T dS^T needs (K^T comes through transposing LDS reads).  dQ^T accumulators are
+// pinned in AGPRs; K/V tiles are DMA-ed from HBM into LDS rings three tiles ahead, one barrier
+// per tile.  The 48 MFMAs of a tile run in three phases of 16, each carrying the vector work of
+// a neighbouring phase so that no phase waits for it:
+//   1: S^T of tile t          2: dP^T of tile t + exp2 of tile t (P^T replaces S^T in place)
+//   3: dQ^T products of tile t-1 (its dS^T fragments were finished a step ago) + dS^T of tile t
+// Only the 16-register dS^T fragment sets exist twice; everything fits the register file
+// without shuttling accumulators through AGPRs.
 #include "burst_bwd_common.h"
 
 namespace burst {
@@ -24,8 +28,8 @@ namespace burst {
 constexpr int DQ_BR = 256;            // query rows per workgroup (4 wavefronts x 64)
 constexpr int DQ_BC = 32;             // keys per tile
 constexpr int DQ_TILE_BYTES = DQ_BC * 256;
-constexpr int DQ_KSLOTS = 4;          // K of tile t is read in steps t-1 (S) and t (dQ)
-constexpr int DQ_VSLOTS = 3;
+constexpr int DQ_KSLOTS = 5;          // K of tiles t-1 (dQ), t (S), t+1, t+2 (landed), t+3 (in flight)
+constexpr int DQ_VSLOTS = 4;          // V of tiles t (dP), t+1, t+2, t+3
 constexpr int DQ_GBASE = (DQ_KSLOTS + DQ_VSLOTS) * DQ_TILE_BYTES;   // dO block of the workgroup: 256 rows
 constexpr int DQ_LDS_BYTES = DQ_GBASE + DQ_BR * 256;
 
@@ -149,59 +153,77 @@ burst_bwd_dq_kernel(BwdArgs a) {
         dma_tile(krs, lds0 + t * DQ_TILE_BYTES, il, t);
         dma_tile(vrs, lds0 + VBASE + t * DQ_TILE_BYTES, il, t);
       }
-    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): this wavefront's DMA has landed
+    {
+      // the slot of "tile -1" feeds the first, all-zero dQ^T products: clear it
+      const i32x4 z = {0, 0, 0, 0};
+      *reinterpret_cast<i32x4*>(smem + (DQ_KSLOTS - 1) * DQ_TILE_BYTES + tid * 32) = z;
+      *reinterpret_cast<i32x4*>(smem + (DQ_KSLOTS - 1) * DQ_TILE_BYTES + tid * 32 + 16) = z;
+    }
+    __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0), lgkmcnt(0): this wavefront's DMA and stores are done
     __builtin_amdgcn_s_barrier();
 
-    // S^T and dP^T of a tile: [row block] accumulators of 32 keys x 32 rows
-    auto sdp_tile = [&](const char* kl, const char* vl, f32x16 (&s)[2], f32x16 (&dp)[2]) __attribute__((always_inline)) {
+    const long long wave_first_q = a.q_off + q0;
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    f32x16 s[2], dp[2];      // S^T (then P^T, in place) and dP^T of the current tile: [row block], 32 keys x 32 rows
+    bf16x8 kfq[3];           // K fragments (A of S^T), read two k-steps ahead; the first two of a tile
+                             // are fetched at the end of the previous step
+    kfq[0] = lds_read_b128(smem, abase);
+    kfq[1] = lds_read_b128(smem, abase ^ (1 << 5));
+
+    // dQ^T += K^T dS^T of one tile: 16 MFMAs (K^T fragment tf = kg*4 + db feeds both row blocks).
+    // `extra(i)` is called once per slice after the MFMA (vector work / DMA that rides along).
+    auto dq_phase = [&](const char* kl_prev, const bf16x8 (&dsp)[2][2], auto extra) __attribute__((always_inline)) {
+      constexpr int TRING = 3;
+      bf16x4 tq[TRING][2];
 #pragma unroll
-      for (int rb = 0; rb < 2; rb++)
+      for (int tn = 0; tn < 2; tn++) {
+        tq[tn][0] = lds_read_tr(kl_prev, taddr[tn & 3][0]);
+        tq[tn][1] = lds_read_tr(kl_prev, taddr[tn & 3][1]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int r = 0; r < 16; r++) { s[rb][r] = 0.f; dp[rb][r] = 0.f; }
-#pragma unroll
-      for (int ks = 0; ks < 8; ks++) {
-        bf16x8 kf = lds_read_b128(kl, abase ^ (ks << 5));
-        bf16x8 vf = lds_read_b128(vl, abase ^ (ks << 5));
-#pragma unroll
-        for (int rb = 0; rb < 2; rb++) {
-          bf16x8 gfr = lds_read_b128(gl, rb * 32 * 256 + (abase ^ (ks << 5)));
-          s[rb] = mfma32(kf, qf[rb][ks], s[rb]);
-          dp[rb] = mfma32(vf, gfr, dp[rb]);
+      for (int i = 0; i < 16; i++) {
+        const int tf = i >> 1, kg = tf >> 2, db = tf & 3, rb = i & 1;
+        if ((i & 1) == 0 && tf + 2 < 8) {
+          const int tn = tf + 2;
+          tq[tn % TRING][0] = lds_read_tr(kl_prev, (tn >> 2) * 16 * 256 + taddr[tn & 3][0]);
+          tq[tn % TRING][1] = lds_read_tr(kl_prev, (tn >> 2) * 16 * 256 + taddr[tn & 3][1]);
         }
+        mfma32_acc(dq[rb][db], cat4(tq[tf % TRING][0], tq[tf % TRING][1]), dsp[rb][kg]);
+        extra(i);
+        __builtin_amdgcn_sched_barrier(0);
       }
     };
-    f32x16 sA[2], dpA[2], sB[2], dpB[2];
-    sdp_tile(smem, smem + VBASE, sA, dpA);
 
-    const long long wave_first_q = a.q_off + q0;
-
-    // One tile: (sc, dpc) hold S^T, dP^T of tile kt; (sx, dpx) receive those of tile kt + 1.
-    auto step = [&](f32x16 (&sc)[2], f32x16 (&dpc)[2], f32x16 (&sx)[2], f32x16 (&dpx)[2], int kt, int kslot,
-                    int vslot) __attribute__((always_inline)) {
-      const int kslot1 = (kslot + 1) & 3;                       // K of tile kt + 1
-      const int kslot3 = (kslot + 3) & 3;                       // K of tile kt + 3 replaces K of tile kt - 1
-      const int vslot1 = (vslot == DQ_VSLOTS - 1) ? 0 : vslot + 1;   // V of tile kt + 1; V of kt + 3 replaces V of kt
-      const char* kl_next = smem + kslot1 * DQ_TILE_BYTES;
-      const char* vl_next = smem + VBASE + vslot1 * DQ_TILE_BYTES;
+    // One step = tile kt: S^T(kt), then dP^T(kt) with the exponentials riding along, then the
+    // dQ^T products of tile kt - 1 (whose dS^T fragments `dsp` were finished one step ago) with the
+    // dS of tile kt riding along into `dsc`.  kslot / vslot: ring slots of tile kt.
+    auto step = [&](const bf16x8 (&dsp)[2][2], bf16x8 (&dsc)[2][2], int kt, int kslot, int vslot) __attribute__((always_inline)) {
       const char* kl = smem + kslot * DQ_TILE_BYTES;
-      const unsigned k_dst = lds0 + kslot3 * DQ_TILE_BYTES;
-      const unsigned v_dst = lds0 + VBASE + vslot * DQ_TILE_BYTES;
-      // Operand queue for the first 32 slices, one LDS read per slice, LEAD slices ahead of its
-      // use.  Read j = 4*ks + m: m = 0 K fragment (A of S^T, slices 4ks, 4ks+1), m = 1 V fragment
-      // (A of dP^T, slices 4ks+2, 4ks+3), m = 2 / 3 dO fragments of row block 0 / 1 (B of dP^T).
-      constexpr int LEAD = 4, RING = LEAD + 3;
-      bf16x8 fq[RING];
-      auto issue_read = [&](int j) __attribute__((always_inline)) {
-        const int ks = j >> 2, m = j & 3;
-        const int off = abase ^ (ks << 5);
-        fq[j % RING] = (m == 0) ? lds_read_b128(kl_next, off)
-                     : (m == 1) ? lds_read_b128(vl_next, off)
-                                : lds_read_b128(gl, (m - 2) * 32 * 256 + off);
-      };
+      const int kprev = (kslot == 0) ? DQ_KSLOTS - 1 : kslot - 1;
+      const int knext = (kslot == DQ_KSLOTS - 1) ? 0 : kslot + 1;
+      const char* kl_prev = smem + kprev * DQ_TILE_BYTES;                    // K of tile kt - 1
+      const char* kl_next = smem + knext * DQ_TILE_BYTES;                    // K of tile kt + 1 (landed a step ago)
+      const char* vl = smem + VBASE + vslot * DQ_TILE_BYTES;
+      int k3 = kslot + 3; if (k3 >= DQ_KSLOTS) k3 -= DQ_KSLOTS;             // K of tile kt + 3 replaces K of tile kt - 2
+      const int v3 = (vslot + 3) & 3;                                        // V of tile kt + 3 replaces V of tile kt - 1
+      const unsigned k_dst = lds0 + k3 * DQ_TILE_BYTES;
+      const unsigned v_dst = lds0 + VBASE + v3 * DQ_TILE_BYTES;
+      bf16x8 vfq[3], gfq[4];   // V fragments (A of dP^T) and dO fragments (B of dP^T) of the wavefront's rows
+      // ---- slices 0..15: S^T = K Q^T (k-step ks = i / 2, row block i % 2)
 #pragma unroll
-      for (int j = 0; j < LEAD; j++) issue_read(j);
-      // ---- masking (diagonal tiles, ragged key tail): rare.  A masked score becomes -inf,
-      // its P and dS become 0.
+      for (int i = 0; i < 16; i++) {
+        const int ks = i >> 1, rb = i & 1;
+        if (rb == 0 && ks + 2 < 8) kfq[(ks + 2) % 3] = lds_read_b128(kl, abase ^ ((ks + 2) << 5));
+        if (i == 12) vfq[0] = lds_read_b128(vl, abase);
+        if (i == 13) gfq[0] = lds_read_b128(gl, abase);
+        if (i == 14) gfq[1] = lds_read_b128(gl, 32 * 256 + abase);
+        if (i == 15) vfq[1] = lds_read_b128(vl, abase ^ (1 << 5));
+        s[rb] = mfma32(kfq[ks % 3], qf[rb][ks], ks == 0 ? zero16 : s[rb]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // ---- masking (diagonal tiles, window edge, ragged key tail): rare.  A masked score becomes
+      // -inf, its P and dS become 0.
       const long long tile_first_k = k_off + (long long)kt * DQ_BC;
       const bool need_mask = (a.causal && tile_first_k + DQ_BC - 1 > wave_first_q) ||
                              (window > 0 && tile_first_k < wave_first_q + 63 - window + 1) ||
@@ -224,76 +246,81 @@ burst_bwd_dq_kernel(BwdArgs a) {
 #pragma unroll
           for (int r = 0; r < 16; r++) {
             const int cpart = 8 * (r >> 2) + (r & 3);
-            sc[rb][r] = (cpart <= lim && cpart >= lim_lo) ? sc[rb][r] : BURST_NEG_INF;
+            s[rb][r] = (cpart <= lim && cpart >= lim_lo) ? s[rb][r] : BURST_NEG_INF;
           }
         }
       }
-      bf16x8 dsf[2][2];    // dS^T fragments (B operand): [row block][16-key group]
-      constexpr int TRING = 3;                     // K^T fragments: LEAD / 2 = 2 ahead
-      bf16x4 tq[TRING][2];
-      auto ds_pair = [&](int pidx) __attribute__((always_inline)) {   // pidx = kg * 8 + rb * 4 + t / 2
-        const int kg = pidx >> 3, srb = (pidx >> 2) & 1, t = (pidx & 3) * 2;
-        const int r = 8 * kg + t;
-        float p0 = fast_exp2(__builtin_fmaf(sc[srb][r], a.c, nlse2[srb]));
-        float p1 = fast_exp2(__builtin_fmaf(sc[srb][r + 1], a.c, nlse2[srb]));
-        float d0 = p0 * (dpc[srb][r] - Dv[srb]);
-        float d1 = p1 * (dpc[srb][r + 1] - Dv[srb]);
-        dsf[srb][kg][t] = (bf16)d0;
-        dsf[srb][kg][t + 1] = (bf16)d1;
-      };
-#pragma unroll
-      for (int rb = 0; rb < 2; rb++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) { sx[rb][r] = 0.f; dpx[rb][r] = 0.f; }
       __builtin_amdgcn_sched_barrier(0);
-      // ---- slices 0..31: S^T and dP^T of the next tile, with the 16 dS pairs of this tile.
-      // After the last tile the products read stale buffers and are discarded.
-#pragma unroll
-      for (int i = 0; i < 32; i++) {
-        const int ks = i >> 2, m = i & 3, rb = i & 1;
-        if (i + LEAD < 32) issue_read(i + LEAD);
-        if (i + LEAD >= 32 && ((i + LEAD) & 1) == 0) {   // first K^T fragments of the last 16 slices
-          const int tn = (i + LEAD - 32) >> 1;
-          tq[tn][0] = lds_read_tr(kl, taddr[tn & 3][0]);
-          tq[tn][1] = lds_read_tr(kl, taddr[tn & 3][1]);
-        }
-        if (m < 2) sx[rb] = mfma32(fq[(4 * ks) % RING], qf[rb][ks], sx[rb]);
-        else dpx[rb] = mfma32(fq[(4 * ks + 1) % RING], fq[(4 * ks + m) % RING], dpx[rb]);
-        if (i & 1) ds_pair(i >> 1);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      // ---- slices 32..47: dQ^T += K^T dS^T, with the DMA of tiles kt + 3
+      // ---- slices 16..31: dP^T = V dO^T; P^T = exp2(c S^T - lse log2 e) of score pair i replaces S^T
 #pragma unroll
       for (int i = 0; i < 16; i++) {
-        const int tf = i >> 1;                     // K^T fragment: kg = tf / 4, db = tf % 4
-        const int kg = tf >> 2, db = tf & 3, rb = i & 1;
-        if ((i & 1) == 0 && tf + 2 < 8) {
-          const int tn = tf + 2;
-          tq[tn % TRING][0] = lds_read_tr(kl, (tn >> 2) * 16 * 256 + taddr[tn & 3][0]);
-          tq[tn % TRING][1] = lds_read_tr(kl, (tn >> 2) * 16 * 256 + taddr[tn & 3][1]);
+        const int ks = i >> 1, rb = i & 1;
+        if (rb == 0 && ks + 2 < 8) vfq[(ks + 2) % 3] = lds_read_b128(vl, abase ^ ((ks + 2) << 5));
+        if (i + 2 < 16) gfq[(i + 2) % 4] = lds_read_b128(gl, ((i + 2) & 1) * 32 * 256 + (abase ^ (((i + 2) >> 1) << 5)));
+        dp[rb] = mfma32(vfq[ks % 3], gfq[i % 4], ks == 0 ? zero16 : dp[rb]);
+        {
+          const int prb = i >> 3, r = 2 * (i & 7);
+          float p0 = fast_exp2(__builtin_fmaf(s[prb][r], a.c, nlse2[prb]));
+          float p1 = fast_exp2(__builtin_fmaf(s[prb][r + 1], a.c, nlse2[prb]));
+          asm volatile("" : "+v"(p0), "+v"(p1));   // keep the arithmetic in this slice
+          s[prb][r] = p0; s[prb][r + 1] = p1;
         }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // ---- slices 32..47: dQ^T(kt - 1) += K^T dS^T; dS^T = P^T o (dP^T - D) of score pair i of
+      // tile kt rides along, and so do the DMA of tile kt + 3 and the first K reads of tile kt + 1
+      dq_phase(kl_prev, dsp, [&](int i) __attribute__((always_inline)) {
+        const int prb = i >> 3, r = 2 * (i & 7), kg = r >> 3, t = r & 7;
+        // (the empty asm statements order this slice's arithmetic after the slice's MFMA, which is
+        // an asm statement too: the compiler would otherwise clump two MFMAs and two slices of
+        // vector work, and an in-order wavefront then stalls behind the second MFMA)
+        float x0 = dp[prb][r], x1 = dp[prb][r + 1];
+        asm volatile("" : "+v"(x0), "+v"(x1));
+        float d0 = s[prb][r] * (x0 - Dv[prb]);
+        float d1 = s[prb][r + 1] * (x1 - Dv[prb]);
+        bf16x2 pk;
+        pk[0] = (bf16)d0; pk[1] = (bf16)d1;
+        unsigned pu = __builtin_bit_cast(unsigned, pk);
+        asm volatile("" : "+v"(pu));               // keep the arithmetic in this slice
+        pk = __builtin_bit_cast(bf16x2, pu);
+        dsc[prb][kg][t] = pk[0]; dsc[prb][kg][t + 1] = pk[1];
         if ((i & 3) == 1) {
           const int j = i >> 2;                    // 0, 1 -> K of tile kt + 3; 2, 3 -> V of tile kt + 3
           if (j < 2) dma_tile(krs, k_dst, j, kt + 3);
           else dma_tile(vrs, v_dst, j - 2, kt + 3);
         }
-        mfma32_acc(dq[rb][db], cat4(tq[tf % TRING][0], tq[tf % TRING][1]), dsf[rb][kg]);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      // The 4 DMA loads just issued may stay in flight; older ones must have landed.
+        if (i == 14) kfq[0] = lds_read_b128(kl_next, abase);
+        if (i == 15) kfq[1] = lds_read_b128(kl_next, abase ^ (1 << 5));
+      });
+      // The 4 DMA loads just issued may stay in flight; older ones (tile kt + 2) must have landed.
       __builtin_amdgcn_s_waitcnt(0x0F74);          // vmcnt(4)
       __builtin_amdgcn_s_barrier();
     };
 
+    // dS^T fragments (B operands of dQ^T): [row block][16-key group], two sets that swap roles
+    bf16x8 dsA[2][2], dsB[2][2];
+#pragma unroll
+    for (int rb = 0; rb < 2; rb++)
+#pragma unroll
+      for (int kg = 0; kg < 2; kg++)
+#pragma unroll
+        for (int t = 0; t < 8; t++) { dsA[rb][kg][t] = (bf16)0.0f; dsB[rb][kg][t] = (bf16)0.0f; }
+    // tiles are taken in pairs; an odd count is rounded up (the extra tile lies past the end of the
+    // chunk: its K / V read as zeros and every score of it is masked)
+    const int ntiles2 = (ntiles + 1) & ~1;
     int kslot = 0, vslot = 0;
-    for (int kt = 0; kt < ntiles; kt += 2) {
-      step(sA, dpA, sB, dpB, kt, kslot, vslot);
-      kslot = (kslot + 1) & 3;
-      vslot = (vslot == DQ_VSLOTS - 1) ? 0 : vslot + 1;
-      if (kt + 1 >= ntiles) break;
-      step(sB, dpB, sA, dpA, kt + 1, kslot, vslot);
-      kslot = (kslot + 1) & 3;
-      vslot = (vslot == DQ_VSLOTS - 1) ? 0 : vslot + 1;
+    for (int kt = 0; kt < ntiles2; kt += 2) {
+      step(dsB, dsA, kt, kslot, vslot);
+      kslot = (kslot == DQ_KSLOTS - 1) ? 0 : kslot + 1;
+      vslot = (vslot + 1) & 3;
+      step(dsA, dsB, kt + 1, kslot, vslot);
+      kslot = (kslot == DQ_KSLOTS - 1) ? 0 : kslot + 1;
+      vslot = (vslot + 1) & 3;
+    }
+    // the dQ^T products of the last tile
+    {
+      const int kprev = (kslot == 0) ? DQ_KSLOTS - 1 : kslot - 1;
+      dq_phase(smem + kprev * DQ_TILE_BYTES, dsB, [&](int) __attribute__((always_inline)) {});
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): no DMA may outlive the loop
   }
