@@ -297,3 +297,49 @@ def test_error_codes_on_device_buffers():
         B.burst_state_init(x, x, x, bad)
     assert e.value.code == -3
     assert torch.all(x == 0)                                     # nothing was written
+
+
+def test_no_kernel_writes_outside_its_buffers():
+    """Every output buffer sits between guard bands filled with a pattern; after the whole path has run
+    on ragged shapes (tails in rows, keys and heads) the bands must be untouched, and so must the
+    read-only inputs."""
+    case = workloads.make_case(B=1, H=3, d=128, Nq=333, chunk_rows=[257, 95], dtype="bf16", seed=47, device=DEV,
+                               causal=True, q_off=40, window=200)
+    G = 4096                                    # guard elements on each side
+    def guarded(shape, dtype, fill=None):
+        n = int(np.prod(shape))
+        pat = 12345.0 if dtype != torch.bfloat16 else 77.0
+        flat = torch.full((n + 2 * G,), pat, device=DEV, dtype=dtype)
+        view = flat[G:G + n].view(*shape)
+        if fill is not None:
+            view.fill_(fill)
+        return flat, view, pat
+    Bt, H, Nq, d = case["Q"].shape
+    bufs = {}
+    for name, shape, dt in (("O_acc", (Bt, H, Nq, d), torch.float32), ("m", (Bt, H, Nq), torch.float32),
+                            ("l", (Bt, H, Nq), torch.float32), ("O", (Bt, H, Nq, d), torch.bfloat16),
+                            ("lse", (Bt, H, Nq), torch.float32), ("D", (Bt, H, Nq), torch.float32),
+                            ("dQ", (Bt, H, Nq, d), torch.float32)):
+        bufs[name] = guarded(shape, dt, 0.0 if name == "dQ" else None)
+    dK = [guarded(tuple(k.shape), torch.float32) for k in case["K"]]
+    dV = [guarded(tuple(k.shape), torch.float32) for k in case["K"]]
+    inputs_before = [t.clone() for t in (case["Q"], case["dO"], *case["K"], *case["V"])]
+    prm = lambda Nc, ko: B.params(Bt, H, Nq, Nc, d, torch.bfloat16, case["scale"], True, case["q_off"], ko, case["window"])
+    v = {k: t[1] for k, t in bufs.items()}
+    B.burst_state_init(v["O_acc"], v["m"], v["l"], prm(0, 0))
+    for K, V, ko in zip(case["K"], case["V"], case["k_offs"]):
+        B.burst_local_fwd(case["Q"], K, V, v["O_acc"], v["m"], v["l"], prm(K.shape[2], ko))
+    B.burst_finalize(v["O_acc"], v["m"], v["l"], v["O"], v["lse"], prm(0, 0))
+    B.burst_bwd_prepare(v["O"], case["dO"], v["D"], prm(0, 0))
+    for j, (K, V, ko) in enumerate(zip(case["K"], case["V"], case["k_offs"])):
+        B.burst_local_bwd(case["Q"], K, V, v["O"], case["dO"], v["lse"], v["D"], v["dQ"], dK[j][1], dV[j][1],
+                          prm(K.shape[2], ko), accumulate_dq=True, accumulate_dkv=False)
+    torch.cuda.synchronize()
+    for name, (flat, view, pat) in list(bufs.items()) + [(f"dK{j}", t) for j, t in enumerate(dK)] + \
+            [(f"dV{j}", t) for j, t in enumerate(dV)]:
+        n = view.numel()
+        assert bool((flat[:G] == pat).all()) and bool((flat[G + n:] == pat).all()), f"guard band of {name} was written"
+    for before, now in zip(inputs_before, (case["Q"], case["dO"], *case["K"], *case["V"])):
+        assert torch.equal(before, now)
+    # and the results are the right ones
+    compare_all_heads(case, "bf16", v["O"], v["lse"], v["dQ"], [t[1] for t in dK], [t[1] for t in dV])
