@@ -140,23 +140,36 @@ def main():
     ev = {k: [] for k in ("fwd", "dq", "dkv")}
 
     def step(timed):
-        def bracket(kind, fn):
-            if not timed:
-                fn()
-                return
-            e0, e1 = B.Event(), B.Event()
-            e0.record(); fn(); e1.record()
-            ev[kind].append((e0, e1))
+        # Consecutive MFMA-kernel launches share one event (end of one = start of the next), so a
+        # timed step records 26 events instead of 48; the stream is never idle between them.
+        def mark():
+            e = B.Event()
+            e.record()
+            return e
         walk.init()
+        prev = mark() if timed else None
         for j in range(w.G):
-            bracket("fwd", lambda: walk.step(Ks[j], Vs[j], k_offs[j]))
+            walk.step(Ks[j], Vs[j], k_offs[j])
+            if timed:
+                cur = mark()
+                ev["fwd"].append((prev, cur))
+                prev = cur
         walk.finalize()
         walk.prepare(dO)
         dQ.zero_()
+        prev = mark() if timed else None
         for j in range(w.G):
             p = walk.params(w.Nc, k_offs[j])
-            bracket("dq", lambda: B.burst_local_bwd_dq(Q, Ks[j], Vs[j], dO, walk.lse, walk.D, dQ, p, True))
-            bracket("dkv", lambda: B.burst_local_bwd_dkv(Q, Ks[j], Vs[j], dO, walk.lse, walk.D, dKs[j], dVs[j], p, False))
+            B.burst_local_bwd_dq(Q, Ks[j], Vs[j], dO, walk.lse, walk.D, dQ, p, True)
+            if timed:
+                cur = mark()
+                ev["dq"].append((prev, cur))
+                prev = cur
+            B.burst_local_bwd_dkv(Q, Ks[j], Vs[j], dO, walk.lse, walk.D, dKs[j], dVs[j], p, False)
+            if timed:
+                cur = mark()
+                ev["dkv"].append((prev, cur))
+                prev = cur
 
     if args.calibration_copy:
         src = torch.ones(64 * 1024 * 1024, device=dev, dtype=torch.float32)

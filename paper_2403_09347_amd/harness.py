@@ -164,3 +164,31 @@ class DoubleBufferedWalk(RingWalk):
                 self._view(vb, rows).copy_(src_Vs[j], non_blocking=True)
         torch.cuda.current_stream(self.Q.device).wait_stream(self.copy_stream)
 
+
+
+class SpanWalk:
+    """A device whose query rows are several contiguous spans of the sequence, each its own tensor
+    with its own global offset -- e.g. the two stripes of a load-balanced ("zig-zag") causal
+    assignment (workloads.zigzag_spans).  Every span keeps its own running state; dK / dV of a
+    chunk accumulate over the spans.  Chunks a span cannot see cost a kernel launch that returns
+    at once (whole-chunk skipping, paper Sec. 2.6)."""
+
+    def __init__(self, Q_spans, q_offs, scale, causal=True, window=0):
+        self.walks = [RingWalk(Q, scale, causal, off, window) for Q, off in zip(Q_spans, q_offs)]
+
+    def forward(self, Ks, Vs, k_offs):
+        return [w.forward(Ks, Vs, k_offs) for w in self.walks]
+
+    def backward(self, Ks, Vs, k_offs, dO_spans):
+        dev = Ks[0].device
+        dKs = [torch.empty(tuple(K.shape), device=dev, dtype=torch.float32) for K in Ks]
+        dVs = [torch.empty(tuple(V.shape), device=dev, dtype=torch.float32) for V in Vs]
+        dQs = []
+        for i, (w, dO) in enumerate(zip(self.walks, dO_spans)):
+            dQ = torch.zeros((w.Bt, w.H, w.Nq, w.d), device=dev, dtype=torch.float32)
+            w.prepare(dO)
+            for j in range(len(Ks)):
+                B.burst_local_bwd(w.Q, Ks[j], Vs[j], w.O, dO, w.lse, w.D, dQ, dKs[j], dVs[j],
+                                  w.params(Ks[j].shape[2], k_offs[j]), accumulate_dq=True, accumulate_dkv=(i > 0))
+            dQs.append(dQ)
+        return dQs, dKs, dVs

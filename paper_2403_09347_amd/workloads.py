@@ -73,6 +73,30 @@ WORKLOADS = [
 ]
 
 
+def contiguous_spans(N, G, rank):
+    """The paper's assignment (Sec. 2.2): rank r owns positions [r N/G, (r+1) N/G).
+    Returns a list of (first position, rows)."""
+    n = N // G
+    return [(rank * n, n)]
+
+
+def zigzag_spans(N, G, rank):
+    """Load-balanced causal assignment: the sequence is cut into 2G stripes of N/(2G) positions and
+    rank r owns stripes r and 2G-1-r, so that every rank sees the same number of causal
+    (query, key) pairs.  Returns a list of (first position, rows)."""
+    n = N // (2 * G)
+    return [(rank * n, n), ((2 * G - 1 - rank) * n, n)]
+
+
+def causal_pairs(spans, N):
+    """Unmasked (query, key) pairs of query spans against keys 0..N-1 under the causal mask."""
+    total = 0
+    for first, rows in spans:
+        lo, hi = min(first, N), min(first + rows, N)          # rows at positions >= N see all N keys
+        total += (hi * (hi + 1) - lo * (lo + 1)) // 2 + (first + rows - hi) * N
+    return total
+
+
 def by_name(name):
     for w in WORKLOADS:
         if w.name == name:

@@ -6,7 +6,7 @@ import torch
 from oracle import burst_oracle as orc
 from paper_2403_09347_amd import binding as B
 from paper_2403_09347_amd import workloads
-from paper_2403_09347_amd.harness import DoubleBufferedWalk, RingWalk
+from paper_2403_09347_amd.harness import DoubleBufferedWalk, RingWalk, SpanWalk
 from gpu_util import check, compare_all_heads, f64, head_inputs
 
 pytestmark = pytest.mark.gpu
@@ -343,3 +343,35 @@ def test_no_kernel_writes_outside_its_buffers():
         assert torch.equal(before, now)
     # and the results are the right ones
     compare_all_heads(case, "bf16", v["O"], v["lse"], v["dQ"], [t[1] for t in dK], [t[1] for t in dV])
+
+
+@pytest.mark.parametrize("rank", [0, 2, 3])
+def test_zigzag_rank_against_the_oracle(rank):
+    """Load-balanced causal assignment: a rank owns stripes r and 2G-1-r of the sequence; its two
+    query spans walk all 2G key/value stripes (most of them fully visible or skipped whole)."""
+    N, G, H, d = 1536, 4, 2, 128
+    n = N // (2 * G)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(900 + rank)
+    mk = lambda rows: torch.randn((1, H, rows, d), generator=gen, device=DEV).to(torch.bfloat16)
+    Ks, Vs = [mk(n) for _ in range(2 * G)], [mk(n) for _ in range(2 * G)]
+    k_offs = [i * n for i in range(2 * G)]
+    spans = workloads.zigzag_spans(N, G, rank)
+    Qs, dOs = [mk(rows) for _, rows in spans], [mk(rows) for _, rows in spans]
+    walk = SpanWalk(Qs, [first for first, _ in spans], 1.0 / np.sqrt(d), causal=True)
+    outs = walk.forward(Ks, Vs, k_offs)
+    dQs, dKs, dVs = walk.backward(Ks, Vs, k_offs, dOs)
+    torch.cuda.synchronize()
+    q_pos = np.concatenate([first + np.arange(rows) for first, rows in spans])
+    for h in range(H):
+        K = np.concatenate([f64(k[0, h]) for k in Ks])
+        V = np.concatenate([f64(v[0, h]) for v in Vs])
+        Q = np.concatenate([f64(q[0, h]) for q in Qs])
+        dO = np.concatenate([f64(g[0, h]) for g in dOs])
+        O_ref, lse_ref = orc.full_forward(Q, K, V, 1.0 / np.sqrt(d), True, q_pos, np.arange(N))
+        dQ_ref, dK_ref, dV_ref = orc.full_backward(Q, K, V, dO, 1.0 / np.sqrt(d), True, q_pos, np.arange(N))
+        check(f"O[h{h}]", np.concatenate([f64(o[0, h]) for o, _ in outs]), O_ref, "bf16")
+        check(f"lse[h{h}]", np.concatenate([f64(l[0, h]) for _, l in outs]), lse_ref, "bf16", "lse")
+        check(f"dQ[h{h}]", np.concatenate([f64(x[0, h]) for x in dQs]), dQ_ref, "bf16")
+        check(f"dK[h{h}]", np.concatenate([f64(x[0, h]) for x in dKs]), dK_ref, "bf16")
+        check(f"dV[h{h}]", np.concatenate([f64(x[0, h]) for x in dVs]), dV_ref, "bf16")

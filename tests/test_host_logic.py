@@ -60,3 +60,19 @@ def test_bench_reads_measured_traffic_from_profiles():
     assert bench.measured_traffic("no_such_kernel", "llama7b_32k_G8") is None
     v = bench.measured_traffic("burst_bwd_dkv_kernel", "llama7b_32k_G8")
     assert v is None or v > 100e6
+
+
+def test_zigzag_assignment_balances_causal_work():
+    N, G = 131072, 32
+    contiguous = [workloads.causal_pairs(workloads.contiguous_spans(N, G, r), N) for r in range(G)]
+    zigzag = [workloads.causal_pairs(workloads.zigzag_spans(N, G, r), N) for r in range(G)]
+    assert sum(contiguous) == sum(zigzag) == N * (N + 1) // 2
+    assert max(contiguous) > 60 * min(contiguous)              # rank 31 does 63x the work of rank 0
+    assert max(zigzag) == min(zigzag)                          # every rank does the same
+    # the spans tile the sequence exactly once
+    covered = sorted(span for r in range(G) for span in workloads.zigzag_spans(N, G, r))
+    assert covered == [(i * (N // (2 * G)), N // (2 * G)) for i in range(2 * G)]
+    # brute-force count on a small case
+    spans = workloads.zigzag_spans(64, 4, 1)
+    brute = sum(1 for first, rows in spans for q in range(first, first + rows) for k in range(64) if k <= q)
+    assert workloads.causal_pairs(spans, 64) == brute
