@@ -30,8 +30,28 @@ constexpr int DQ_BC = 32;             // keys per tile
 constexpr int DQ_TILE_BYTES = DQ_BC * 256;
 constexpr int DQ_KSLOTS = 5;          // K of tiles t-1 (dQ), t (S), t+1, t+2 (landed), t+3 (in flight)
 constexpr int DQ_VSLOTS = 4;          // V of tiles t (dP), t+1, t+2, t+3
-constexpr int DQ_GBASE = (DQ_KSLOTS + DQ_VSLOTS) * DQ_TILE_BYTES;   // dO block of the workgroup: 256 rows
-constexpr int DQ_LDS_BYTES = DQ_GBASE + DQ_BR * 256;
+constexpr int DQ_LDS_BYTES = (DQ_KSLOTS + DQ_VSLOTS) * DQ_TILE_BYTES;
+
+// dP^T MFMA: accumulator in VGPRs (the vector unit reads it next), B operand (a dO fragment of
+// the wavefront's own rows, resident for the whole kernel) in AGPRs, which this kernel otherwise
+// leaves half empty.  As inline assembly the instruction is invisible to the compiler's hazard
+// recognizer: the leading s_nop covers register copies the compiler may place right before (a
+// vector write must not be read by an MFMA within two cycles), the caller separates the last one
+// from the first vector read of the accumulator (mfma_vgpr_fence) and never issues two in a row
+// on the same accumulator.
+// The resident operand is declared read-write although the instruction only reads it: its value
+// then lives in AGPRs from one statement to the next, like the pinned accumulators; as a plain
+// input the compiler keeps its home in VGPRs and copies it over before every use.
+__device__ __forceinline__ void mfma32_dp_first(f32x16& acc, bf16x8 a, bf16x8& b_resident) {
+  asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %1, 0"
+               : "=&v"(acc), "+a"(b_resident) : "v"(a));   // early clobber: the result must not share registers with an operand
+}
+__device__ __forceinline__ void mfma32_dp(f32x16& acc, bf16x8 a, bf16x8& b_resident) {
+  asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %1, %0" : "+v"(acc), "+a"(b_resident) : "v"(a));
+}
+__device__ __forceinline__ void mfma_vgpr_fence(f32x16 (&acc)[2]) {
+  asm volatile("s_nop 15\n\ts_nop 3" : "+v"(acc[0]), "+v"(acc[1]));
+}
 
 // WINDOW = false compiles the sliding-window code away: this kernel uses every register of the
 // file, and the few values the window logic keeps alive would otherwise push others to scratch.
@@ -90,7 +110,8 @@ burst_bwd_dq_kernel(BwdArgs a) {
       for (int r = 0; r < 16; r++) dq[rb][db][r] = 0.f;
 
   if (ntiles > 0) {
-    bf16x8 qf[2][8];
+    bf16x8 qf[2][8];       // Q fragments of the wavefront's rows (B operand of S^T), VGPRs
+    bf16x8 gfr[2][8];      // dO fragments of the same rows (B operand of dP^T), AGPRs
     float nlse2[2], Dv[2];
 #pragma unroll
     for (int rb = 0; rb < 2; rb++) {
@@ -105,6 +126,7 @@ burst_bwd_dq_kernel(BwdArgs a) {
 #pragma unroll
         for (int t = 0; t < 8; t++) z[t] = (bf16)0.0f;
         qf[rb][ks] = ok ? *reinterpret_cast<const bf16x8*>(Qh + (size_t)row * 128 + ks * 16 + h * 8) : z;
+        gfr[rb][ks] = ok ? *reinterpret_cast<const bf16x8*>(Gh + (size_t)row * 128 + ks * 16 + h * 8) : z;
       }
     }
     // LDS addressing.  A-operand reads (128-bit): row lr, granule 2*ks + h; since 2*ks and
@@ -134,18 +156,6 @@ burst_bwd_dq_kernel(BwdArgs a) {
       dma_b128_to_lds(rs, lds_tile + (unsigned)(wu * 2 + il) * 1024u, tile * DQ_TILE_BYTES + goff[il]);
     };
     constexpr int VBASE = DQ_KSLOTS * DQ_TILE_BYTES;
-    // dO rows of the workgroup -> LDS once (64 wave-loads of 4 rows, 16 per wavefront); rows
-    // past Nq read as zeros
-    {
-      const __amdgpu_buffer_rsrc_t grs = make_rsrc(Gh, (unsigned)a.Nq * 256u);
-#pragma unroll
-      for (int il = 0; il < 16; il++) {
-        int row = 64 * w + 4 * il + (lane >> 4);
-        int off = row * 256 + (((lane & 15) ^ row_code(row)) << 4);
-        dma_b128_to_lds(grs, lds0 + DQ_GBASE + (unsigned)(wu * 16 + il) * 1024u, qb * DQ_BR * 256 + off);
-      }
-    }
-    const char* gl = smem + DQ_GBASE + w * 64 * 256;         // this wavefront's 64 dO rows
 #pragma unroll
     for (int t = 0; t < 3; t++)
 #pragma unroll
@@ -209,15 +219,13 @@ burst_bwd_dq_kernel(BwdArgs a) {
       const int v3 = (vslot + 3) & 3;                                        // V of tile kt + 3 replaces V of tile kt - 1
       const unsigned k_dst = lds0 + k3 * DQ_TILE_BYTES;
       const unsigned v_dst = lds0 + VBASE + v3 * DQ_TILE_BYTES;
-      bf16x8 vfq[3], gfq[4];   // V fragments (A of dP^T) and dO fragments (B of dP^T) of the wavefront's rows
+      bf16x8 vfq[3];           // V fragments (A of dP^T), read two k-steps ahead
       // ---- slices 0..15: S^T = K Q^T (k-step ks = i / 2, row block i % 2)
 #pragma unroll
       for (int i = 0; i < 16; i++) {
         const int ks = i >> 1, rb = i & 1;
         if (rb == 0 && ks + 2 < 8) kfq[(ks + 2) % 3] = lds_read_b128(kl, abase ^ ((ks + 2) << 5));
-        if (i == 12) vfq[0] = lds_read_b128(vl, abase);
-        if (i == 13) gfq[0] = lds_read_b128(gl, abase);
-        if (i == 14) gfq[1] = lds_read_b128(gl, 32 * 256 + abase);
+        if (i == 13) vfq[0] = lds_read_b128(vl, abase);
         if (i == 15) vfq[1] = lds_read_b128(vl, abase ^ (1 << 5));
         s[rb] = mfma32(kfq[ks % 3], qf[rb][ks], ks == 0 ? zero16 : s[rb]);
         __builtin_amdgcn_sched_barrier(0);
@@ -256,17 +264,22 @@ burst_bwd_dq_kernel(BwdArgs a) {
       for (int i = 0; i < 16; i++) {
         const int ks = i >> 1, rb = i & 1;
         if (rb == 0 && ks + 2 < 8) vfq[(ks + 2) % 3] = lds_read_b128(vl, abase ^ ((ks + 2) << 5));
-        if (i + 2 < 16) gfq[(i + 2) % 4] = lds_read_b128(gl, ((i + 2) & 1) * 32 * 256 + (abase ^ (((i + 2) >> 1) << 5)));
-        dp[rb] = mfma32(vfq[ks % 3], gfq[i % 4], ks == 0 ? zero16 : dp[rb]);
+        if (ks == 0) mfma32_dp_first(dp[rb], vfq[0], gfr[rb][0]);
+        else mfma32_dp(dp[rb], vfq[ks % 3], gfr[rb][ks]);
         {
+          // (the empty asm statements tie this slice's arithmetic between this slice's MFMA and
+          // the next one: all of them are asm statements and keep their order)
           const int prb = i >> 3, r = 2 * (i & 7);
-          float p0 = fast_exp2(__builtin_fmaf(s[prb][r], a.c, nlse2[prb]));
-          float p1 = fast_exp2(__builtin_fmaf(s[prb][r + 1], a.c, nlse2[prb]));
-          asm volatile("" : "+v"(p0), "+v"(p1));   // keep the arithmetic in this slice
+          float x0 = s[prb][r], x1 = s[prb][r + 1];
+          asm volatile("" : "+v"(x0), "+v"(x1));
+          float p0 = fast_exp2(__builtin_fmaf(x0, a.c, nlse2[prb]));
+          float p1 = fast_exp2(__builtin_fmaf(x1, a.c, nlse2[prb]));
+          asm volatile("" : "+v"(p0), "+v"(p1));
           s[prb][r] = p0; s[prb][r + 1] = p1;
         }
         __builtin_amdgcn_sched_barrier(0);
       }
+      mfma_vgpr_fence(dp);     // the last dP^T MFMAs have written their accumulators
       // ---- slices 32..47: dQ^T(kt - 1) += K^T dS^T; dS^T = P^T o (dP^T - D) of score pair i of
       // tile kt rides along, and so do the DMA of tile kt + 3 and the first K reads of tile kt + 1
       dq_phase(kl_prev, dsp, [&](int i) __attribute__((always_inline)) {
