@@ -29,7 +29,7 @@ constexpr int DKV_SLOTS = 3;
 constexpr int DKV_LDS_Q = 0;
 constexpr int DKV_LDS_G = DKV_SLOTS * DKV_TILE_BYTES;
 constexpr int DKV_STAT_SLOTS = 4;     // row statistics run one tile further ahead than the tiles
-constexpr int DKV_LDS_L = 2 * DKV_SLOTS * DKV_TILE_BYTES;              // -lse * log2(e) per row
+constexpr int DKV_LDS_L = 2 * DKV_SLOTS * DKV_TILE_BYTES;              // -lse / scale per row
 constexpr int DKV_LDS_D = DKV_LDS_L + DKV_STAT_SLOTS * DKV_BR * 4;     // -D per row
 constexpr int DKV_LDS_DUMMY = DKV_LDS_D + DKV_STAT_SLOTS * DKV_BR * 4; // sink of the padding DMA (256 B)
 constexpr int DKV_LDS_BYTES = DKV_LDS_DUMMY + 256;
@@ -77,10 +77,7 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     for (int r = 0; r < 16; r++) { dk[db][r] = 0.f; dv[db][r] = 0.f; }
 
   if (t_begin < ntiles_all) {
-    // K, V fragments (B operands: lane = key lr, 8 consecutive d).  K is multiplied by
-    // c = scale*log2(e) here, once (rounded to bf16 again: a relative perturbation of 2^-9 per
-    // element, below the rounding P gets anyway), so that the S accumulator, started at
-    // -lse*log2(e), directly holds the exponent of P = exp2(c S - lse log2 e).
+    // K, V fragments (B operands: lane = key lr, 8 consecutive d)
     bf16x8 kf[8], vf[8];
     {
       const int key = key0 + lr;
@@ -91,8 +88,6 @@ burst_bwd_dkv_kernel(BwdArgs a) {
         for (int t = 0; t < 8; t++) z[t] = (bf16)0.0f;
         kf[ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Kh + (size_t)key * 128 + ks * 16 + h * 8) : z;
         vf[ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Vh + (size_t)key * 128 + ks * 16 + h * 8) : z;
-#pragma unroll
-        for (int t = 0; t < 8; t++) kf[ks][t] = (bf16)((float)kf[ks][t] * a.c);
       }
     }
     // LDS addressing inside a 64-row tile.  A operands (128-bit): row rb*32 + lr, granule
@@ -125,10 +120,12 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     // Per-row statistics of a tile travel like the tiles: wavefront 0 DMAs the 64 lse values,
     // wavefront 1 the 64 D values (rows past Nq read as 0; their Q and dO rows are 0 too, so they
     // contribute nothing).  Two steps before use, wavefront 0 rewrites lse in place as
-    // -lse*log2(e), or -inf for a row that saw nothing (then P = exp2(-inf) = 0), and wavefront
-    // 1 rewrites D as -D: the S and dP accumulators START at these values, which removes the
-    // subtraction from the per-element vector work.  No compiler-visible global load is left
-    // in the loop: its wait would drain the DMA queue.
+    // -lse/scale, or -inf for a row that saw nothing (then P = exp2(-inf) = 0), and wavefront
+    // 1 rewrites D as -D: the S and dP accumulators START at these values, so that
+    // P = exp2(c (Q K^T - lse/scale)) and dS = P o (dO V^T - D) need no subtraction in the
+    // per-element vector work.  (Multiplying K by c beforehand would also remove the multiply,
+    // but rounds c K to bf16 again; with few visible keys per row P is then visibly off.)  No
+    // compiler-visible global load is left in the loop: its wait would drain the DMA queue.
     const __amdgpu_buffer_rsrc_t lrs = make_rsrc(lseh, (unsigned)a.Nq * 4u);
     const __amdgpu_buffer_rsrc_t drs = make_rsrc(Dh, (unsigned)a.Nq * 4u);
     auto dma_rowstat = [&](int t, int slot) __attribute__((always_inline)) {
@@ -138,11 +135,12 @@ burst_bwd_dkv_kernel(BwdArgs a) {
                          : (wu == 1) ? lds0 + DKV_LDS_D + slot * DKV_BR * 4 : lds0 + DKV_LDS_DUMMY;
       dma_b32_to_lds(wu == 1 ? drs : lrs, dst, (t * DKV_BR + lane) * 4);
     };
+    const float inv_scale = 1.0f / a.scale;
     auto scale_rowstat = [&](int slot) __attribute__((always_inline)) {
       if (tid < 64) {
         float* ptr = reinterpret_cast<float*>(smem + DKV_LDS_L) + slot * DKV_BR + tid;
         float lv = *ptr;
-        *ptr = (lv == BURST_NEG_INF) ? BURST_NEG_INF : -lv * kLog2e;
+        *ptr = (lv == BURST_NEG_INF) ? BURST_NEG_INF : -lv * inv_scale;
       } else if (tid < 128) {
         float* ptr = reinterpret_cast<float*>(smem + DKV_LDS_D) + slot * DKV_BR + (tid - 64);
         *ptr = -*ptr;
@@ -174,7 +172,7 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     constexpr int LEAD = 4, RING = LEAD + 2;       // A-operand reads run LEAD slices ahead
     constexpr int TLEAD = 3, TRING = TLEAD + 1;    // transposed fragments run TLEAD slices ahead
 
-    // S and dP accumulators of the two row blocks.  They start at -lse*log2(e) and -D of their
+    // S and dP accumulators of the two row blocks.  They start at -lse/scale and -D of their
     // rows (register r of a block = row 8*(r/4) + 4h + r%4: four 128-bit broadcast reads per
     // block and statistic, straight into the accumulator registers).  Block 0 of the next tile is
     // loaded while the current tile's last phases run.
@@ -231,8 +229,8 @@ burst_bwd_dkv_kernel(BwdArgs a) {
         float ph0, ph1;
         auto pds_half0 = [&](int rb, int pidx) __attribute__((always_inline)) {  // pidx 0..7
           const int r = 2 * pidx;
-          ph0 = fast_exp2(s[rb][r]);
-          ph1 = fast_exp2(s[rb][r + 1]);
+          ph0 = fast_exp2(s[rb][r] * a.c);
+          ph1 = fast_exp2(s[rb][r + 1] * a.c);
           asm volatile("" : "+v"(ph0), "+v"(ph1));   // keep the arithmetic in this slice
         };
         auto pds_half1 = [&](int rb, int pidx) __attribute__((always_inline)) {
