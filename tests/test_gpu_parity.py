@@ -43,6 +43,7 @@ BF16_CASES = [
     dict(B=1, H=1, d=128, Nq=300, chunk_rows=[128, 128, 128, 128], causal=True, q_off=2000, window=64,
          k_offs=[0, 1800, 1928, 2200]),                                    # first chunk out of every window
     dict(B=2, H=1, d=128, Nq=130, chunk_rows=[257], causal=True, q_off=60, window=1),   # each row sees one key
+    dict(B=1, H=3, d=128, Nq=596, chunk_rows=[356], causal=True, q_off=107, window=1),  # P must be exactly 1: dV = dO
 ]
 
 
