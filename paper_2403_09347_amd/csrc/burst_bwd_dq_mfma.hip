@@ -42,9 +42,10 @@ constexpr int DQ_LDS_BYTES = (DQ_KSLOTS + DQ_VSLOTS) * DQ_TILE_BYTES;
 // The resident operand is declared read-write although the instruction only reads it: its value
 // then lives in AGPRs from one statement to the next, like the pinned accumulators; as a plain
 // input the compiler keeps its home in VGPRs and copies it over before every use.
-__device__ __forceinline__ void mfma32_dp_first(f32x16& acc, bf16x8 a, bf16x8& b_resident) {
-  asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %1, 0"
-               : "=&v"(acc), "+a"(b_resident) : "v"(a));   // early clobber: the result must not share registers with an operand
+// First k-step: the accumulator starts at `start` (16 registers holding -D of the lane's row).
+__device__ __forceinline__ void mfma32_dp_first(f32x16& acc, bf16x8 a, bf16x8& b_resident, const f32x16& start) {
+  asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %1, %3"
+               : "=&v"(acc), "+a"(b_resident) : "v"(a), "v"(start));   // early clobber: the result must not share registers with an operand
 }
 __device__ __forceinline__ void mfma32_dp(f32x16& acc, bf16x8 a, bf16x8& b_resident) {
   asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %1, %0" : "+v"(acc), "+a"(b_resident) : "v"(a));
@@ -112,14 +113,20 @@ burst_bwd_dq_kernel(BwdArgs a) {
   if (ntiles > 0) {
     bf16x8 qf[2][8];       // Q fragments of the wavefront's rows (B operand of S^T), VGPRs
     bf16x8 gfr[2][8];      // dO fragments of the same rows (B operand of dP^T), AGPRs
-    float nlse2[2], Dv[2];
+    float nlse2[2];
+    f32x16 negD[2];        // -D of the lane's row in all 16 registers: start value of the dP^T accumulators,
+                           // so that dS^T = P^T o (dP^T - D) needs no subtraction per score
 #pragma unroll
     for (int rb = 0; rb < 2; rb++) {
       int row = q0 + rb * 32 + lr;
       bool ok = row < a.Nq;
       float lv = ok ? lseh[row] : BURST_NEG_INF;
       nlse2[rb] = (lv == BURST_NEG_INF) ? BURST_NEG_INF : -lv * kLog2e;   // -inf => P = exp2(-inf) = 0
-      Dv[rb] = ok ? Dh[row] : 0.f;
+      {
+        const float nd = ok ? -Dh[row] : 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; r++) negD[rb][r] = nd;
+      }
 #pragma unroll
       for (int ks = 0; ks < 8; ks++) {
         bf16x8 z;
@@ -264,7 +271,7 @@ burst_bwd_dq_kernel(BwdArgs a) {
       for (int i = 0; i < 16; i++) {
         const int ks = i >> 1, rb = i & 1;
         if (rb == 0 && ks + 2 < 8) vfq[(ks + 2) % 3] = lds_read_b128(vl, abase ^ ((ks + 2) << 5));
-        if (ks == 0) mfma32_dp_first(dp[rb], vfq[0], gfr[rb][0]);
+        if (ks == 0) mfma32_dp_first(dp[rb], vfq[0], gfr[rb][0], negD[rb]);
         else mfma32_dp(dp[rb], vfq[ks % 3], gfr[rb][ks]);
         {
           // (the empty asm statements tie this slice's arithmetic between this slice's MFMA and
@@ -289,8 +296,8 @@ burst_bwd_dq_kernel(BwdArgs a) {
         // vector work, and an in-order wavefront then stalls behind the second MFMA)
         float x0 = dp[prb][r], x1 = dp[prb][r + 1];
         asm volatile("" : "+v"(x0), "+v"(x1));
-        float d0 = s[prb][r] * (x0 - Dv[prb]);
-        float d1 = s[prb][r + 1] * (x1 - Dv[prb]);
+        float d0 = s[prb][r] * x0;
+        float d1 = s[prb][r + 1] * x1;
         bf16x2 pk;
         pk[0] = (bf16)d0; pk[1] = (bf16)d1;
         unsigned pu = __builtin_bit_cast(unsigned, pk);
