@@ -289,6 +289,14 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           if (i == 0 && need_mask) mask_block(1);
           if (i + TLEAD < 32) issue_tread(i + TLEAD);
           if (i == 4) load_init(0, lp_next, dp_next);     // block 0 of tile t + 1
+          // phase 4 has no vector work: the DMA of tile t + 2 (into the slot of tile t - 1, free
+          // since the last barrier) and of the statistics of tile t + 3 is issued here
+          if (i == 16) dma_rowstat(t + 3, (n + 3) & 3);
+          if (i > 16 && (i & 1)) {
+            const int j = (i - 17) >> 1;                  // 0..7: Q rows, then dO rows
+            if (j < 4) dma_tile(qrs, lds0 + DKV_LDS_Q + slot2 * DKV_TILE_BYTES, j, t + 2);
+            else dma_tile(grs, lds0 + DKV_LDS_G + slot2 * DKV_TILE_BYTES, j - 4, t + 2);
+          }
           const bf16x8 bt = cat4(tq[i % TRING][0], tq[i % TRING][1]);
           if (isk) mfma32_acc(dk[db], dsf[rb][u], bt);
           else mfma32_acc(dv[db], pf[rb][u], bt);
@@ -296,18 +304,12 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-      // ---- scale the statistics of tile t + 1 (landed during the previous step), DMA tile
-      // t + 2 and its statistics.  The newest loads may stay in flight across the barrier.
-      __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): the previous step's DMA (old by now)
+      // ---- everything but the 9 loads of this step has landed (tile t + 1, statistics of tile
+      // t + 2): scale those statistics.  The newest loads stay in flight across the barrier.
+      __builtin_amdgcn_s_waitcnt(0x0F79);          // vmcnt(9)
       scale_rowstat((n + 2) & 3);
-#pragma unroll
-      for (int il = 0; il < 4; il++) {
-        dma_tile(qrs, lds0 + DKV_LDS_Q + slot2 * DKV_TILE_BYTES, il, t + 2);
-        dma_tile(grs, lds0 + DKV_LDS_G + slot2 * DKV_TILE_BYTES, il, t + 2);
-      }
-      dma_rowstat(t + 3, (n + 3) & 3);
       slot = slot1;
-      __builtin_amdgcn_s_waitcnt(0x0079);          // vmcnt(9): everything but the 9 loads just issued; lgkmcnt(0)
+      __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
       __builtin_amdgcn_s_barrier();
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): no DMA may outlive the loop
