@@ -136,6 +136,20 @@ burst_bwd_dkv_kernel(BwdArgs a) {
       dma_b32_to_lds(wu == 1 ? drs : lrs, dst, (t * DKV_BR + lane) * 4);
     };
     const float inv_scale = 1.0f / a.scale;
+    // The same in two parts for the main loop, so that the LDS round trip hides behind MFMAs:
+    // wavefronts 0 / 1 fetch their 64 values at one point of the step and write them back later.
+    float stat_tmp = 0.f;
+    auto rowstat_fetch = [&](int slot) __attribute__((always_inline)) {
+      if (tid < 64) stat_tmp = *(reinterpret_cast<const float*>(smem + DKV_LDS_L) + slot * DKV_BR + tid);
+      else if (tid < 128) stat_tmp = *(reinterpret_cast<const float*>(smem + DKV_LDS_D) + slot * DKV_BR + (tid - 64));
+    };
+    auto rowstat_store = [&](int slot) __attribute__((always_inline)) {
+      if (tid < 64)
+        *(reinterpret_cast<float*>(smem + DKV_LDS_L) + slot * DKV_BR + tid) =
+            (stat_tmp == BURST_NEG_INF) ? BURST_NEG_INF : -stat_tmp * inv_scale;
+      else if (tid < 128)
+        *(reinterpret_cast<float*>(smem + DKV_LDS_D) + slot * DKV_BR + (tid - 64)) = -stat_tmp;
+    };
     auto scale_rowstat = [&](int slot) __attribute__((always_inline)) {
       if (tid < 64) {
         float* ptr = reinterpret_cast<float*>(smem + DKV_LDS_L) + slot * DKV_BR + tid;
@@ -289,6 +303,11 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           if (i == 0 && need_mask) mask_block(1);
           if (i + TLEAD < 32) issue_tread(i + TLEAD);
           if (i == 4) load_init(0, lp_next, dp_next);     // block 0 of tile t + 1
+          // the loads of the previous step (tile t + 1, statistics of tile t + 2) are most of a
+          // step old: wait for them here, before this step's loads are issued, and rewrite those
+          // statistics (fetch now, store a few slices later)
+          if (i == 12) { __builtin_amdgcn_s_waitcnt(0x0F70); rowstat_fetch((n + 2) & 3); }
+          if (i == 22) rowstat_store((n + 2) & 3);
           // phase 4 has no vector work: the DMA of tile t + 2 (into the slot of tile t - 1, free
           // since the last barrier) and of the statistics of tile t + 3 is issued here
           if (i == 16) dma_rowstat(t + 3, (n + 3) & 3);
@@ -304,10 +323,8 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-      // ---- everything but the 9 loads of this step has landed (tile t + 1, statistics of tile
-      // t + 2): scale those statistics.  The newest loads stay in flight across the barrier.
-      __builtin_amdgcn_s_waitcnt(0x0F79);          // vmcnt(9)
-      scale_rowstat((n + 2) & 3);
+      // ---- the 9 loads of this step stay in flight across the barrier; the LDS stores of the
+      // rewritten statistics must be done
       slot = slot1;
       __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
       __builtin_amdgcn_s_barrier();
