@@ -130,6 +130,25 @@ int burst_local_bwd_dkv(const void* Q, const void* K_chunk, const void* V_chunk,
                         float* dK_chunk, float* dV_chunk, int accumulate_dkv,
                         const burst_params* p, void* stream);
 
+/* Alg. 1, body of the loop for one chunk exactly as printed, WITHOUT the tiling of
+ * Sec. 2.4 (the "w/o LAO" variant of the paper's ablation, Tables 2-3): the whole
+ * S_ij = scale Q K_chunk^T and P_ij = exp(S_ij - m_ij) of the block pair are stored in
+ * `workspace` between the steps, then O_ij = P_ij V_chunk is merged into the state.
+ * Same arguments, masking and resulting state as burst_local_fwd (up to rounding).
+ * workspace: device memory, 256-byte aligned, at least
+ * burst_materialized_workspace_bytes(p) bytes (B H Nq Nc (4 + element size) plus the
+ * chunk's row statistics); owned by the caller, contents undefined afterwards except
+ * that it starts with S_ij as fp32 [B,H,Nq,ceil8(Nc)] (raw scaled scores, unmasked),
+ * followed at the next 256-byte boundary by P_ij in `dtype` with the same pitch
+ * (masked entries and the padding columns are 0).  Returns BURST_ERR_SHAPE if
+ * workspace_bytes is too small.  burst_materialized_workspace_bytes returns 0 for
+ * invalid parameters. */
+size_t burst_materialized_workspace_bytes(const burst_params* p);
+int burst_local_fwd_materialized(const void* Q, const void* K_chunk, const void* V_chunk,
+                                 float* O_acc, float* m, float* l,
+                                 void* workspace, size_t workspace_bytes,
+                                 const burst_params* p, void* stream);
+
 /* Timing helper for harnesses that cannot create HIP events themselves:
  * records/queries events on the same stream the kernels are launched on.
  * burst_event_create returns an opaque handle (NULL on failure). */

@@ -123,7 +123,17 @@ def gao_local_forward(Q, K_j, V_j, scale, vis=None):
     S_ij = scale Q K_j^T; m_ij = rowmax; P_ij = exp(S_ij - m_ij);
     l_ij = rowsum(P_ij); O_ij = P_ij V_j  (unnormalised partial result).
     """
-    Q, K_j, V_j = _f64(Q), _f64(K_j), _f64(V_j)
+    S_ij, m_ij, P_ij = gao_local_scores(Q, K_j, scale, vis)
+    l_ij = P_ij.sum(axis=1)
+    O_ij = P_ij @ _f64(V_j)
+    return O_ij, m_ij, l_ij
+
+
+def gao_local_scores(Q, K_j, scale, vis=None):
+    """Alg. 1, the first three steps of the local attention of one chunk, with their
+    intermediate matrices returned: S_ij = scale Q K_j^T (hidden entries -inf),
+    m_ij = rowmax(S_ij), P_ij = exp(S_ij - m_ij)."""
+    Q, K_j = _f64(Q), _f64(K_j)
     S_ij = scale * (Q @ K_j.T)
     if vis is not None:
         S_ij = np.where(vis, S_ij, -np.inf)
@@ -133,9 +143,7 @@ def gao_local_forward(Q, K_j, V_j, scale, vis=None):
         m_ij = S_ij.max(axis=1)
     shift = np.where(np.isfinite(m_ij), m_ij, 0.0)   # rows with no visible key
     P_ij = np.exp(S_ij - shift[:, None])
-    l_ij = P_ij.sum(axis=1)
-    O_ij = P_ij @ V_j
-    return O_ij, m_ij, l_ij
+    return S_ij, m_ij, P_ij
 
 
 def gao_merge(O_i, m_i, l_i, O_ij, m_ij, l_ij):

@@ -18,6 +18,7 @@ EXPORTS = [
     "burst_state_init", "burst_local_fwd", "burst_finalize", "burst_merge_state",
     "burst_bwd_prepare", "burst_local_bwd", "burst_local_bwd_dq", "burst_local_bwd_dkv", "burst_event_create", "burst_event_record",
     "burst_event_elapsed_ms", "burst_event_destroy", "burst_strerror", "burst_version",
+    "burst_materialized_workspace_bytes", "burst_local_fwd_materialized",
 ]
 
 
@@ -52,6 +53,10 @@ def load():
     lib.burst_state_init.argtypes = [fp, fp, fp, pp, vp]
     lib.burst_local_fwd.argtypes = [vp, vp, vp, fp, fp, fp, pp, vp]
     lib.burst_finalize.argtypes = [fp, fp, fp, vp, fp, pp, vp]
+    lib.burst_materialized_workspace_bytes.argtypes = [pp]
+    lib.burst_materialized_workspace_bytes.restype = ctypes.c_size_t
+    lib.burst_local_fwd_materialized.argtypes = [vp, vp, vp, fp, fp, fp, vp, ctypes.c_size_t, pp, vp]
+    lib.burst_local_fwd_materialized.restype = ctypes.c_int
     lib.burst_merge_state.argtypes = [fp, fp, fp, fp, fp, fp, pp, vp]
     lib.burst_bwd_prepare.argtypes = [vp, vp, fp, pp, vp]
     lib.burst_local_bwd.argtypes = [vp, vp, vp, vp, vp, fp, fp, fp, fp, fp, ctypes.c_int, ctypes.c_int, pp, vp]
@@ -118,6 +123,17 @@ def burst_state_init(O_acc, m, l, p):
 def burst_local_fwd(Q, K_chunk, V_chunk, O_acc, m, l, p):
     _check(load().burst_local_fwd(_ptr(Q), _ptr(K_chunk), _ptr(V_chunk), _f32(O_acc), _f32(m), _f32(l),
                                   ctypes.byref(p), _stream()), "burst_local_fwd")
+
+
+def burst_materialized_workspace_bytes(p):
+    return int(load().burst_materialized_workspace_bytes(ctypes.byref(p)))
+
+
+def burst_local_fwd_materialized(Q, K_chunk, V_chunk, O_acc, m, l, workspace, p):
+    """workspace: a contiguous uint8 device tensor (see burst_materialized_workspace_bytes)."""
+    _check(load().burst_local_fwd_materialized(_ptr(Q), _ptr(K_chunk), _ptr(V_chunk), _f32(O_acc), _f32(m), _f32(l),
+                                               _ptr(workspace), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
+                                               ctypes.byref(p), _stream()), "burst_local_fwd_materialized")
 
 
 def burst_finalize(O_acc, m, l, O_out, lse, p):

@@ -21,6 +21,9 @@ int launch_bwd_dq_generic(const KParams&, int, const void*, const void*, const v
                           const float*, float*, int, hipStream_t);
 int launch_bwd_dkv_generic(const KParams&, int, const void*, const void*, const void*, const void*, const float*,
                            const float*, float*, float*, int, hipStream_t);
+size_t materialized_workspace_bytes(const KParams&, int);
+int launch_fwd_materialized(const KParams&, int, bool, const void*, const void*, const void*, float*, float*, float*,
+                            void*, hipStream_t);
 }  // namespace burst
 
 namespace {
@@ -119,6 +122,30 @@ int burst_local_fwd(const void* Q, const void* K_chunk, const void* V_chunk,
   if ((st = check_arch()) != BURST_OK) return st;
   if (use_mfma(p)) return burst::launch_fwd_mfma(k, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
   return burst::launch_fwd_generic(k, p->dtype, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
+}
+
+size_t burst_materialized_workspace_bytes(const burst_params* p) {
+  KParams k;
+  if (check_params(p, &k) != BURST_OK) return 0;
+  return burst::materialized_workspace_bytes(k, p->dtype);
+}
+
+int burst_local_fwd_materialized(const void* Q, const void* K_chunk, const void* V_chunk,
+                                 float* O_acc, float* m, float* l,
+                                 void* workspace, size_t workspace_bytes,
+                                 const burst_params* p, void* stream) {
+  KParams k;
+  int st = check_params(p, &k);
+  if (st != BURST_OK) return st;
+  if ((long long)k.B * k.H * k.Nq == 0 || k.Nc == 0) return BURST_OK;   // an empty chunk is the identity
+  REQUIRE_PTR(Q); REQUIRE_PTR(K_chunk); REQUIRE_PTR(V_chunk);
+  REQUIRE_PTR(O_acc); REQUIRE_PTR(m); REQUIRE_PTR(l);
+  if (workspace == nullptr) return BURST_ERR_NULL;
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return BURST_ERR_ALIGN;
+  if (workspace_bytes < burst::materialized_workspace_bytes(k, p->dtype)) return BURST_ERR_SHAPE;
+  if ((st = check_arch()) != BURST_OK) return st;
+  return burst::launch_fwd_materialized(k, p->dtype, use_mfma(p), Q, K_chunk, V_chunk, O_acc, m, l, workspace,
+                                        (hipStream_t)stream);
 }
 
 int burst_finalize(const float* O_acc, const float* m, const float* l,
@@ -268,6 +295,6 @@ const char* burst_strerror(int status) {
   }
 }
 
-int burst_version(void) { return 101; }
+int burst_version(void) { return 102; }
 
 }  // extern "C"

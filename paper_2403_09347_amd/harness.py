@@ -66,6 +66,38 @@ class RingWalk:
         return dQ, dKs, dVs
 
 
+class MaterializedWalk(RingWalk):
+    """The forward walk with the chunk step that stores S_ij and P_ij in HBM (the paper's
+    "w/o LAO" ablation): same state, same finalize, one workspace sized for the largest chunk."""
+
+    def __init__(self, Q, scale, causal=False, q_off=0, window=0, max_chunk_rows=0):
+        super().__init__(Q, scale, causal, q_off, window)
+        self.workspace = None
+        if max_chunk_rows:
+            self._reserve(max_chunk_rows)
+
+    def _reserve(self, rows):
+        need = B.burst_materialized_workspace_bytes(self.params(rows, 0))
+        if self.workspace is None or self.workspace.numel() < need:
+            self.workspace = torch.empty(max(need, 256), device=self.Q.device, dtype=torch.uint8)
+        return need
+
+    def step(self, K_c, V_c, k_off):
+        self._reserve(K_c.shape[2])
+        B.burst_local_fwd_materialized(self.Q, K_c, V_c, self.O_acc, self.m, self.l, self.workspace,
+                                       self.params(K_c.shape[2], k_off))
+
+    def stored_scores(self, Nc):
+        """Views of S_ij (fp32) and P_ij (input type) of the last step: [B, H, Nq, Nc]."""
+        ncp = (Nc + 7) // 8 * 8
+        rows = self.Bt * self.H * self.Nq
+        s_bytes = (rows * ncp * 4 + 255) // 256 * 256
+        S = self.workspace[: rows * ncp * 4].view(torch.float32).view(self.Bt, self.H, self.Nq, ncp)
+        P = self.workspace[s_bytes: s_bytes + rows * ncp * self.Q.element_size()].view(self.Q.dtype) \
+            .view(self.Bt, self.H, self.Nq, ncp)
+        return S[..., :Nc], P[..., :Nc]
+
+
 class DoubleBufferedWalk(RingWalk):
     """Paper Sec. 2.5 / Alg. 3 on one GPU: chunk j+1 is copied from its source (another HBM
     allocation, or pinned host memory as a slow link) into the alternate receive buffer on a

@@ -65,3 +65,18 @@ def test_argument_validation_without_gpu():
     assert lib.burst_state_init(mis, mis, mis, ctypes.byref(ok), null) == -2         # misaligned
     empty = binding.params(1, 1, 0, 16, 128, "bf16", 0.5)      # nothing to do: ok without pointers
     assert lib.burst_state_init(null, null, null, ctypes.byref(empty), null) == 0
+
+
+def test_materialized_workspace_size_without_gpu():
+    """S (fp32) + P (input type) with the key count rounded up to 8, each region rounded up to
+    256 bytes, plus two per-row vectors; 0 for an invalid parameter block."""
+    from paper_2403_09347_amd import binding
+    p = binding.params(1, 2, 5, 9, 8, "bf16", 0.5)             # 10 rows x 16 padded keys
+    assert binding.burst_materialized_workspace_bytes(p) == 768 + 512 + 2 * 256
+    p = binding.params(2, 2, 5, 16, 8, "f32", 0.5)             # 20 rows x 16 keys
+    assert binding.burst_materialized_workspace_bytes(p) == 1280 + 1280 + 2 * 256
+    bad = binding.params(1, 1, 16, 16, 300, "bf16", 0.5)
+    assert binding.burst_materialized_workspace_bytes(bad) == 0
+    lib = binding.load()
+    null = ctypes.c_void_p(0)
+    assert lib.burst_local_fwd_materialized(null, null, null, null, null, null, null, 0, ctypes.byref(bad), null) == -3

@@ -1,0 +1,89 @@
+"""GPU parity of the chunk step that stores S_ij and P_ij in HBM (the paper's "w/o LAO" ablation)
+against the fp64 oracle: the resulting state, and the two stored matrices themselves."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import burst_oracle as orc
+from paper_2403_09347_amd import binding as B
+from paper_2403_09347_amd import workloads
+from paper_2403_09347_amd.harness import MaterializedWalk, RingWalk
+from gpu_util import check, compare_all_heads, f64
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+CASES = [
+    ("bf16", dict(B=1, H=2, d=128, Nq=64, chunk_rows=[64])),
+    ("bf16", dict(B=2, H=3, d=128, Nq=300, chunk_rows=[200, 65, 331])),                 # ragged on both sides
+    ("bf16", dict(B=1, H=2, d=128, Nq=300, chunk_rows=[256, 192], causal=True, q_off=148)),
+    ("bf16", dict(B=1, H=1, d=128, Nq=100, chunk_rows=[64, 64], causal=True, q_off=-30)),   # rows that see nothing
+    ("bf16", dict(B=1, H=2, d=128, Nq=260, chunk_rows=[129, 7, 200], causal=True, q_off=200, window=40)),
+    ("bf16", dict(B=1, H=2, d=64, Nq=70, chunk_rows=[33, 50], causal=True, q_off=20)),  # generic kernels
+    ("f32", dict(B=1, H=2, d=16, Nq=45, chunk_rows=[31, 18])),
+    ("f32", dict(B=1, H=1, d=128, Nq=40, chunk_rows=[70], causal=True, q_off=35, window=9)),
+]
+
+
+@pytest.mark.parametrize("dtype,spec", CASES, ids=lambda v: v if isinstance(v, str) else "-".join(f"{k}{x}" for k, x in v.items()))
+def test_materialized_walk_against_the_oracle(dtype, spec):
+    case = workloads.make_case(dtype=dtype, seed=61, device=DEV, **spec)
+    walk = MaterializedWalk(case["Q"], case["scale"], case["causal"], case["q_off"], case.get("window", 0))
+    O, lse = walk.forward(case["K"], case["V"], case["k_offs"])
+    torch.cuda.synchronize()
+    compare_all_heads(case, dtype, O, lse)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 32)])
+def test_workspace_holds_the_scores_and_probabilities_of_the_block_pair(dtype, d):
+    """After one step the workspace starts with S_ij = scale Q K^T (unmasked) and, behind it,
+    P_ij = exp(S_ij - m_ij) with hidden entries 0 (Alg. 1, chunk step)."""
+    Nq, Nc = 150, 203
+    case = workloads.make_case(B=1, H=2, d=d, Nq=Nq, chunk_rows=[Nc], dtype=dtype, seed=67, device=DEV,
+                               causal=True, q_off=90, window=120)
+    walk = MaterializedWalk(case["Q"], case["scale"], True, 90, 120)
+    walk.forward(case["K"], case["V"], case["k_offs"])
+    torch.cuda.synchronize()
+    S, P = walk.stored_scores(Nc)
+    qp, kp = 90 + np.arange(Nq), case["k_offs"][0] + np.arange(Nc)
+    vis = orc.visibility(qp, kp, True, 120)
+    for h in range(2):
+        Qh, Kh = f64(case["Q"][0, h]), f64(case["K"][0][0, h])
+        S_raw, _, _ = orc.gao_local_scores(Qh, Kh, case["scale"], None)
+        _, m_ij, P_ref = orc.gao_local_scores(Qh, Kh, case["scale"], vis)
+        assert np.max(np.abs(f64(S[0, h]) - S_raw)) <= (1e-4 if dtype == "f32" else 1e-3)
+        got = f64(P[0, h])
+        assert np.array_equal(got[~vis], np.zeros_like(got[~vis]))
+        assert np.max(np.abs(got - P_ref)) <= (1e-4 if dtype == "f32" else 2 ** -8)
+        rows_with_keys = np.isfinite(m_ij)
+        assert np.all(got[rows_with_keys].max(axis=1) == 1.0)      # the row maximum itself gives P = 1
+
+
+def test_materialized_and_tiled_steps_interleave_on_one_state():
+    """Both chunk steps keep the same kind of state: a walk may mix them."""
+    case = workloads.make_case(B=1, H=2, d=128, Nq=200, chunk_rows=[100, 150, 90], dtype="bf16", seed=71, device=DEV)
+    walk = MaterializedWalk(case["Q"], case["scale"])
+    walk.init()
+    walk.step(case["K"][0], case["V"][0], case["k_offs"][0])
+    RingWalk.step(walk, case["K"][1], case["V"][1], case["k_offs"][1])
+    walk.step(case["K"][2], case["V"][2], case["k_offs"][2])
+    O, lse = walk.finalize()
+    torch.cuda.synchronize()
+    compare_all_heads(case, "bf16", O, lse)
+
+
+def test_workspace_size_is_checked():
+    case = workloads.make_case(B=1, H=1, d=128, Nq=64, chunk_rows=[64], dtype="bf16", seed=73, device=DEV)
+    walk = MaterializedWalk(case["Q"], case["scale"])
+    walk.init()
+    p = walk.params(64, 0)
+    need = B.burst_materialized_workspace_bytes(p)
+    assert need == 64 * 64 * 4 + 64 * 64 * 2 + 2 * 256
+    small = torch.empty(need - 256, device=DEV, dtype=torch.uint8)
+    with pytest.raises(B.BurstError) as e:
+        B.burst_local_fwd_materialized(case["Q"], case["K"][0], case["V"][0], walk.O_acc, walk.m, walk.l, small, p)
+    assert e.value.code == -3
+    big = torch.empty(need + 256, device=DEV, dtype=torch.uint8)
+    with pytest.raises(B.BurstError) as e:
+        B.burst_local_fwd_materialized(case["Q"], case["K"][0], case["V"][0], walk.O_acc, walk.m, walk.l, big[16:], p)
+    assert e.value.code == -2
