@@ -87,6 +87,36 @@ def overlap_measurement(w, inp, source, reps):
             "copy_GBps": w.G * chunk_bytes / (t_copy * 1e-3) / 1e9, "chunk_MiB": chunk_bytes / 2**20}
 
 
+def ablation_measurement(w, inp, reps):
+    """Forward walk of the workload with the tiled chunk step and with the step that stores
+    S_ij and P_ij in HBM (the paper's "w/o LAO" ablation, Tables 2-3).  Times in ms, median of
+    `reps`; memory is the workspace one chunk step needs on top of the inputs and the state."""
+    import statistics
+    import torch
+    from paper_2403_09347_amd.harness import MaterializedWalk, RingWalk
+    Q, Ks, Vs = inp["Q"], inp["K"], inp["V"]
+    k_offs = [w.k_off(j) for j in range(w.G)]
+    tiled = RingWalk(Q, w.scale, w.causal, w.q_off)
+    stored = MaterializedWalk(Q, w.scale, w.causal, w.q_off, max_chunk_rows=w.Nc)
+
+    def timed(fn):
+        ts = []
+        for _ in range(reps + 1):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            ts.append((time.perf_counter() - t0) * 1e3)
+        return statistics.median(ts[1:])
+    t_tiled = timed(lambda: tiled.forward(Ks, Vs, k_offs))
+    t_stored = timed(lambda: stored.forward(Ks, Vs, k_offs))
+    return {"tiled_forward_ms": t_tiled, "stored_forward_ms": t_stored, "slowdown": t_stored / t_tiled,
+            "stored_workspace_MiB": stored.workspace.numel() / 2**20,
+            "tiled_workspace_MiB": 0.0,
+            "inputs_and_state_MiB": (Q.numel() * Q.element_size() * (1 + 2 * len(Ks)) + tiled.O_acc.numel() * 4
+                                     + 2 * tiled.m.numel() * 4) / 2**20}
+
+
 def measured_traffic(kernel, workload):
     """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary (None if absent)."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
@@ -111,6 +141,9 @@ def main():
                     help="also time the double-buffered chunk walk (paper Sec. 2.5): chunks are copied from a source "
                          "pool of that kind into two receive buffers on a second stream while the previous chunk "
                          "computes; adds an 'overlap' object to the JSON line")
+    ap.add_argument("--ablation", action="store_true",
+                    help="also time the forward walk with the chunk step that stores S_ij and P_ij in HBM "
+                         "(the paper's 'w/o LAO' ablation); adds an 'ablation' object to the JSON line")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch a plain elementwise copy kernel of known size (256 MiB read, 256 MiB "
                          "written) so that HBM counters of a profiler run can be scaled")
@@ -221,6 +254,8 @@ def main():
     }
     if args.overlap:
         out["overlap"] = overlap_measurement(w, inp, args.overlap, max(3, args.steps // 2))
+    if args.ablation:
+        out["ablation"] = ablation_measurement(w, inp, max(3, args.steps // 2))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(out))

@@ -132,3 +132,18 @@ def test_llama7b_32k_last_rank_causal_sliding_window():
     check_identities(w, inp, 6, dQ, dKs, dVs)
     for j in range(5):                                     # chunks 0..4 are out of every window
         assert float(dKs[j].abs().max()) == 0.0 and float(dVs[j].abs().max()) == 0.0
+
+
+def test_llama7b_32k_G8_with_scores_stored_in_hbm():
+    """The chunk step without the Sec. 2.4 tiling (S_ij, P_ij in HBM: 3 GiB of workspace for this
+    shape) at the benchmark's full size: sampled rows of several heads against the oracle."""
+    from paper_2403_09347_amd.harness import MaterializedWalk
+    w = workloads.by_name("llama7b_32k_G8")
+    inp = workloads.make_inputs(w, DEV)
+    k_offs = [w.k_off(j) for j in range(w.G)]
+    walk = MaterializedWalk(inp["Q"], w.scale, w.causal, w.q_off, w.window, max_chunk_rows=w.Nc)
+    assert walk.workspace.numel() >= w.B * w.H * w.Nq * w.Nc * 6
+    O, lse = walk.forward(inp["K"], inp["V"], k_offs)
+    torch.cuda.synchronize()
+    for h in (0, 13, w.H - 1):
+        check_sampled_rows(w, inp, h, O, lse, None)
