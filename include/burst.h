@@ -26,6 +26,10 @@
  *     k_off + c > q_off + r - w: a sliding window, the query itself and its w - 1
  *     predecessors when combined with causal; w = 0 means no window.  Key tiles and
  *     whole chunks outside the window are skipped, not computed and masked.
+ *     With block_mask != NULL (block-sparse patterns, Sec. 2.6) a key must in addition
+ *     lie in a block whose mask byte is nonzero; the three conditions are ANDed.  Key
+ *     tiles no row of a workgroup can see are skipped.  The mask is read while the
+ *     kernels run: keep it unchanged until they have finished.
  *     A row that sees no key keeps its state.
  *   - Return value: 0 on success, a negative burst_status otherwise.  On error
  *     nothing is enqueued and no output is written.
@@ -68,6 +72,13 @@ typedef struct burst_params {
   int64_t q_off;    /* global position of query row 0 */
   int64_t k_off;    /* global position of row 0 of this chunk */
   int64_t window;   /* 0 = none; w > 0: keys at positions <= query position - w are hidden */
+  const uint8_t* block_mask; /* NULL = none; else DEVICE pointer to a row-major byte matrix
+                              * [ceil(Nq / block)][ceil(Nc / block)] for THIS query slice x chunk
+                              * pair, shared by every batch entry and head: entry (i, j) = 0 hides
+                              * keys j*block .. of the chunk from query rows i*block .. of the slice */
+  int32_t block;    /* edge of a mask block in rows = keys; a positive multiple of 64 when
+                     * block_mask != NULL, ignored otherwise */
+  int32_t reserved; /* must be 0 */
 } burst_params;
 
 /* Alg. 1, initialisation: O_acc = 0, l = 0, m = -inf.

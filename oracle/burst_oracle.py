@@ -29,7 +29,10 @@ Readings of the paper taken here (the paper is silent or inconsistent):
   need.  The one pattern taken here is a sliding window: with `window` = w > 0
   a key is visible only if kp > qp - w (the query itself and its w - 1
   predecessors when combined with `causal`); w = 0 means no window.  Skipped
-  pairs behave exactly like masked ones (score -inf).
+  pairs behave exactly like masked ones (score -inf).  Any other pattern is
+  given as a boolean matrix `pattern` [Nq, Nk] that is ANDed with the above;
+  `block_visibility` expands a matrix of block flags (one flag per
+  block x block square of the query-slice x chunk pair) into such a matrix.
 * Alg. 1 initialises m = -inf.  When m_new = -inf (a row sees no key of the
   chunk and has seen none before) both rescale factors are taken as 0, so a
   fully masked chunk leaves the state unchanged.  Finalising a row with l = 0
@@ -61,11 +64,18 @@ def visibility(q_pos, k_pos, causal, window=0):
     return vis
 
 
+def block_visibility(nq, nk, flags, block):
+    """Boolean [nq, nk]: entry (r, c) is flags[r // block, c // block] != 0."""
+    flags = np.asarray(flags)
+    assert flags.shape == (-(-nq // block), -(-nk // block)), (flags.shape, nq, nk, block)
+    return flags[np.arange(nq) // block][:, np.arange(nk) // block] != 0
+
+
 # --------------------------------------------------------------------------
 # The definition: Eq. 1 and its gradient
 # --------------------------------------------------------------------------
 def full_forward(Q, K, V, scale, causal=False, q_pos=None, k_pos=None,
-                 return_p=False, window=0):
+                 return_p=False, window=0, pattern=None):
     """Eq. 1 on one head.  Returns O [Nq,d], lse [Nq] (and P if asked)."""
     Q, K, V = _f64(Q), _f64(K), _f64(V)
     nq, nk = Q.shape[0], K.shape[0]
@@ -73,6 +83,8 @@ def full_forward(Q, K, V, scale, causal=False, q_pos=None, k_pos=None,
     k_pos = np.arange(nk) if k_pos is None else k_pos
     S = scale * (Q @ K.T)
     vis = visibility(q_pos, k_pos, causal, window)
+    if pattern is not None:
+        vis &= np.asarray(pattern, dtype=bool)
     S = np.where(vis, S, -np.inf)
     if nk == 0:
         row_max = np.full(nq, -np.inf)
@@ -91,14 +103,14 @@ def full_forward(Q, K, V, scale, causal=False, q_pos=None, k_pos=None,
 
 
 def full_backward(Q, K, V, dO, scale, causal=False, q_pos=None, k_pos=None,
-                  return_ds=False, window=0):
+                  return_ds=False, window=0, pattern=None):
     """Gradient of L = sum(O o dO) w.r.t. Q, K, V from the softmax Jacobian.
 
     dV = P^T dO;  dP = dO V^T;  dS = P o (dP - rowsum(P o dP));
     dQ = scale dS K;  dK = scale dS^T Q.
     """
     Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
-    _, _, P = full_forward(Q, K, V, scale, causal, q_pos, k_pos, return_p=True, window=window)
+    _, _, P = full_forward(Q, K, V, scale, causal, q_pos, k_pos, return_p=True, window=window, pattern=pattern)
     dV = P.T @ dO
     dP = dO @ V.T
     dS = P * (dP - (P * dP).sum(axis=1, keepdims=True))
@@ -172,8 +184,9 @@ def gao_finalize(O_i, m_i, l_i):
 
 
 def gao_forward(Q, K_chunks, V_chunks, scale, causal=False, q_pos=None,
-                k_pos_chunks=None, order=None, window=0):
-    """Alg. 1 on one head over a list of K/V chunks, visited in `order`."""
+                k_pos_chunks=None, order=None, window=0, pattern_chunks=None):
+    """Alg. 1 on one head over a list of K/V chunks, visited in `order`.
+    pattern_chunks: optional list of boolean [Nq, Nc_j] matrices (Sec. 2.6 patterns)."""
     Q = _f64(Q)
     nq, d = Q.shape
     q_pos = np.arange(nq) if q_pos is None else q_pos
@@ -186,6 +199,8 @@ def gao_forward(Q, K_chunks, V_chunks, scale, causal=False, q_pos=None,
     O_i, m_i, l_i = gao_state_init(nq, d)
     for j in order:
         vis = visibility(q_pos, k_pos_chunks[j], causal, window) if (causal or window) else None
+        if pattern_chunks is not None:
+            vis = np.asarray(pattern_chunks[j], dtype=bool) & (True if vis is None else vis)
         O_ij, m_ij, l_ij = gao_local_forward(Q, K_chunks[j], V_chunks[j], scale, vis)
         O_i, m_i, l_i = gao_merge(O_i, m_i, l_i, O_ij, m_ij, l_ij)
     return gao_finalize(O_i, m_i, l_i)
@@ -222,7 +237,7 @@ def gao_local_backward(Q, K_c, V_c, dO, lse, D, scale, vis=None):
 
 
 def gao_backward(Q, K_chunks, V_chunks, O, dO, lse, scale, causal=False,
-                 q_pos=None, k_pos_chunks=None, window=0):
+                 q_pos=None, k_pos_chunks=None, window=0, pattern_chunks=None):
     """Alg. 2 on one head with Q pinned and the K/V chunks walked in order.
 
     Returns dQ [Nq,d] and lists dK_chunks, dV_chunks.
@@ -240,6 +255,8 @@ def gao_backward(Q, K_chunks, V_chunks, O, dO, lse, scale, causal=False,
     dKs, dVs = [], []
     for j in range(len(K_chunks)):
         vis = visibility(q_pos, k_pos_chunks[j], causal, window) if (causal or window) else None
+        if pattern_chunks is not None:
+            vis = np.asarray(pattern_chunks[j], dtype=bool) & (True if vis is None else vis)
         dq, dk, dv = gao_local_backward(Q, K_chunks[j], V_chunks[j], dO, lse, D, scale, vis)
         dQ += dq
         dKs.append(dk)

@@ -62,6 +62,12 @@ int check_params(const burst_params* p, KParams* k) {
   k->causal = p->causal != 0; k->scale = p->scale; k->q_off = p->q_off; k->k_off = p->k_off;
   if (p->window < 0) return BURST_ERR_SHAPE;
   k->window = p->window;
+  if (p->reserved != 0) return BURST_ERR_SHAPE;
+  k->bmask = nullptr; k->bsize = 64; k->bpitch = 0;
+  if (p->block_mask != nullptr) {
+    if (p->block <= 0 || p->block % 64 != 0) return BURST_ERR_SHAPE;
+    k->bmask = p->block_mask; k->bsize = p->block; k->bpitch = (p->Nc + p->block - 1) / p->block;
+  }
   return BURST_OK;
 }
 
@@ -75,7 +81,8 @@ int check_params(const burst_params* p, KParams* k) {
 // tiles of prefetch past the end); longer slices or chunks take the generic kernels.
 constexpr int kMaxMfmaRows = 4 * 1024 * 1024;
 bool use_mfma(const burst_params* p) {
-  return p->dtype == BURST_BF16 && p->d == 128 && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows;
+  return p->dtype == BURST_BF16 && p->d == 128 && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows &&
+         p->block_mask == nullptr;
 }
 
 int get_d_scratch(size_t elems, float** out) {

@@ -26,6 +26,8 @@ struct KParams {
   float scale;
   long long q_off, k_off;
   long long window;      // 0 = none
+  const uint8_t* bmask;  // block mask [ceil(Nq/bsize)][bpitch] (nullptr = none), bpitch = ceil(Nc/bsize)
+  int bsize, bpitch;
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

@@ -21,6 +21,7 @@ struct MatArgs {
   int causal;
   float scale;
   long long q_off, k_off, window;
+  const uint8_t* bmask; int bsize, bpitch;   // block mask (nullptr = none)
 };
 
 // ---- step 1, bf16, d = 128: one wavefront = a 32 x 32 block of S (8 MFMAs over d)
@@ -88,8 +89,8 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// ---- step 2: one wavefront per query row.  The visible keys of a row form one interval of the
-// chunk (causal: up to the row's position; window: from position - window + 1).
+// ---- step 2: one wavefront per query row.  Causal and window leave one interval of the chunk
+// visible (up to the row's position; from position - window + 1); a block mask thins it further.
 template <typename T>
 __global__ void __launch_bounds__(256)
 mat_softmax_kernel(MatArgs a) {
@@ -105,13 +106,16 @@ mat_softmax_kernel(MatArgs a) {
   if (a.window > 0) lo = qpos - a.window + 1 - a.k_off > 0 ? qpos - a.window + 1 - a.k_off : 0;
   if (hi < 0) hi = 0;
   if (lo > hi) lo = hi;
+  const uint8_t* brow = a.bmask == nullptr ? nullptr : a.bmask + (size_t)(r / a.bsize) * a.bpitch;
+  auto seen = [&](long long c) { return c >= lo && c < hi && (brow == nullptr || brow[c / a.bsize] != 0); };
   float mx = BURST_NEG_INF;
-  for (long long c = lo + lane; c < hi; c += 64) mx = fmaxf(mx, Srow[c]);
+  for (long long c = lo + lane; c < hi; c += 64)
+    if (seen(c)) mx = fmaxf(mx, Srow[c]);
   mx = wave_max(mx);
   const float ref = (mx == BURST_NEG_INF) ? 0.f : mx;
   float sum = 0.f;
   for (int c = lane; c < a.Ncp; c += 64) {
-    float p = (c >= lo && c < hi) ? fast_exp2((Srow[c] - ref) * kLog2e) : 0.f;
+    float p = seen(c) ? fast_exp2((Srow[c] - ref) * kLog2e) : 0.f;
     T pt = (T)p;
     Prow[c] = pt;
     sum += (float)pt;                   // the sum of what step 3 multiplies with
@@ -289,6 +293,7 @@ int launch_fwd_materialized(const KParams& p, int dtype, bool mfma, const void* 
   a.Q = Q; a.K = K; a.V = V; a.O_acc = O_acc; a.m = m; a.l = l;
   a.Nq = p.Nq; a.Nc = p.Nc; a.Ncp = (p.Nc + 7) & ~7; a.d = p.d; a.BH = (long long)p.B * p.H;
   a.causal = p.causal; a.scale = p.scale; a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
+  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch;
   const size_t rows = (size_t)a.BH * a.Nq;
   const size_t esize = dtype == BURST_BF16 ? 2 : 4;
   char* ws = (char*)workspace;

@@ -12,9 +12,10 @@ from . import binding as B
 class RingWalk:
     """Buffers and call sequence for one query slice against a list of chunks."""
 
-    def __init__(self, Q, scale, causal=False, q_off=0, window=0):
+    def __init__(self, Q, scale, causal=False, q_off=0, window=0, block=0):
         assert Q.dim() == 4
         self.Q = Q
+        self.block = int(block)          # edge of the blocks of per-chunk block masks (0 = no masks)
         self.Bt, self.H, self.Nq, self.d = Q.shape
         self.scale, self.causal, self.q_off, self.window = float(scale), bool(causal), int(q_off), int(window)
         dev = Q.device
@@ -25,32 +26,33 @@ class RingWalk:
         self.lse = torch.empty_like(self.m)
         self.D = torch.empty_like(self.m)
 
-    def params(self, Nc, k_off):
+    def params(self, Nc, k_off, mask=None):
         return B.params(self.Bt, self.H, self.Nq, Nc, self.d, self.Q.dtype, self.scale,
-                        self.causal, self.q_off, k_off, self.window)
+                        self.causal, self.q_off, k_off, self.window, mask, self.block)
 
     # ---- forward (Alg. 1)
     def init(self):
         B.burst_state_init(self.O_acc, self.m, self.l, self.params(0, 0))
 
-    def step(self, K_c, V_c, k_off):
-        B.burst_local_fwd(self.Q, K_c, V_c, self.O_acc, self.m, self.l, self.params(K_c.shape[2], k_off))
+    def step(self, K_c, V_c, k_off, mask=None):
+        B.burst_local_fwd(self.Q, K_c, V_c, self.O_acc, self.m, self.l, self.params(K_c.shape[2], k_off, mask))
 
     def finalize(self):
         B.burst_finalize(self.O_acc, self.m, self.l, self.O, self.lse, self.params(0, 0))
         return self.O, self.lse
 
-    def forward(self, Ks, Vs, k_offs, order=None):
+    def forward(self, Ks, Vs, k_offs, order=None, masks=None):
+        """masks: optional list of per-chunk block masks (uint8 device tensors, see binding.params)."""
         self.init()
         for j in (range(len(Ks)) if order is None else order):
-            self.step(Ks[j], Vs[j], k_offs[j])
+            self.step(Ks[j], Vs[j], k_offs[j], None if masks is None else masks[j])
         return self.finalize()
 
     # ---- backward (Alg. 2), query slice pinned, chunks walked
     def prepare(self, dO):
         B.burst_bwd_prepare(self.O, dO, self.D, self.params(0, 0))
 
-    def backward(self, Ks, Vs, k_offs, dO, dQ=None, dKs=None, dVs=None, use_D=True):
+    def backward(self, Ks, Vs, k_offs, dO, dQ=None, dKs=None, dVs=None, use_D=True, masks=None):
         dev = self.Q.device
         if dQ is None:
             dQ = torch.zeros((self.Bt, self.H, self.Nq, self.d), device=dev, dtype=torch.float32)
@@ -61,7 +63,8 @@ class RingWalk:
             self.prepare(dO)
         for j in range(len(Ks)):
             B.burst_local_bwd(self.Q, Ks[j], Vs[j], self.O, dO, self.lse, self.D if use_D else None,
-                              dQ, dKs[j], dVs[j], self.params(Ks[j].shape[2], k_offs[j]),
+                              dQ, dKs[j], dVs[j],
+                              self.params(Ks[j].shape[2], k_offs[j], None if masks is None else masks[j]),
                               accumulate_dq=True, accumulate_dkv=False)
         return dQ, dKs, dVs
 
@@ -70,8 +73,8 @@ class MaterializedWalk(RingWalk):
     """The forward walk with the chunk step that stores S_ij and P_ij in HBM (the paper's
     "w/o LAO" ablation): same state, same finalize, one workspace sized for the largest chunk."""
 
-    def __init__(self, Q, scale, causal=False, q_off=0, window=0, max_chunk_rows=0):
-        super().__init__(Q, scale, causal, q_off, window)
+    def __init__(self, Q, scale, causal=False, q_off=0, window=0, max_chunk_rows=0, block=0):
+        super().__init__(Q, scale, causal, q_off, window, block)
         self.workspace = None
         if max_chunk_rows:
             self._reserve(max_chunk_rows)
@@ -82,10 +85,10 @@ class MaterializedWalk(RingWalk):
             self.workspace = torch.empty(max(need, 256), device=self.Q.device, dtype=torch.uint8)
         return need
 
-    def step(self, K_c, V_c, k_off):
+    def step(self, K_c, V_c, k_off, mask=None):
         self._reserve(K_c.shape[2])
         B.burst_local_fwd_materialized(self.Q, K_c, V_c, self.O_acc, self.m, self.l, self.workspace,
-                                       self.params(K_c.shape[2], k_off))
+                                       self.params(K_c.shape[2], k_off, mask))
 
     def stored_scores(self, Nc):
         """Views of S_ij (fp32) and P_ij (input type) of the last step: [B, H, Nq, Nc]."""

@@ -120,9 +120,31 @@ def make_inputs(w, device="cpu", seed=None):
     return {"Q": Q, "K": K, "V": V, "dO": dO}
 
 
+def block_flags(n_row_blocks, n_col_blocks, kind="random", density=0.4, seed=0, diag_shift=0):
+    """Seeded block-sparse patterns as a uint8 matrix of block flags (1 = the block pair is
+    computed).  kind: "random" (each flag set with probability `density`), "band" (blocks on and
+    next to the diagonal, which sits `diag_shift` column blocks to the right), "band_global"
+    (band, plus the first column block for every row block and the first row block complete: the
+    shape of global-plus-local patterns for long documents)."""
+    import numpy as np
+    rng = np.random.default_rng(seed)
+    i, j = np.arange(n_row_blocks)[:, None], np.arange(n_col_blocks)[None, :]
+    if kind == "random":
+        f = rng.random((n_row_blocks, n_col_blocks)) < density
+    elif kind in ("band", "band_global"):
+        f = np.abs(j - diag_shift - i) <= 1
+        if kind == "band_global":
+            f = f | (j == 0) | (i == 0)
+    else:
+        raise ValueError(kind)
+    return f.astype(np.uint8)
+
+
 def make_case(B, H, d, Nq, chunk_rows, dtype="bf16", seed=0, device="cpu",
-              causal=False, q_off=0, k_offs=None, window=0):
-    """Free-form case for parity tests: `chunk_rows` lists the rows of each chunk."""
+              causal=False, q_off=0, k_offs=None, window=0, block=0, pattern="random", density=0.4):
+    """Free-form case for parity tests: `chunk_rows` lists the rows of each chunk.  With
+    block > 0 the case carries one block-flag matrix per chunk ("flags": numpy, "masks": the
+    same on the device), blocks counted from the first row of the slice / of each chunk."""
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)
     dt = torch.bfloat16 if dtype == "bf16" else torch.float32
@@ -135,5 +157,13 @@ def make_case(B, H, d, Nq, chunk_rows, dtype="bf16", seed=0, device="cpu",
         for n in chunk_rows:
             k_offs.append(s)
             s += n
-    return {"Q": Q, "K": K, "V": V, "dO": dO, "k_offs": list(k_offs),
+    case = {"Q": Q, "K": K, "V": V, "dO": dO, "k_offs": list(k_offs),
             "q_off": q_off, "causal": causal, "window": window, "scale": 1.0 / math.sqrt(d)}
+    if block:
+        nrb = -(-Nq // block)
+        case["block"] = block
+        case["flags"] = [block_flags(nrb, -(-n // block), pattern, density, seed + 101 * j,
+                                     diag_shift=(q_off - k_offs[j]) // block if pattern != "random" else 0)
+                         for j, n in enumerate(chunk_rows)]
+        case["masks"] = [torch.from_numpy(f).to(device).contiguous() for f in case["flags"]]
+    return case

@@ -34,6 +34,16 @@ def head_inputs(case, b, h, rows=None):
     return Q, K, V, dO, qp, positions(case)
 
 
+def pattern_of(case, rows=None):
+    """Boolean [Nq, total keys] expansion of the case's per-chunk block flags (None if it has none)."""
+    if "flags" not in case:
+        return None
+    nq = case["Q"].shape[2]
+    pat = np.concatenate([orc.block_visibility(nq, k.shape[2], f, case["block"])
+                          for f, k in zip(case["flags"], case["K"])], axis=1)
+    return pat if rows is None else pat[rows]
+
+
 def check(name, got, ref, dtype, kind="abs"):
     """Element-by-element comparison; -inf entries (lse of rows that saw nothing) must match exactly."""
     tol = TOL[dtype]
@@ -60,13 +70,14 @@ def compare_all_heads(case, dtype, O, lse, dQ=None, dKs=None, dVs=None, heads=No
     for b in range(Bt):
         for h in (range(H) if heads is None else heads):
             Q, K, V, dO, qp, kp = head_inputs(case, b, h)
+            pat = pattern_of(case)
             O_ref, lse_ref = orc.full_forward(Q, K, V, case["scale"], case["causal"], qp, kp,
-                                              window=case.get("window", 0))
+                                              window=case.get("window", 0), pattern=pat)
             check(f"O[{b},{h}]", f64(O[b, h]), O_ref, dtype)
             check(f"lse[{b},{h}]", f64(lse[b, h]), lse_ref, dtype, "lse")
             if dQ is not None:
                 dQ_ref, dK_ref, dV_ref = orc.full_backward(Q, K, V, dO, case["scale"], case["causal"], qp, kp,
-                                                           window=case.get("window", 0))
+                                                           window=case.get("window", 0), pattern=pat)
                 check(f"dQ[{b},{h}]", f64(dQ[b, h]), dQ_ref, dtype)
                 d = Q.shape[1]
                 dK = np.concatenate([f64(x[b, h]) for x in dKs]) if dKs else np.zeros((0, d))

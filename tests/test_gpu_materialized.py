@@ -22,14 +22,17 @@ CASES = [
     ("bf16", dict(B=1, H=2, d=64, Nq=70, chunk_rows=[33, 50], causal=True, q_off=20)),  # generic kernels
     ("f32", dict(B=1, H=2, d=16, Nq=45, chunk_rows=[31, 18])),
     ("f32", dict(B=1, H=1, d=128, Nq=40, chunk_rows=[70], causal=True, q_off=35, window=9)),
+    ("bf16", dict(B=1, H=2, d=128, Nq=300, chunk_rows=[200, 140], block=64, pattern="random", density=0.5)),
+    ("bf16", dict(B=1, H=1, d=128, Nq=260, chunk_rows=[260], block=128, pattern="band_global", causal=True)),
 ]
 
 
 @pytest.mark.parametrize("dtype,spec", CASES, ids=lambda v: v if isinstance(v, str) else "-".join(f"{k}{x}" for k, x in v.items()))
 def test_materialized_walk_against_the_oracle(dtype, spec):
     case = workloads.make_case(dtype=dtype, seed=61, device=DEV, **spec)
-    walk = MaterializedWalk(case["Q"], case["scale"], case["causal"], case["q_off"], case.get("window", 0))
-    O, lse = walk.forward(case["K"], case["V"], case["k_offs"])
+    walk = MaterializedWalk(case["Q"], case["scale"], case["causal"], case["q_off"], case.get("window", 0),
+                            block=case.get("block", 0))
+    O, lse = walk.forward(case["K"], case["V"], case["k_offs"], masks=case.get("masks"))
     torch.cuda.synchronize()
     compare_all_heads(case, dtype, O, lse)
 

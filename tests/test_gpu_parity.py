@@ -14,11 +14,13 @@ DEV = "cuda:0"
 
 
 def run_case(case, dtype, backward=True, use_D=True, order=None):
-    walk = RingWalk(case["Q"], case["scale"], case["causal"], case["q_off"], case.get("window", 0))
-    O, lse = walk.forward(case["K"], case["V"], case["k_offs"], order=order)
+    walk = RingWalk(case["Q"], case["scale"], case["causal"], case["q_off"], case.get("window", 0),
+                    case.get("block", 0))
+    masks = case.get("masks")
+    O, lse = walk.forward(case["K"], case["V"], case["k_offs"], order=order, masks=masks)
     res = (O, lse, None, None, None)
     if backward:
-        dQ, dKs, dVs = walk.backward(case["K"], case["V"], case["k_offs"], case["dO"], use_D=use_D)
+        dQ, dKs, dVs = walk.backward(case["K"], case["V"], case["k_offs"], case["dO"], use_D=use_D, masks=masks)
         res = (O, lse, dQ, dKs, dVs)
     torch.cuda.synchronize()
     return walk, res
@@ -52,6 +54,37 @@ def test_bf16_mfma_forward_backward(spec):
     case = workloads.make_case(dtype="bf16", seed=17, device=DEV, **spec)
     _, (O, lse, dQ, dKs, dVs) = run_case(case, "bf16")
     compare_all_heads(case, "bf16", O, lse, dQ, dKs, dVs)
+
+
+# Block-sparse patterns (Sec. 2.6): one flag matrix per chunk, blocks of 64 .. 256 rows/keys; random flags
+# (rows and whole chunks that see nothing included), a band around the diagonal, band + global blocks.
+SPARSE_CASES = [
+    dict(B=1, H=2, d=128, Nq=300, chunk_rows=[200, 64, 331], block=64, pattern="random"),
+    dict(B=2, H=2, d=128, Nq=517, chunk_rows=[256, 1, 390], block=128, pattern="random", density=0.5),
+    dict(B=1, H=3, d=128, Nq=700, chunk_rows=[512, 300], block=256, pattern="random", density=0.3),
+    dict(B=1, H=2, d=128, Nq=640, chunk_rows=[640, 640], block=64, pattern="band", causal=True, q_off=640),
+    dict(B=1, H=2, d=128, Nq=600, chunk_rows=[384, 421], block=128, pattern="band_global", causal=True, q_off=300),
+    dict(B=1, H=1, d=128, Nq=520, chunk_rows=[300, 300, 300], block=64, pattern="random", density=0.6,
+         causal=True, q_off=380, window=200),
+    dict(B=1, H=2, d=128, Nq=200, chunk_rows=[256, 256], block=64, pattern="random", density=0.0),   # nothing visible
+]
+
+
+@pytest.mark.parametrize("spec", SPARSE_CASES, ids=lambda s: "-".join(f"{k}{v}" for k, v in s.items() if k != "d"))
+def test_bf16_block_sparse_forward_backward(spec):
+    case = workloads.make_case(dtype="bf16", seed=29, device=DEV, **spec)
+    _, (O, lse, dQ, dKs, dVs) = run_case(case, "bf16")
+    compare_all_heads(case, "bf16", O, lse, dQ, dKs, dVs)
+
+
+@pytest.mark.parametrize("dtype,spec", [
+    ("f32", dict(B=1, H=2, d=32, Nq=150, chunk_rows=[100, 90], block=64, pattern="random", density=0.5)),
+    ("bf16", dict(B=1, H=2, d=64, Nq=130, chunk_rows=[200], block=64, pattern="band_global", causal=True, q_off=70)),
+])
+def test_generic_kernels_block_sparse(dtype, spec):
+    case = workloads.make_case(dtype=dtype, seed=37, device=DEV, **spec)
+    _, (O, lse, dQ, dKs, dVs) = run_case(case, dtype)
+    compare_all_heads(case, dtype, O, lse, dQ, dKs, dVs)
 
 
 def test_config0_tiny_fp32_complete():

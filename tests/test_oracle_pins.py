@@ -420,3 +420,69 @@ def test_window_backward_matches_central_differences():
             args[idx][i, t] -= 2 * h
             fd = (up - loss(*args)) / (2 * h)
             assert abs(fd - grads[idx][i, t]) < 1e-8 * max(1.0, abs(fd)), (idx, i, t)
+
+
+# ---------------------------------------------------------------- block patterns (Sec. 2.6: skipped block pairs)
+def test_block_visibility_expands_flags_blockwise():
+    flags = np.array([[1, 0, 1], [0, 0, 2]])
+    vis = orc.block_visibility(5, 7, flags, 3)          # rows 0-2 / 3-4, columns 0-2 / 3-5 / 6
+    assert vis.shape == (5, 7) and vis.dtype == bool
+    for r in range(5):
+        for c in range(7):
+            assert vis[r, c] == (flags[r // 3, c // 3] != 0)
+    assert vis.sum() == 3 * 3 + 3 * 1 + 2 * 1
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_block_pattern_equals_plain_attention_on_the_visible_keys(causal):
+    """Row by row: attention under a block pattern = plain attention (no pattern argument) over
+    exactly the keys of the row's visible blocks; gradients scatter back accordingly.  Also the
+    chunked algorithm with one flag matrix per chunk, some chunks fully hidden for some rows."""
+    r = rng(31)
+    nq, nk, d, blk = 10, 16, 5, 4
+    Q, K, V, dO = (r.normal(size=(n, d)) for n in (nq, nk, nk, nq))
+    scale = 0.4
+    q_pos, k_pos = 6 + np.arange(nq), np.arange(nk)
+    flags = np.array([[1, 0, 0, 1], [0, 1, 0, 0], [1, 1, 0, 1]])       # 3 row blocks x 4 key blocks
+    pattern = orc.block_visibility(nq, nk, flags, blk)
+    O, lse = orc.full_forward(Q, K, V, scale, causal, q_pos, k_pos, pattern=pattern)
+    dQ, dK, dV = orc.full_backward(Q, K, V, dO, scale, causal, q_pos, k_pos, pattern=pattern)
+    dK2, dV2 = np.zeros_like(K), np.zeros_like(V)
+    for i in range(nq):
+        keep = [c for c in range(nk) if flags[i // blk, c // blk] and (not causal or k_pos[c] <= q_pos[i])]
+        assert keep, "every row of this pattern sees something"
+        Oi, lsei = orc.full_forward(Q[i:i + 1], K[keep], V[keep], scale)
+        dqi, dki, dvi = orc.full_backward(Q[i:i + 1], K[keep], V[keep], dO[i:i + 1], scale)
+        assert np.allclose(O[i], Oi[0], atol=1e-14) and abs(lse[i] - lsei[0]) < 1e-14
+        assert np.allclose(dQ[i], dqi[0], atol=1e-14)
+        dK2[keep] += dki
+        dV2[keep] += dvi
+    assert np.allclose(dK, dK2, atol=1e-13) and np.allclose(dV, dV2, atol=1e-13)
+    sizes = [8, 4, 4]                                   # chunk boundaries on block boundaries
+    cols = np.cumsum([0] + sizes)
+    pats = [pattern[:, cols[j]:cols[j + 1]] for j in range(3)]
+    for j in range(3):                                  # the same thing from per-chunk flag matrices
+        fj = flags[:, cols[j] // blk: cols[j + 1] // blk]
+        assert np.array_equal(pats[j], orc.block_visibility(nq, sizes[j], fj, blk))
+    kp = split(k_pos, sizes)
+    Oc, lsec = orc.gao_forward(Q, split(K, sizes), split(V, sizes), scale, causal, q_pos, kp, pattern_chunks=pats)
+    dQc, dKs, dVs = orc.gao_backward(Q, split(K, sizes), split(V, sizes), Oc, dO, lsec, scale, causal, q_pos, kp,
+                                     pattern_chunks=pats)
+    for a, b in ((O, Oc), (lse, lsec), (dQ, dQc), (dK, np.concatenate(dKs)), (dV, np.concatenate(dVs))):
+        assert np.max(np.abs(a - b)) < 1e-13
+
+
+def test_block_pattern_all_ones_is_no_pattern_and_hidden_rows_get_nothing():
+    r = rng(32)
+    nq, nk, d = 6, 9, 4
+    Q, K, V, dO = (r.normal(size=(n, d)) for n in (nq, nk, nk, nq))
+    ones = orc.block_visibility(nq, nk, np.ones((2, 3)), 3)
+    a, b = orc.full_forward(Q, K, V, 0.5), orc.full_forward(Q, K, V, 0.5, pattern=ones)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    flags = np.array([[0, 0, 0], [1, 0, 1]])            # rows 0-2 see nothing
+    pat = orc.block_visibility(nq, nk, flags, 3)
+    O, lse = orc.full_forward(Q, K, V, 0.5, pattern=pat)
+    assert np.all(O[:3] == 0) and np.all(np.isneginf(lse[:3])) and np.all(np.isfinite(lse[3:]))
+    dQ, dK, dV = orc.full_backward(Q, K, V, dO, 0.5, pattern=pat)
+    assert np.all(dQ[:3] == 0) and np.all(dK[3:6] == 0) and np.all(dV[3:6] == 0)
+    assert np.allclose(dV.sum(axis=0), dO[3:].sum(axis=0), atol=1e-13)      # visible rows of P sum to 1
