@@ -80,9 +80,11 @@ int check_params(const burst_params* p, KParams* k) {
 // The MFMA kernels address a head's rows through 32-bit byte offsets (256 B per row, plus a few
 // tiles of prefetch past the end); longer slices or chunks take the generic kernels.
 constexpr int kMaxMfmaRows = 4 * 1024 * 1024;
+// With block flags the MFMA kernels keep a list of visible tiles in LDS: at most 8192 tiles of
+// 64 keys (forward) per chunk; longer masked chunks take the generic kernels.
+constexpr int kMaxMaskedRows = 8192 * 64;
 bool use_mfma(const burst_params* p) {
-  return p->dtype == BURST_BF16 && p->d == 128 && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows &&
-         p->block_mask == nullptr;
+  return p->dtype == BURST_BF16 && p->d == 128 && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows;
 }
 
 int get_d_scratch(size_t elems, float** out) {
@@ -127,7 +129,8 @@ int burst_local_fwd(const void* Q, const void* K_chunk, const void* V_chunk,
   REQUIRE_PTR(Q); REQUIRE_PTR(K_chunk); REQUIRE_PTR(V_chunk);
   REQUIRE_PTR(O_acc); REQUIRE_PTR(m); REQUIRE_PTR(l);
   if ((st = check_arch()) != BURST_OK) return st;
-  if (use_mfma(p)) return burst::launch_fwd_mfma(k, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
+  if (use_mfma(p) && (p->block_mask == nullptr || p->Nc <= kMaxMaskedRows))
+    return burst::launch_fwd_mfma(k, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
   return burst::launch_fwd_generic(k, p->dtype, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
 }
 
@@ -227,7 +230,7 @@ static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const v
     if ((st = burst::launch_bwd_prepare(k, p->dtype, O, dO, scratch, s)) != BURST_OK) return st;
     Duse = scratch;
   }
-  const bool mfma = use_mfma(p);
+  const bool mfma = use_mfma(p) && p->block_mask == nullptr;
   if (want_dq) {
     st = mfma ? burst::launch_bwd_dq_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)
               : burst::launch_bwd_dq_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dQ,

@@ -25,6 +25,8 @@ constexpr int FWD_BC = 64;    // keys per tile
 constexpr int FWD_TILE_BYTES = FWD_BC * 256;
 constexpr int FWD_NBUF = 3;
 constexpr float FWD_LAZY = 8.0f;   // log2 of the largest P allowed before the max is raised
+constexpr int FWD_MAX_LIST = 8192;  // block-sparse calls: most key tiles of one chunk (512K keys)
+constexpr int FWD_LIST_BYTES = (FWD_MAX_LIST + 8) * 4;
 
 struct FwdArgs {
   const bf16* Q; const bf16* K; const bf16* V;
@@ -35,6 +37,8 @@ struct FwdArgs {
   long long q_off, k_off;
   long long window;      // 0 = none; else keys at positions <= query position - window are hidden
   int q_blocks;          // ceil(Nq / FWD_BR)
+  const uint8_t* bmask;  // block flags [ceil(Nq / bsize)][bpitch], nullptr = none (paper Sec. 2.6)
+  int bsize, bpitch;     // bsize: a multiple of 64, so a wavefront's 64 rows and a key tile lie in one block
 };
 
 // HBM -> LDS for one 64x128 bf16 tile (K or V) without staging registers.  One wave-wide
@@ -74,6 +78,12 @@ __device__ __forceinline__ void qk_tile(const char* kl, const int (&kaddr)[8], c
   }
 }
 
+// SPARSE: the call carries block flags.  The workgroup first writes the list of key tiles that at
+// least one of its wavefronts can see (tile index plus one bit per wavefront) into LDS and then
+// walks that list instead of 0, 1, 2, ...; a wavefront whose bit is clear hides the whole tile
+// in the masking path.  Entries past the end name a tile beyond the chunk: its DMA reads zeros
+// and the ragged-tail mask hides it.
+template <bool SPARSE>
 __global__ void __launch_bounds__(256, 1)
 burst_fwd_mfma_kernel(FwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -104,13 +114,18 @@ burst_fwd_mfma_kernel(FwdArgs a) {
   // tiles; everything below works on that shortened chunk.
   int Nc = a.Nc;
   long long k_off = a.k_off;
+  int t_lo = 0;                                    // SPARSE: first tile of the list (the chunk is not shifted)
   if (a.window > 0) {
     long long lo = a.q_off + (long long)qb * FWD_BR - a.window + 1 - a.k_off;   // first visible key index
     if (lo >= a.Nc) return;                        // nothing visible: state unchanged
     if (lo > 0) {
       const int skip = (int)(lo / FWD_BC) * FWD_BC;
-      Kh += (size_t)skip * 128; Vh += (size_t)skip * 128;
-      Nc -= skip; k_off += skip;
+      if constexpr (SPARSE) {
+        t_lo = skip / FWD_BC;
+      } else {
+        Kh += (size_t)skip * 128; Vh += (size_t)skip * 128;
+        Nc -= skip; k_off += skip;
+      }
     }
   }
 
@@ -125,6 +140,43 @@ burst_fwd_mfma_kernel(FwdArgs a) {
     if (t < ntiles) ntiles = (int)t;
   }
   if (ntiles <= 0) return;
+
+  // SPARSE: the list of visible tiles, built by wavefront 0 (64 candidate tiles per round).
+  // list[0] = number of entries, list[1 + j] = tile | (wavefront bits << 16), then 4 end entries.
+  int* const list = reinterpret_cast<int*>(smem + 2 * FWD_NBUF * FWD_TILE_BYTES);
+  if constexpr (SPARSE) {
+    const int end_tile = (Nc + FWD_BC - 1) / FWD_BC;             // a tile past the chunk
+    if (w == 0) {
+      int n = 0;
+      for (int base = t_lo; base < ntiles; base += 64) {
+        const int kt = base + lane;
+        int bits = 0;
+        if (kt < ntiles) {
+          const int col = (kt * FWD_BC) / a.bsize;
+#pragma unroll
+          for (int ww = 0; ww < 4; ww++) {
+            const int row0 = qb * FWD_BR + ww * 64;
+            if (row0 < a.Nq && a.bmask[(size_t)(row0 / a.bsize) * a.bpitch + col] != 0) bits |= 1 << ww;
+          }
+        }
+        const unsigned long long bal = __builtin_amdgcn_ballot_w64(bits != 0);
+        if (bits != 0) {
+          const int pos = n + __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0u));
+          list[1 + pos] = kt | (bits << 16);
+        }
+        n += __builtin_popcountll(bal);
+      }
+      if (lane < 4) list[1 + n + lane] = end_tile;
+      if (lane == 0) list[0] = n;
+    }
+    __syncthreads();
+    ntiles = __builtin_amdgcn_readfirstlane(list[0]);            // from here on: number of list entries
+    if (ntiles == 0) return;
+  }
+  auto tile_at = [&](int j) __attribute__((always_inline)) {      // tile index of list entry j
+    if constexpr (SPARSE) return __builtin_amdgcn_readfirstlane(list[1 + j]) & 0xffff;
+    else return j;
+  };
 
   // Q fragments (B operand): lane holds row lr of each 32-row block, 8 consecutive d.
   bf16x8 qf[2][8];
@@ -178,12 +230,14 @@ burst_fwd_mfma_kernel(FwdArgs a) {
   int goff[4];
   tile_dma_offsets(w, lane, goff);
 #pragma unroll
-  for (int t = 0; t < 3; t++)
+  for (int t = 0; t < 3; t++) {
+    const int src = tile_at(t);
 #pragma unroll
     for (int il = 0; il < 4; il++) {
-      tile_dma(krs, lds0 + t * FWD_TILE_BYTES, wu, il, t * FWD_TILE_BYTES + goff[il]);
-      if (t < 2) tile_dma(vrs, lds0 + (3 + t) * FWD_TILE_BYTES, wu, il, t * FWD_TILE_BYTES + goff[il]);
+      tile_dma(krs, lds0 + t * FWD_TILE_BYTES, wu, il, src * FWD_TILE_BYTES + goff[il]);
+      if (t < 2) tile_dma(vrs, lds0 + (3 + t) * FWD_TILE_BYTES, wu, il, src * FWD_TILE_BYTES + goff[il]);
     }
+  }
   __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): this wavefront's DMA has landed
   __builtin_amdgcn_s_barrier();                    // ... and everyone else's
   // Two score buffers that swap roles every tile (the loop body is unrolled twice, so no
@@ -211,9 +265,18 @@ burst_fwd_mfma_kernel(FwdArgs a) {
   ones[0] = (bf16)1.0f; ones[1] = (bf16)1.0f;
   constexpr int PF = 4;          // operand fragments are fetched PF MFMA pairs ahead
 
-  // One tile: `sc` holds S^T of tile kt (unmasked), `sx` receives S^T of tile kt + 1.
-  // slot = kt % 3 is the LDS ring slot of tile kt.
-  auto step = [&](f32x16 (&sc)[2][2], f32x16 (&sx)[2][2], int kt, int slot) __attribute__((always_inline)) {
+  // One tile: `sc` holds S^T of tile kt (unmasked), `sx` receives S^T of the next tile.
+  // jt = position of the tile in the walk (dense: jt = kt), slot = jt % 3 its LDS ring slot.
+  auto step = [&](f32x16 (&sc)[2][2], f32x16 (&sx)[2][2], int jt, int slot) __attribute__((always_inline)) {
+    int kt = jt, kt2 = jt + 2, kt3 = jt + 3;       // this tile, and the tiles whose V / K are fetched now
+    bool mine = true;                              // SPARSE: this wavefront's rows can see the tile
+    if constexpr (SPARSE) {
+      const int e = __builtin_amdgcn_readfirstlane(list[1 + jt]);
+      kt = e & 0xffff;
+      mine = ((e >> (16 + wu)) & 1) != 0;
+      kt2 = tile_at(jt + 2);
+      kt3 = tile_at(jt + 3);
+    }
     const int slot1 = (slot == FWD_NBUF - 1) ? 0 : slot + 1;     // tile kt + 1
     const int slot2 = (slot1 == FWD_NBUF - 1) ? 0 : slot1 + 1;   // tile kt + 2
     const char* kl_next = smem + slot1 * FWD_TILE_BYTES;         // K of tile kt + 1
@@ -228,7 +291,7 @@ burst_fwd_mfma_kernel(FwdArgs a) {
     // ---- masking (diagonal tiles, ragged key tail): rare; redo the row maxima afterwards
     const bool need_mask = (a.causal && tile_first_k + FWD_BC - 1 > wave_first_q) ||
                            (a.window > 0 && tile_first_k < wave_last_q - a.window + 1) ||
-                           ((kt + 1) * FWD_BC > Nc);
+                           ((kt + 1) * FWD_BC > Nc) || !mine;
     if (need_mask) {
       raise = false;
 #pragma unroll
@@ -243,6 +306,7 @@ burst_fwd_mfma_kernel(FwdArgs a) {
         const int tail = Nc - 1 - (kt * FWD_BC + 4 * mh);
         int lim = a.causal ? (int)(dd < -1 ? -1 : (dd > 64 ? 64 : dd)) : 64;
         lim = lim < tail ? lim : tail;
+        if (!mine) lim = -1;
         const long long dl = dd - a.window + 1;
         const int lim_lo = a.window > 0 ? (int)(dl < -1 ? -1 : (dl > 64 ? 64 : dl)) : -1;
         float v = BURST_NEG_INF;
@@ -348,8 +412,8 @@ burst_fwd_mfma_kernel(FwdArgs a) {
       }
       if ((i & 3) == 1) {                          // 8 slots: one DMA of 4 tile rows each
         const int j = i >> 2;                      // 0..3 -> K of tile kt + 3, 4..7 -> V of tile kt + 2
-        if (j < 4) tile_dma(krs, k_dst, wu, j, (kt + 3) * FWD_TILE_BYTES + goff[j]);
-        else tile_dma(vrs, v_dst, wu, j - 4, (kt + 2) * FWD_TILE_BYTES + goff[j - 4]);
+        if (j < 4) tile_dma(krs, k_dst, wu, j, kt3 * FWD_TILE_BYTES + goff[j]);
+        else tile_dma(vrs, v_dst, wu, j - 4, kt2 * FWD_TILE_BYTES + goff[j - 4]);
       }
       {
         bf16x8 vf;
@@ -434,17 +498,26 @@ int launch_fwd_mfma(const KParams& p, const void* Q, const void* K, const void* 
   a.c = p.scale * kLog2e;
   a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
   a.q_blocks = (p.Nq + FWD_BR - 1) / FWD_BR;
+  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch;
   int heads8 = ((a.H + 7) / 8) * 8;                // pad the head count to a multiple of 8 ids
   long long nblocks = (long long)heads8 * a.q_blocks;
   if (nblocks > 0x7fffffffLL) return BURST_ERR_SHAPE;
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)burst_fwd_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            2 * FWD_NBUF * FWD_TILE_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
+    if (hipFuncSetAttribute((const void*)burst_fwd_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            2 * FWD_NBUF * FWD_TILE_BYTES) != hipSuccess ||
+        hipFuncSetAttribute((const void*)burst_fwd_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            2 * FWD_NBUF * FWD_TILE_BYTES + FWD_LIST_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
     attr_set = true;
   }
-  hipLaunchKernelGGL(burst_fwd_mfma_kernel, dim3((unsigned)nblocks), dim3(256),
-                     2 * FWD_NBUF * FWD_TILE_BYTES, stream, a);
+  if (a.bmask != nullptr) {
+    if ((p.Nc + FWD_BC - 1) / FWD_BC > FWD_MAX_LIST) return BURST_ERR_SHAPE;
+    hipLaunchKernelGGL(burst_fwd_mfma_kernel<true>, dim3((unsigned)nblocks), dim3(256),
+                       2 * FWD_NBUF * FWD_TILE_BYTES + FWD_LIST_BYTES, stream, a);
+  } else {
+    hipLaunchKernelGGL(burst_fwd_mfma_kernel<false>, dim3((unsigned)nblocks), dim3(256),
+                       2 * FWD_NBUF * FWD_TILE_BYTES, stream, a);
+  }
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 
