@@ -80,8 +80,8 @@ int check_params(const burst_params* p, KParams* k) {
 // The MFMA kernels address a head's rows through 32-bit byte offsets (256 B per row, plus a few
 // tiles of prefetch past the end); longer slices or chunks take the generic kernels.
 constexpr int kMaxMfmaRows = 4 * 1024 * 1024;
-// With block flags the MFMA kernels keep a list of visible tiles in LDS: at most 8192 tiles of
-// 64 keys (forward) per chunk; longer masked chunks take the generic kernels.
+// With block flags the MFMA kernels keep a list of visible tiles in LDS (8192 tiles of 64 keys or
+// rows, or 16384 of 32 keys): longer masked slices or chunks take the generic kernels.
 constexpr int kMaxMaskedRows = 8192 * 64;
 bool use_mfma(const burst_params* p) {
   return p->dtype == BURST_BF16 && p->d == 128 && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows;
@@ -230,7 +230,7 @@ static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const v
     if ((st = burst::launch_bwd_prepare(k, p->dtype, O, dO, scratch, s)) != BURST_OK) return st;
     Duse = scratch;
   }
-  const bool mfma = use_mfma(p) && p->block_mask == nullptr;
+  const bool mfma = use_mfma(p) && (p->block_mask == nullptr || (p->Nq <= kMaxMaskedRows && p->Nc <= kMaxMaskedRows));
   if (want_dq) {
     st = mfma ? burst::launch_bwd_dq_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)
               : burst::launch_bwd_dq_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dQ,

@@ -33,7 +33,15 @@ constexpr int DKV_LDS_L = 2 * DKV_SLOTS * DKV_TILE_BYTES;              // -lse /
 constexpr int DKV_LDS_D = DKV_LDS_L + DKV_STAT_SLOTS * DKV_BR * 4;     // -D per row
 constexpr int DKV_LDS_DUMMY = DKV_LDS_D + DKV_STAT_SLOTS * DKV_BR * 4; // sink of the padding DMA (256 B)
 constexpr int DKV_LDS_BYTES = DKV_LDS_DUMMY + 256;
+constexpr int DKV_MAX_LIST = 8192;    // block-sparse calls: most query tiles of one slice (512K rows)
+constexpr int DKV_LIST_BYTES = (DKV_MAX_LIST + 8) * 4;
 
+// SPARSE: the call carries block flags (paper Sec. 2.6).  The workgroup first writes the list of
+// query tiles that at least one of its wavefronts' keys are visible to (tile index plus one bit per
+// wavefront) into LDS and then walks that list instead of t_begin, t_begin + 1, ...; a wavefront
+// whose bit is clear hides the whole tile in the masking path.  Entries past the end name a tile
+// beyond the slice: its Q, dO and statistics read as zeros and contribute nothing.
+template <bool SPARSE>
 __global__ void __launch_bounds__(256, 1)
 burst_bwd_dkv_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -76,7 +84,44 @@ burst_bwd_dkv_kernel(BwdArgs a) {
 #pragma unroll
     for (int r = 0; r < 16; r++) { dk[db][r] = 0.f; dv[db][r] = 0.f; }
 
-  if (t_begin < ntiles_all) {
+  int nwalk = ntiles_all - t_begin;                // tiles to walk
+  // SPARSE: the list of visible tiles, built by wavefront 0 (64 candidate tiles per round).
+  // list[0] = number of entries, list[1 + j] = tile | (wavefront bits << 16), then 4 end entries.
+  int* const list = reinterpret_cast<int*>(smem + DKV_LDS_BYTES);
+  if constexpr (SPARSE) {
+    const int end_tile = (a.Nq + DKV_BR - 1) / DKV_BR;          // a tile past the slice
+    if (w == 0) {
+      int n = 0;
+      for (int base = t_begin; base < ntiles_all; base += 64) {
+        const int t = base + lane;
+        int bits = 0;
+        if (t < ntiles_all) {
+          const uint8_t* mrow = a.bmask + (size_t)((t * DKV_BR) / a.bsize) * a.bpitch;
+#pragma unroll
+          for (int ww = 0; ww < 4; ww++) {
+            const int k0 = key_wg + ww * 32;
+            if (k0 < a.Nc && mrow[k0 / a.bsize] != 0) bits |= 1 << ww;
+          }
+        }
+        const unsigned long long bal = __builtin_amdgcn_ballot_w64(bits != 0);
+        if (bits != 0) {
+          const int pos = n + __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0u));
+          list[1 + pos] = t | (bits << 16);
+        }
+        n += __builtin_popcountll(bal);
+      }
+      if (lane < 4) list[1 + n + lane] = end_tile;
+      if (lane == 0) list[0] = n;
+    }
+    __syncthreads();
+    nwalk = __builtin_amdgcn_readfirstlane(list[0]);
+  }
+  auto tile_at = [&](int j) __attribute__((always_inline)) {      // tile index of walk position j
+    if constexpr (SPARSE) return __builtin_amdgcn_readfirstlane(list[1 + j]) & 0xffff;
+    else return t_begin + j;
+  };
+
+  if (nwalk > 0) {
     // K, V fragments (B operands: lane = key lr, 8 consecutive d)
     bf16x8 kf[8], vf[8];
     {
@@ -165,14 +210,15 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     // t_begin .. t_begin + 2 into statistic slots 0 .. 2, the first two scaled right away
 #pragma unroll
     for (int t = 0; t < 2; t++) {
+      const int src = tile_at(t);
 #pragma unroll
       for (int il = 0; il < 4; il++) {
-        dma_tile(qrs, lds0 + DKV_LDS_Q + t * DKV_TILE_BYTES, il, t_begin + t);
-        dma_tile(grs, lds0 + DKV_LDS_G + t * DKV_TILE_BYTES, il, t_begin + t);
+        dma_tile(qrs, lds0 + DKV_LDS_Q + t * DKV_TILE_BYTES, il, src);
+        dma_tile(grs, lds0 + DKV_LDS_G + t * DKV_TILE_BYTES, il, src);
       }
     }
 #pragma unroll
-    for (int t = 0; t < 3; t++) dma_rowstat(t_begin + t, t);
+    for (int t = 0; t < 3; t++) dma_rowstat(tile_at(t), t);
     __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0), lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
     scale_rowstat(0);
@@ -203,10 +249,18 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     load_init(0, reinterpret_cast<const float*>(smem + DKV_LDS_L), reinterpret_cast<const float*>(smem + DKV_LDS_D));
 
     int slot = 0;
-    for (int t = t_begin; t < ntiles_all; t++) {
+    for (int n = 0; n < nwalk; n++) {                  // n = walk position; statistic slot n & 3 holds its tile
+      int t = t_begin + n, t2 = t + 2, t3 = t + 3;     // this tile, and the tiles whose rows / statistics are fetched now
+      bool mine = true;                                // SPARSE: this wavefront's keys are visible to the tile
+      if constexpr (SPARSE) {
+        const int e = __builtin_amdgcn_readfirstlane(list[1 + n]);
+        t = e & 0xffff;
+        mine = ((e >> (16 + wu)) & 1) != 0;
+        t2 = tile_at(n + 2);
+        t3 = tile_at(n + 3);
+      }
       const int slot1 = (slot == DKV_SLOTS - 1) ? 0 : slot + 1;
       const int slot2 = (slot1 == DKV_SLOTS - 1) ? 0 : slot1 + 1;
-      const int n = t - t_begin;                       // statistic slots: n & 3 holds tile t
       const char* ql = smem + DKV_LDS_Q + slot * DKV_TILE_BYTES;
       const char* gl = smem + DKV_LDS_G + slot * DKV_TILE_BYTES;
       const float* lp = reinterpret_cast<const float*>(smem + DKV_LDS_L) + (n & 3) * DKV_BR;
@@ -217,7 +271,7 @@ burst_bwd_dkv_kernel(BwdArgs a) {
       // (no branch around the MFMA phases: the AGPR-pinned accumulators must not become phi
       // values, the allocator would shuttle them through VGPRs every iteration)
       const bool need_mask = (a.causal && wave_last_k > tile_first_q) ||
-                             (a.window > 0 && tile_first_q + DKV_BR - 1 >= wave_first_k + a.window);
+                             (a.window > 0 && tile_first_q + DKV_BR - 1 >= wave_first_k + a.window) || !mine;
       {
         // A-operand read j (0..31): rb = j / 16, ks = (j / 2) % 8, even: Q fragment (for S), odd:
         // dO fragment (for dP).  S and dP alternate so that no MFMA waits for its predecessor.
@@ -269,7 +323,7 @@ burst_bwd_dkv_kernel(BwdArgs a) {
         // A masked score becomes -inf, its P and dS become 0.
         auto mask_block = [&](int rb) __attribute__((always_inline)) {
           const long long d = kpos - (tile_first_q + rb * 32 + 4 * h);
-          const int lim = a.causal ? (int)(d < -1 ? -1 : (d > 64 ? 64 : d)) : -1;
+          const int lim = !mine ? 65 : a.causal ? (int)(d < -1 ? -1 : (d > 64 ? 64 : d)) : -1;
           const long long d2 = d + a.window - 1;
           const int lim2 = a.window > 0 ? (int)(d2 < -1 ? -1 : (d2 > 64 ? 64 : d2)) : 64;
 #pragma unroll
@@ -310,11 +364,11 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           if (i == 22) rowstat_store((n + 2) & 3);
           // phase 4 has no vector work: the DMA of tile t + 2 (into the slot of tile t - 1, free
           // since the last barrier) and of the statistics of tile t + 3 is issued here
-          if (i == 16) dma_rowstat(t + 3, (n + 3) & 3);
+          if (i == 16) dma_rowstat(t3, (n + 3) & 3);
           if (i > 16 && (i & 1)) {
             const int j = (i - 17) >> 1;                  // 0..7: Q rows, then dO rows
-            if (j < 4) dma_tile(qrs, lds0 + DKV_LDS_Q + slot2 * DKV_TILE_BYTES, j, t + 2);
-            else dma_tile(grs, lds0 + DKV_LDS_G + slot2 * DKV_TILE_BYTES, j - 4, t + 2);
+            if (j < 4) dma_tile(qrs, lds0 + DKV_LDS_Q + slot2 * DKV_TILE_BYTES, j, t2);
+            else dma_tile(grs, lds0 + DKV_LDS_G + slot2 * DKV_TILE_BYTES, j - 4, t2);
           }
           const bf16x8 bt = cat4(tq[i % TRING][0], tq[i % TRING][1]);
           if (isk) mfma32_acc(dk[db], dsf[rb][u], bt);
@@ -360,8 +414,10 @@ int launch_bwd_dkv_mfma(const KParams& p, const void* Q, const void* K, const vo
   if (p.Nc <= 0) return BURST_OK;
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            DKV_LDS_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
+    if (hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            DKV_LDS_BYTES) != hipSuccess ||
+        hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            DKV_LDS_BYTES + DKV_LIST_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
     attr_set = true;
   }
   BwdArgs a = make_bwd_args(p, Q, K, V, dO, lse, D, nullptr, dK, dV, 0, acc_dkv);
@@ -369,7 +425,12 @@ int launch_bwd_dkv_mfma(const KParams& p, const void* Q, const void* K, const vo
   a.blocks_per_head = (p.Nc + DKV_BC - 1) / DKV_BC;
   long long nb = (long long)heads8 * a.blocks_per_head;
   if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;
-  hipLaunchKernelGGL(burst_bwd_dkv_kernel, dim3((unsigned)nb), dim3(256), DKV_LDS_BYTES, stream, a);
+  if (a.bmask != nullptr) {
+    if ((p.Nq + DKV_BR - 1) / DKV_BR > DKV_MAX_LIST) return BURST_ERR_SHAPE;
+    hipLaunchKernelGGL(burst_bwd_dkv_kernel<true>, dim3((unsigned)nb), dim3(256), DKV_LDS_BYTES + DKV_LIST_BYTES, stream, a);
+  } else {
+    hipLaunchKernelGGL(burst_bwd_dkv_kernel<false>, dim3((unsigned)nb), dim3(256), DKV_LDS_BYTES, stream, a);
+  }
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 

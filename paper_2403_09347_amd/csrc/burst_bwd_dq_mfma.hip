@@ -31,6 +31,8 @@ constexpr int DQ_TILE_BYTES = DQ_BC * 256;
 constexpr int DQ_KSLOTS = 5;          // K of tiles t-1 (dQ), t (S), t+1, t+2 (landed), t+3 (in flight)
 constexpr int DQ_VSLOTS = 4;          // V of tiles t (dP), t+1, t+2, t+3
 constexpr int DQ_LDS_BYTES = (DQ_KSLOTS + DQ_VSLOTS) * DQ_TILE_BYTES;
+constexpr int DQ_MAX_LIST = 16384;    // block-sparse calls: most key tiles of one chunk (512K keys)
+constexpr int DQ_LIST_BYTES = (DQ_MAX_LIST + 8) * 4;
 
 // dP^T MFMA: accumulator in VGPRs (the vector unit reads it next), B operand (a dO fragment of
 // the wavefront's own rows, resident for the whole kernel) in AGPRs, which this kernel otherwise
@@ -54,12 +56,18 @@ __device__ __forceinline__ void mfma_vgpr_fence(f32x16 (&acc)[2]) {
   asm volatile("s_nop 15\n\ts_nop 3" : "+v"(acc[0]), "+v"(acc[1]));
 }
 
-// WINDOW = false compiles the sliding-window code away: this kernel uses every register of the
-// file, and the few values the window logic keeps alive would otherwise push others to scratch.
-template <bool WINDOW>
+// MODE 0 compiles the sliding-window code away: this kernel uses every register of the file, and
+// the few values the window logic keeps alive would otherwise push others to scratch.  MODE 1
+// has it.  MODE 2 (the call carries block flags, paper Sec. 2.6) has it too and walks a list of
+// the key tiles that at least one wavefront of the workgroup can see, built in LDS at the start
+// (tile index plus one bit per wavefront); a wavefront whose bit is clear hides the whole tile
+// in the masking path.  Entries past the end name a tile beyond the chunk: its DMA reads zeros
+// and the ragged-tail mask hides it.
+template <int MODE>
 __global__ void __launch_bounds__(256, 1)
 burst_bwd_dq_kernel(BwdArgs a) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr bool WINDOW = MODE != 0, SPARSE = MODE == 2;
   const long long window = WINDOW ? a.window : 0;
   const int tid = threadIdx.x;
   const int w = tid >> 6, lane = tid & 63, lr = lane & 31, h = lane >> 5;
@@ -86,21 +94,62 @@ burst_bwd_dq_kernel(BwdArgs a) {
   // tiles; everything below works on that shortened chunk.
   int Nc = a.Nc;
   long long k_off = a.k_off;
+  int t_lo = 0;                                    // SPARSE: first tile of the list (the chunk is not shifted)
+  bool nothing = false;
   if (window > 0) {
     long long lo = a.q_off + (long long)qb * DQ_BR - window + 1 - a.k_off;   // first visible key index
-    if (lo >= a.Nc) Nc = 0;                        // nothing visible: contribution 0
+    if (lo >= a.Nc) nothing = true;                // nothing visible: contribution 0
     else if (lo > 0) {
       const int skip = (int)(lo / DQ_BC) * DQ_BC;
-      Kh += (size_t)skip * 128; Vh += (size_t)skip * 128;
-      Nc -= skip; k_off += skip;
+      if constexpr (SPARSE) {
+        t_lo = skip / DQ_BC;
+      } else {
+        Kh += (size_t)skip * 128; Vh += (size_t)skip * 128;
+        Nc -= skip; k_off += skip;
+      }
     }
   }
-  int ntiles = (Nc + DQ_BC - 1) / DQ_BC;
+  int ntiles = nothing ? 0 : (Nc + DQ_BC - 1) / DQ_BC;
   if (a.causal) {
     long long lim = a.q_off + min(qb * DQ_BR + DQ_BR, a.Nq) - 1 - k_off;
     long long t = lim < 0 ? 0 : lim / DQ_BC + 1;
     if (t < ntiles) ntiles = (int)t;
   }
+  // SPARSE: the list of visible tiles, built by wavefront 0 (64 candidate tiles per round).
+  // list[0] = number of entries, list[1 + j] = tile | (wavefront bits << 20), then 6 end entries.
+  int* const list = reinterpret_cast<int*>(smem + DQ_LDS_BYTES);
+  if constexpr (SPARSE) {
+    const int end_tile = (Nc + DQ_BC - 1) / DQ_BC;               // a tile past the chunk
+    if (w == 0) {
+      int n = 0;
+      for (int base = t_lo; base < ntiles; base += 64) {
+        const int kt = base + lane;
+        int bits = 0;
+        if (kt < ntiles) {
+          const int col = (kt * DQ_BC) / a.bsize;
+#pragma unroll
+          for (int ww = 0; ww < 4; ww++) {
+            const int row0 = qb * DQ_BR + ww * 64;
+            if (row0 < a.Nq && a.bmask[(size_t)(row0 / a.bsize) * a.bpitch + col] != 0) bits |= 1 << ww;
+          }
+        }
+        const unsigned long long bal = __builtin_amdgcn_ballot_w64(bits != 0);
+        if (bits != 0) {
+          const int pos = n + __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0u));
+          list[1 + pos] = kt | (bits << 20);
+        }
+        n += __builtin_popcountll(bal);
+      }
+      if (lane < 6) list[1 + n + lane] = end_tile;
+      if (lane == 0) list[0] = n;
+    }
+    __syncthreads();
+    ntiles = __builtin_amdgcn_readfirstlane(list[0]);            // from here on: number of list entries
+  }
+  auto tile_at = [&](int j) __attribute__((always_inline)) {      // tile index of list entry j
+    if constexpr (SPARSE) return __builtin_amdgcn_readfirstlane(list[1 + j]) & 0xfffff;
+    else return j;
+  };
 
   f32x16 dq[2][4];         // dQ^T accumulators [row block][32-wide d block], pinned in AGPRs
 #pragma unroll
@@ -164,12 +213,14 @@ burst_bwd_dq_kernel(BwdArgs a) {
     };
     constexpr int VBASE = DQ_KSLOTS * DQ_TILE_BYTES;
 #pragma unroll
-    for (int t = 0; t < 3; t++)
+    for (int t = 0; t < 3; t++) {
+      const int src = tile_at(t);
 #pragma unroll
       for (int il = 0; il < 2; il++) {
-        dma_tile(krs, lds0 + t * DQ_TILE_BYTES, il, t);
-        dma_tile(vrs, lds0 + VBASE + t * DQ_TILE_BYTES, il, t);
+        dma_tile(krs, lds0 + t * DQ_TILE_BYTES, il, src);
+        dma_tile(vrs, lds0 + VBASE + t * DQ_TILE_BYTES, il, src);
       }
+    }
     {
       // the slot of "tile -1" feeds the first, all-zero dQ^T products: clear it
       const i32x4 z = {0, 0, 0, 0};
@@ -215,7 +266,16 @@ burst_bwd_dq_kernel(BwdArgs a) {
     // One step = tile kt: S^T(kt), then dP^T(kt) with the exponentials riding along, then the
     // dQ^T products of tile kt - 1 (whose dS^T fragments `dsp` were finished one step ago) with the
     // dS of tile kt riding along into `dsc`.  kslot / vslot: ring slots of tile kt.
-    auto step = [&](const bf16x8 (&dsp)[2][2], bf16x8 (&dsc)[2][2], int kt, int kslot, int vslot) __attribute__((always_inline)) {
+    // jt = position of the tile in the walk (dense: jt = kt).
+    auto step = [&](const bf16x8 (&dsp)[2][2], bf16x8 (&dsc)[2][2], int jt, int kslot, int vslot) __attribute__((always_inline)) {
+      int kt = jt, kt3 = jt + 3;                   // this tile, and the tile whose K / V are fetched now
+      bool mine = true;                            // SPARSE: this wavefront's rows can see the tile
+      if constexpr (SPARSE) {
+        const int e = __builtin_amdgcn_readfirstlane(list[1 + jt]);
+        kt = e & 0xfffff;
+        mine = ((e >> (20 + wu)) & 1) != 0;
+        kt3 = tile_at(jt + 3);
+      }
       const char* kl = smem + kslot * DQ_TILE_BYTES;
       const int kprev = (kslot == 0) ? DQ_KSLOTS - 1 : kslot - 1;
       const int knext = (kslot == DQ_KSLOTS - 1) ? 0 : kslot + 1;
@@ -242,7 +302,7 @@ burst_bwd_dq_kernel(BwdArgs a) {
       const long long tile_first_k = k_off + (long long)kt * DQ_BC;
       const bool need_mask = (a.causal && tile_first_k + DQ_BC - 1 > wave_first_q) ||
                              (window > 0 && tile_first_k < wave_first_q + 63 - window + 1) ||
-                             ((kt + 1) * DQ_BC > Nc);
+                             ((kt + 1) * DQ_BC > Nc) || !mine;
       if (need_mask) {
 #pragma unroll
         for (int rb = 0; rb < 2; rb++) {
@@ -256,6 +316,7 @@ burst_bwd_dq_kernel(BwdArgs a) {
           const int tail = Nc - 1 - (kt * DQ_BC + 4 * mh);
           int lim = a.causal ? (int)(dd < -1 ? -1 : (dd > 64 ? 64 : dd)) : 64;
           lim = lim < tail ? lim : tail;
+          if (!mine) lim = -1;
           const long long dl = dd - window + 1;
           const int lim_lo = window > 0 ? (int)(dl < -1 ? -1 : (dl > 64 ? 64 : dl)) : -1;
 #pragma unroll
@@ -306,8 +367,8 @@ burst_bwd_dq_kernel(BwdArgs a) {
         dsc[prb][kg][t] = pk[0]; dsc[prb][kg][t + 1] = pk[1];
         if ((i & 3) == 1) {
           const int j = i >> 2;                    // 0, 1 -> K of tile kt + 3; 2, 3 -> V of tile kt + 3
-          if (j < 2) dma_tile(krs, k_dst, j, kt + 3);
-          else dma_tile(vrs, v_dst, j - 2, kt + 3);
+          if (j < 2) dma_tile(krs, k_dst, j, kt3);
+          else dma_tile(vrs, v_dst, j - 2, kt3);
         }
         if (i == 14) kfq[0] = lds_read_b128(kl_next, abase);
         if (i == 15) kfq[1] = lds_read_b128(kl_next, abase ^ (1 << 5));
@@ -377,16 +438,22 @@ int launch_bwd_dq_mfma(const KParams& p, const void* Q, const void* K, const voi
   if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    if (hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             DQ_LDS_BYTES) != hipSuccess ||
-        hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            DQ_LDS_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
+        hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            DQ_LDS_BYTES) != hipSuccess ||
+        hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            DQ_LDS_BYTES + DQ_LIST_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
     attr_set = true;
   }
-  if (a.window > 0)
-    hipLaunchKernelGGL(burst_bwd_dq_kernel<true>, dim3((unsigned)nb), dim3(256), DQ_LDS_BYTES, stream, a);
-  else
-    hipLaunchKernelGGL(burst_bwd_dq_kernel<false>, dim3((unsigned)nb), dim3(256), DQ_LDS_BYTES, stream, a);
+  if (a.bmask != nullptr) {
+    if ((p.Nc + DQ_BC - 1) / DQ_BC > DQ_MAX_LIST) return BURST_ERR_SHAPE;
+    hipLaunchKernelGGL(burst_bwd_dq_kernel<2>, dim3((unsigned)nb), dim3(256), DQ_LDS_BYTES + DQ_LIST_BYTES, stream, a);
+  } else if (a.window > 0) {
+    hipLaunchKernelGGL(burst_bwd_dq_kernel<1>, dim3((unsigned)nb), dim3(256), DQ_LDS_BYTES, stream, a);
+  } else {
+    hipLaunchKernelGGL(burst_bwd_dq_kernel<0>, dim3((unsigned)nb), dim3(256), DQ_LDS_BYTES, stream, a);
+  }
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 

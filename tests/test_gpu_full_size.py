@@ -51,16 +51,18 @@ def check_complete_head(w, inp, h, O, lse, dQ, dKs, dVs):
     check(f"dV[h{h}]", np.concatenate([f64(x[0, h]) for x in dVs]), dV_ref, w.dtype)
 
 
-def check_sampled_rows(w, inp, h, O, lse, dQ, n_rows=64, seed=0):
+def check_sampled_rows(w, inp, h, O, lse, dQ, n_rows=64, seed=0, pattern=None):
     Q, K, V, dO = head_arrays(inp, h)
     rows = np.sort(np.random.default_rng(seed + h).choice(w.Nq, size=n_rows, replace=False))
     rows[0], rows[-1] = 0, w.Nq - 1                      # always include the first and last row
     qp, kp = w.q_off + rows, np.arange(K.shape[0])
-    O_ref, lse_ref = orc.full_forward(Q[rows], K, V, w.scale, w.causal, qp, kp, window=w.window)
+    pat = None if pattern is None else pattern[rows]
+    O_ref, lse_ref = orc.full_forward(Q[rows], K, V, w.scale, w.causal, qp, kp, window=w.window, pattern=pat)
     check(f"O[h{h},rows]", f64(O[0, h])[rows], O_ref, w.dtype)
     check(f"lse[h{h},rows]", f64(lse[0, h])[rows], lse_ref, w.dtype, "lse")
     if dQ is not None:
-        dQ_ref, _, _ = orc.full_backward(Q[rows], K, V, dO[rows], w.scale, w.causal, qp, kp, window=w.window)
+        dQ_ref, _, _ = orc.full_backward(Q[rows], K, V, dO[rows], w.scale, w.causal, qp, kp, window=w.window,
+                                         pattern=pat)
         check(f"dQ[h{h},rows]", f64(dQ[0, h])[rows], dQ_ref, w.dtype)
 
 
@@ -147,3 +149,44 @@ def test_llama7b_32k_G8_with_scores_stored_in_hbm():
     torch.cuda.synchronize()
     for h in (0, 13, w.H - 1):
         check_sampled_rows(w, inp, h, O, lse, None)
+
+
+def test_llama7b_32k_G8_block_sparse_band_plus_global():
+    """Block flags (Sec. 2.6) at the benchmark's full size: a band of 128-wide blocks around the
+    diagonal of rank 3's slice plus global first blocks, one flag matrix per chunk.  Lists of
+    visible tiles are longer than one round of the list builder for every kernel.  One complete
+    head (all five outputs) and sampled rows of others against the oracle."""
+    w = workloads.by_name("llama7b_32k_G8")
+    inp = workloads.make_inputs(w, DEV)
+    k_offs = [w.k_off(j) for j in range(w.G)]
+    block, q_off = 128, 3 * w.Nq
+    nrb, ncb = w.Nq // block, w.Nc // block
+    flags = [workloads.block_flags(nrb, ncb, "band_global", seed=7 + j, diag_shift=(q_off - k_offs[j]) // block)
+             for j in range(w.G)]
+    flags[5] |= workloads.block_flags(nrb, ncb, "random", density=0.2, seed=99)     # one chunk with scattered blocks
+    flags[6][0, 1:] = 0                                                             # only the global column block left
+    flags[7][:] = 0                                                                 # a chunk nobody sees
+    masks = [torch.from_numpy(f).to(DEV).contiguous() for f in flags]
+    walk = RingWalk(inp["Q"], w.scale, False, q_off, 0, block)
+    O, lse = walk.forward(inp["K"], inp["V"], k_offs, masks=masks)
+    dQ, dKs, dVs = walk.backward(inp["K"], inp["V"], k_offs, inp["dO"], masks=masks)
+    torch.cuda.synchronize()
+    pattern = np.concatenate([orc.block_visibility(w.Nq, w.Nc, f, block) for f in flags], axis=1)
+    h = 11
+    Q, K, V, dO = head_arrays(inp, h)
+    qp, kp = q_off + np.arange(w.Nq), np.arange(K.shape[0])
+    O_ref, lse_ref = orc.full_forward(Q, K, V, w.scale, False, qp, kp, pattern=pattern)
+    dQ_ref, dK_ref, dV_ref = orc.full_backward(Q, K, V, dO, w.scale, False, qp, kp, pattern=pattern)
+    check("O", f64(O[0, h]), O_ref, w.dtype)
+    check("lse", f64(lse[0, h]), lse_ref, w.dtype, "lse")
+    check("dQ", f64(dQ[0, h]), dQ_ref, w.dtype)
+    check("dK", np.concatenate([f64(x[0, h]) for x in dKs]), dK_ref, w.dtype)
+    check("dV", np.concatenate([f64(x[0, h]) for x in dVs]), dV_ref, w.dtype)
+    for h in (0, 31):
+        check_sampled_rows(w, inp, h, O, lse, dQ, pattern=pattern)
+    # key blocks no row block sees get exactly zero gradients
+    for j in (6, 7):
+        hidden = np.repeat(flags[j].sum(axis=0) == 0, block)
+        assert hidden.any()
+        assert torch.count_nonzero(dKs[j][0, :, torch.from_numpy(hidden).to(DEV)]) == 0
+        assert torch.count_nonzero(dVs[j][0, :, torch.from_numpy(hidden).to(DEV)]) == 0
