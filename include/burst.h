@@ -14,7 +14,8 @@
  *     only enqueues kernels on `stream` (a hipStream_t passed as void*, NULL =
  *     the default stream).  Pointers must be 16-byte aligned.
  *   - Tensors are dense, row-major [B, H, rows, d] (d contiguous); per-row
- *     vectors (m, l, lse, D) are [B, H, rows].
+ *     vectors (m, l, lse, D) are [B, H, rows].  K, V, dK, dV may have fewer heads
+ *     than Q (burst_params.kv_heads; not in the paper).
  *   - Q, K, V, O, dO have element type `dtype` (bf16 or fp32).  The running
  *     state, lse, D and all gradients are fp32.
  *   - Scores are S = scale * Q K^T (Eq. 1 has scale = 1/sqrt(d); Alg. 1/2 omit
@@ -78,7 +79,9 @@ typedef struct burst_params {
                               * keys j*block .. of the chunk from query rows i*block .. of the slice */
   int32_t block;    /* edge of a mask block in rows = keys; a positive multiple of 64 when
                      * block_mask != NULL, ignored otherwise */
-  int32_t reserved; /* must be 0 */
+  int32_t kv_heads; /* 0 or H: K, V, dK, dV have H heads.  Otherwise (grouped-query attention) they
+                     * have kv_heads heads, [B, kv_heads, Nc, d]; H must be a multiple of kv_heads and
+                     * query head h uses key/value head h / (H / kv_heads); dK, dV sum over the group */
 } burst_params;
 
 /* Alg. 1, initialisation: O_acc = 0, l = 0, m = -inf.

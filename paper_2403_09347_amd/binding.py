@@ -28,7 +28,7 @@ class BurstParams(ctypes.Structure):
         ("d", ctypes.c_int32), ("dtype", ctypes.c_int32), ("causal", ctypes.c_int32),
         ("scale", ctypes.c_float), ("q_off", ctypes.c_int64), ("k_off", ctypes.c_int64),
         ("window", ctypes.c_int64), ("block_mask", ctypes.c_void_p), ("block", ctypes.c_int32),
-        ("reserved", ctypes.c_int32),
+        ("kv_heads", ctypes.c_int32),
     ]
 
 
@@ -87,7 +87,8 @@ def version():
     return load().burst_version()
 
 
-def params(B, H, Nq, Nc, d, dtype, scale, causal=False, q_off=0, k_off=0, window=0, block_mask=None, block=0):
+def params(B, H, Nq, Nc, d, dtype, scale, causal=False, q_off=0, k_off=0, window=0, block_mask=None, block=0,
+           kv_heads=0):
     """block_mask: a contiguous uint8 device tensor [ceil(Nq/block), ceil(Nc/block)] (or None); the
     caller keeps it alive and unchanged until the kernels that use these parameters have run."""
     code = {torch.bfloat16: BURST_BF16, torch.float32: BURST_F32, "bf16": BURST_BF16, "f32": BURST_F32}.get(dtype, dtype)
@@ -99,7 +100,7 @@ def params(B, H, Nq, Nc, d, dtype, scale, causal=False, q_off=0, k_off=0, window
             raise ValueError("block_mask: shape must be [ceil(Nq/block), ceil(Nc/block)]")
         ptr = block_mask.data_ptr()
     return BurstParams(B, H, Nq, Nc, d, code, 1 if causal else 0, scale, q_off, k_off, window, ptr,
-                       block if block_mask is not None else 0, 0)
+                       block if block_mask is not None else 0, kv_heads)
 
 
 def _ptr(t):

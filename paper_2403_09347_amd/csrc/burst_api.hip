@@ -62,7 +62,11 @@ int check_params(const burst_params* p, KParams* k) {
   k->causal = p->causal != 0; k->scale = p->scale; k->q_off = p->q_off; k->k_off = p->k_off;
   if (p->window < 0) return BURST_ERR_SHAPE;
   k->window = p->window;
-  if (p->reserved != 0) return BURST_ERR_SHAPE;
+  k->group = 1;
+  if (p->kv_heads != 0) {
+    if (p->kv_heads < 0 || p->H % p->kv_heads != 0) return BURST_ERR_SHAPE;
+    k->group = p->H / p->kv_heads;
+  }
   k->bmask = nullptr; k->bsize = 64; k->bpitch = 0;
   if (p->block_mask != nullptr) {
     if (p->block <= 0 || p->block % 64 != 0) return BURST_ERR_SHAPE;
@@ -85,6 +89,13 @@ constexpr int kMaxMfmaRows = 4 * 1024 * 1024;
 constexpr int kMaxMaskedRows = 8192 * 64;
 bool use_mfma(const burst_params* p) {
   return p->dtype == BURST_BF16 && p->d == 128 && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows;
+}
+// The dK/dV MFMA kernel walks the query tiles of all heads of a group as one list: whole 64-row
+// tiles per head and at most 8192 tiles in all; other grouped shapes take the generic kernel.
+bool dkv_mfma_ok(const burst_params* p, const KParams& k) {
+  if (k.group > 1) return p->Nq % 64 == 0 && (long long)k.group * (p->Nq / 64) <= 8192 &&
+                          (long long)k.group * p->Nq <= kMaxMfmaRows;
+  return p->block_mask == nullptr || p->Nq <= kMaxMaskedRows;
 }
 
 int get_d_scratch(size_t elems, float** out) {
@@ -218,8 +229,8 @@ static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const v
     if (want_dq && have_q && !accumulate_dq &&
         (st = burst::launch_zero_fill(dQ, bh * k.Nq * k.d, s)) != BURST_OK) return st;
     if (want_dkv && have_k && !accumulate_dkv) {
-      if ((st = burst::launch_zero_fill(dK_chunk, bh * k.Nc * k.d, s)) != BURST_OK) return st;
-      if ((st = burst::launch_zero_fill(dV_chunk, bh * k.Nc * k.d, s)) != BURST_OK) return st;
+      if ((st = burst::launch_zero_fill(dK_chunk, bh / k.group * k.Nc * k.d, s)) != BURST_OK) return st;
+      if ((st = burst::launch_zero_fill(dV_chunk, bh / k.group * k.Nc * k.d, s)) != BURST_OK) return st;
     }
     return BURST_OK;
   }
@@ -230,15 +241,16 @@ static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const v
     if ((st = burst::launch_bwd_prepare(k, p->dtype, O, dO, scratch, s)) != BURST_OK) return st;
     Duse = scratch;
   }
-  const bool mfma = use_mfma(p) && (p->block_mask == nullptr || (p->Nq <= kMaxMaskedRows && p->Nc <= kMaxMaskedRows));
+  const bool mfma_dq = use_mfma(p) && (p->block_mask == nullptr || p->Nc <= kMaxMaskedRows);
+  const bool mfma_dkv = use_mfma(p) && dkv_mfma_ok(p, k);
   if (want_dq) {
-    st = mfma ? burst::launch_bwd_dq_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)
+    st = mfma_dq ? burst::launch_bwd_dq_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)
               : burst::launch_bwd_dq_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dQ,
                                              accumulate_dq != 0, s);
     if (st != BURST_OK) return st;
   }
   if (want_dkv) {
-    st = mfma ? burst::launch_bwd_dkv_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk,
+    st = mfma_dkv ? burst::launch_bwd_dkv_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk,
                                            accumulate_dkv != 0, s)
               : burst::launch_bwd_dkv_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk,
                                               dV_chunk, accumulate_dkv != 0, s);

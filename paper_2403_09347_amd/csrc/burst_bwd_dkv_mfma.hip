@@ -36,7 +36,10 @@ constexpr int DKV_LDS_BYTES = DKV_LDS_DUMMY + 256;
 constexpr int DKV_MAX_LIST = 8192;    // block-sparse calls: most query tiles of one slice (512K rows)
 constexpr int DKV_LIST_BYTES = (DKV_MAX_LIST + 8) * 4;
 
-// SPARSE: the call carries block flags (paper Sec. 2.6).  The workgroup first writes the list of
+// SPARSE: the call carries block flags (paper Sec. 2.6) or several query heads share a key/value
+// head (a.group > 1: the tiles of all heads of the group are walked, `head` is then the key/value
+// head and Q, dO, lse, D of the group are addressed as one tensor of group * Nq rows, which needs
+// Nq to be a multiple of the tile).  The workgroup first writes the list of
 // query tiles that at least one of its wavefronts' keys are visible to (tile index plus one bit per
 // wavefront) into LDS and then walks that list instead of t_begin, t_begin + 1, ...; a wavefront
 // whose bit is clear hides the whole tile in the masking path.  Entries past the end name a tile
@@ -58,12 +61,14 @@ burst_bwd_dkv_kernel(BwdArgs a) {
   }
   const int key_wg = kblk * DKV_BC;
   const int key0 = key_wg + w * 32;                // first key of this wavefront
-  const bf16* Qh = a.Q + (size_t)head * a.Nq * 128;
-  const bf16* Gh = a.dO + (size_t)head * a.Nq * 128;
+  const int group = SPARSE ? a.group : 1;          // query heads that share this key/value head
+  const int q_rows = group * a.Nq;                 // rows of the group's Q / dO / lse / D
+  const bf16* Qh = a.Q + (size_t)head * q_rows * 128;
+  const bf16* Gh = a.dO + (size_t)head * q_rows * 128;
   const bf16* Kh = a.K + (size_t)head * a.Nc * 128;
   const bf16* Vh = a.V + (size_t)head * a.Nc * 128;
-  const float* lseh = a.lse + (size_t)head * a.Nq;
-  const float* Dh = a.D + (size_t)head * a.Nq;
+  const float* lseh = a.lse + (size_t)head * q_rows;
+  const float* Dh = a.D + (size_t)head * q_rows;
 
   // query tiles to visit: causal rows before the first key of the workgroup see none of it
   int ntiles_all = (a.Nq + DKV_BR - 1) / DKV_BR;
@@ -88,28 +93,34 @@ burst_bwd_dkv_kernel(BwdArgs a) {
   // SPARSE: the list of visible tiles, built by wavefront 0 (64 candidate tiles per round).
   // list[0] = number of entries, list[1 + j] = tile | (wavefront bits << 16), then 4 end entries.
   int* const list = reinterpret_cast<int*>(smem + DKV_LDS_BYTES);
+  const int tiles_per_head = (a.Nq + DKV_BR - 1) / DKV_BR;
   if constexpr (SPARSE) {
-    const int end_tile = (a.Nq + DKV_BR - 1) / DKV_BR;          // a tile past the slice
+    const int end_tile = (q_rows + DKV_BR - 1) / DKV_BR;        // a tile past the group's rows
     if (w == 0) {
       int n = 0;
-      for (int base = t_begin; base < ntiles_all; base += 64) {
-        const int t = base + lane;
-        int bits = 0;
-        if (t < ntiles_all) {
-          const uint8_t* mrow = a.bmask + (size_t)((t * DKV_BR) / a.bsize) * a.bpitch;
+      for (int g = 0; g < group; g++)
+        for (int base = t_begin; base < ntiles_all; base += 64) {
+          const int t = base + lane;
+          int bits = 0;
+          if (t < ntiles_all) {
+            if (a.bmask == nullptr) {
+              bits = 0xf;
+            } else {
+              const uint8_t* mrow = a.bmask + (size_t)((t * DKV_BR) / a.bsize) * a.bpitch;
 #pragma unroll
-          for (int ww = 0; ww < 4; ww++) {
-            const int k0 = key_wg + ww * 32;
-            if (k0 < a.Nc && mrow[k0 / a.bsize] != 0) bits |= 1 << ww;
+              for (int ww = 0; ww < 4; ww++) {
+                const int k0 = key_wg + ww * 32;
+                if (k0 < a.Nc && mrow[k0 / a.bsize] != 0) bits |= 1 << ww;
+              }
+            }
           }
+          const unsigned long long bal = __builtin_amdgcn_ballot_w64(bits != 0);
+          if (bits != 0) {
+            const int pos = n + __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0u));
+            list[1 + pos] = (g * tiles_per_head + t) | (bits << 16);
+          }
+          n += __builtin_popcountll(bal);
         }
-        const unsigned long long bal = __builtin_amdgcn_ballot_w64(bits != 0);
-        if (bits != 0) {
-          const int pos = n + __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0u));
-          list[1 + pos] = t | (bits << 16);
-        }
-        n += __builtin_popcountll(bal);
-      }
       if (lane < 4) list[1 + n + lane] = end_tile;
       if (lane == 0) list[0] = n;
     }
@@ -149,8 +160,8 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           taddr[db][sx] = tile_off(8 * sx + 4 * h + (j16 >> 2), db * 4 + 2 * dh + ((j16 & 3) >> 1)) + (j16 & 1) * 8;
     }
     // DMA: a 64-row tile is 16 wave-loads of 4 rows; wavefront w issues loads 4w .. 4w+3
-    const __amdgpu_buffer_rsrc_t qrs = make_rsrc(Qh, (unsigned)a.Nq * 256u);
-    const __amdgpu_buffer_rsrc_t grs = make_rsrc(Gh, (unsigned)a.Nq * 256u);
+    const __amdgpu_buffer_rsrc_t qrs = make_rsrc(Qh, (unsigned)q_rows * 256u);
+    const __amdgpu_buffer_rsrc_t grs = make_rsrc(Gh, (unsigned)q_rows * 256u);
     const int wu = __builtin_amdgcn_readfirstlane(w);
     const unsigned lds0 = lds_addr(smem);
     int goff[4];
@@ -171,8 +182,8 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     // per-element vector work.  (Multiplying K by c beforehand would also remove the multiply,
     // but rounds c K to bf16 again; with few visible keys per row P is then visibly off.)  No
     // compiler-visible global load is left in the loop: its wait would drain the DMA queue.
-    const __amdgpu_buffer_rsrc_t lrs = make_rsrc(lseh, (unsigned)a.Nq * 4u);
-    const __amdgpu_buffer_rsrc_t drs = make_rsrc(Dh, (unsigned)a.Nq * 4u);
+    const __amdgpu_buffer_rsrc_t lrs = make_rsrc(lseh, (unsigned)q_rows * 4u);
+    const __amdgpu_buffer_rsrc_t drs = make_rsrc(Dh, (unsigned)q_rows * 4u);
     auto dma_rowstat = [&](int t, int slot) __attribute__((always_inline)) {
       // every wavefront issues exactly one such load per tile (the wait counts below rely on
       // it): 0 -> lse, 1 -> D, 2 and 3 -> a dummy copy of lse that nobody reads
@@ -267,7 +278,8 @@ burst_bwd_dkv_kernel(BwdArgs a) {
       const float* dp_ = reinterpret_cast<const float*>(smem + DKV_LDS_D) + (n & 3) * DKV_BR;
       const float* lp_next = reinterpret_cast<const float*>(smem + DKV_LDS_L) + ((n + 1) & 3) * DKV_BR;
       const float* dp_next = reinterpret_cast<const float*>(smem + DKV_LDS_D) + ((n + 1) & 3) * DKV_BR;
-      const long long tile_first_q = a.q_off + (long long)t * DKV_BR;
+      // (t counts tiles over all heads of the group; the position restarts with every head)
+      const long long tile_first_q = a.q_off + (long long)((SPARSE && group > 1) ? t % tiles_per_head : t) * DKV_BR;
       // (no branch around the MFMA phases: the AGPR-pinned accumulators must not become phi
       // values, the allocator would shuttle them through VGPRs every iteration)
       const bool need_mask = (a.causal && wave_last_k > tile_first_q) ||
@@ -421,12 +433,14 @@ int launch_bwd_dkv_mfma(const KParams& p, const void* Q, const void* K, const vo
     attr_set = true;
   }
   BwdArgs a = make_bwd_args(p, Q, K, V, dO, lse, D, nullptr, dK, dV, 0, acc_dkv);
+  a.H = p.B * p.H / p.group;                       // workgroups are laid out over key/value heads
   int heads8 = ((a.H + 7) / 8) * 8;
   a.blocks_per_head = (p.Nc + DKV_BC - 1) / DKV_BC;
   long long nb = (long long)heads8 * a.blocks_per_head;
   if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;
-  if (a.bmask != nullptr) {
-    if ((p.Nq + DKV_BR - 1) / DKV_BR > DKV_MAX_LIST) return BURST_ERR_SHAPE;
+  if (a.bmask != nullptr || a.group > 1) {
+    if ((long long)a.group * ((p.Nq + DKV_BR - 1) / DKV_BR) > DKV_MAX_LIST) return BURST_ERR_SHAPE;
+    if (a.group > 1 && p.Nq % DKV_BR != 0) return BURST_ERR_SHAPE;
     hipLaunchKernelGGL(burst_bwd_dkv_kernel<true>, dim3((unsigned)nb), dim3(256), DKV_LDS_BYTES + DKV_LIST_BYTES, stream, a);
   } else {
     hipLaunchKernelGGL(burst_bwd_dkv_kernel<false>, dim3((unsigned)nb), dim3(256), DKV_LDS_BYTES, stream, a);

@@ -83,8 +83,8 @@ burst_bwd_dq_kernel(BwdArgs a) {
   const int q0 = qb * DQ_BR + w * 64;
   const bf16* Qh = a.Q + (size_t)head * a.Nq * 128;
   const bf16* Gh = a.dO + (size_t)head * a.Nq * 128;
-  const bf16* Kh = a.K + (size_t)head * a.Nc * 128;
-  const bf16* Vh = a.V + (size_t)head * a.Nc * 128;
+  const bf16* Kh = a.K + (size_t)(head / a.group) * a.Nc * 128;
+  const bf16* Vh = a.V + (size_t)(head / a.group) * a.Nc * 128;
   const float* lseh = a.lse + (size_t)head * a.Nq;
   const float* Dh = a.D + (size_t)head * a.Nq;
   float* dQh = a.dQ + (size_t)head * a.Nq * 128;

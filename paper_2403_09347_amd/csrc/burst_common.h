@@ -28,6 +28,7 @@ struct KParams {
   long long window;      // 0 = none
   const uint8_t* bmask;  // block mask [ceil(Nq/bsize)][bpitch] (nullptr = none), bpitch = ceil(Nc/bsize)
   int bsize, bpitch;
+  int group;             // query heads per key/value head (1 = every head has its own K, V)
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

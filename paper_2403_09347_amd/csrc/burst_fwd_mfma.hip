@@ -39,6 +39,7 @@ struct FwdArgs {
   int q_blocks;          // ceil(Nq / FWD_BR)
   const uint8_t* bmask;  // block flags [ceil(Nq / bsize)][bpitch], nullptr = none (paper Sec. 2.6)
   int bsize, bpitch;     // bsize: a multiple of 64, so a wavefront's 64 rows and a key tile lie in one block
+  int group;             // query heads per key/value head (grouped-query attention; 1 = none)
 };
 
 // HBM -> LDS for one 64x128 bf16 tile (K or V) without staging registers.  One wave-wide
@@ -106,8 +107,8 @@ burst_fwd_mfma_kernel(FwdArgs a) {
 
   const int q0 = qb * FWD_BR + w * 64;             // first query row of this wave
   const bf16* Qh = a.Q + (size_t)head * a.Nq * 128;
-  const bf16* Kh = a.K + (size_t)head * a.Nc * 128;
-  const bf16* Vh = a.V + (size_t)head * a.Nc * 128;
+  const bf16* Kh = a.K + (size_t)(head / a.group) * a.Nc * 128;
+  const bf16* Vh = a.V + (size_t)(head / a.group) * a.Nc * 128;
 
   // Sliding window: key tiles before the first one that the workgroup's first row can see are
   // skipped by moving the start of the chunk (pointers, length, global offset) forward by whole
@@ -498,7 +499,7 @@ int launch_fwd_mfma(const KParams& p, const void* Q, const void* K, const void* 
   a.c = p.scale * kLog2e;
   a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
   a.q_blocks = (p.Nq + FWD_BR - 1) / FWD_BR;
-  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch;
+  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.group = p.group;
   int heads8 = ((a.H + 7) / 8) * 8;                // pad the head count to a multiple of 8 ids
   long long nblocks = (long long)heads8 * a.q_blocks;
   if (nblocks > 0x7fffffffLL) return BURST_ERR_SHAPE;

@@ -19,6 +19,7 @@ struct GenArgs {
   long long q_off, k_off;
   long long window;
   const uint8_t* bmask; int bsize, bpitch;        // block mask (nullptr = none)
+  int group;                                      // query heads per key/value head
   int acc_dq, acc_dkv;
 };
 
@@ -54,8 +55,8 @@ fwd_generic_kernel(GenArgs a) {
   if (!live) wave = 0;                             // keep every wavefront up to the barrier
   const int head = (int)(wave / a.Nq), row = (int)(wave % a.Nq);
   const T* Qr = (const T*)a.Q + ((size_t)head * a.Nq + row) * a.d;
-  const T* Kh = (const T*)a.K + (size_t)head * a.Nc * a.d;
-  const T* Vh = (const T*)a.V + (size_t)head * a.Nc * a.d;
+  const T* Kh = (const T*)a.K + (size_t)(head / a.group) * a.Nc * a.d;
+  const T* Vh = (const T*)a.V + (size_t)(head / a.group) * a.Nc * a.d;
   for (int t = lane; t < a.d; t += 64) qrow[w][t] = ld(Qr + t);
   __syncthreads();
   if (!live) return;
@@ -118,8 +119,8 @@ bwd_dq_generic_kernel(GenArgs a) {
   size_t r = (size_t)head * a.Nq + row;
   const T* Qr = (const T*)a.Q + r * a.d;
   const T* Gr = (const T*)a.dO + r * a.d;
-  const T* Kh = (const T*)a.K + (size_t)head * a.Nc * a.d;
-  const T* Vh = (const T*)a.V + (size_t)head * a.Nc * a.d;
+  const T* Kh = (const T*)a.K + (size_t)(head / a.group) * a.Nc * a.d;
+  const T* Vh = (const T*)a.V + (size_t)(head / a.group) * a.Nc * a.d;
   for (int t = lane; t < a.d; t += 64) { qrow[w][t] = ld(Qr + t); grow[w][t] = ld(Gr + t); }
   __syncthreads();
   if (!live) return;
@@ -163,22 +164,23 @@ bwd_dkv_generic_kernel(GenArgs a) {
   __shared__ float vrow[4][128];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   long long wave = (long long)blockIdx.x * 4 + w;
-  long long total = (long long)a.BH * a.Nc;
+  long long total = (long long)(a.BH / a.group) * a.Nc;      // one wavefront per key row of a key/value head
   const bool live = wave < total;
   if (!live) wave = 0;
-  const int head = (int)(wave / a.Nc), key = (int)(wave % a.Nc);
-  size_t kr_i = (size_t)head * a.Nc + key;
+  const int kvhead = (int)(wave / a.Nc), key = (int)(wave % a.Nc);
+  size_t kr_i = (size_t)kvhead * a.Nc + key;
   const T* Kr = (const T*)a.K + kr_i * a.d;
   const T* Vr = (const T*)a.V + kr_i * a.d;
+  for (int t = lane; t < a.d; t += 64) { krow[w][t] = ld(Kr + t); vrow[w][t] = ld(Vr + t); }
+  __syncthreads();
+  if (!live) return;
+  float k0a = 0.f, k1a = 0.f, v0a = 0.f, v1a = 0.f;
+  for (int g = 0; g < a.group; g++) {                        // the query heads that share this key/value head
+  const int head = kvhead * a.group + g;
   const T* Qh = (const T*)a.Q + (size_t)head * a.Nq * a.d;
   const T* Gh = (const T*)a.dO + (size_t)head * a.Nq * a.d;
   const float* lseh = a.lse + (size_t)head * a.Nq;
   const float* Dh = a.D + (size_t)head * a.Nq;
-  for (int t = lane; t < a.d; t += 64) { krow[w][t] = ld(Kr + t); vrow[w][t] = ld(Vr + t); }
-  __syncthreads();
-  if (!live) return;
-  const long long kpos = a.k_off + key;
-  float k0a = 0.f, k1a = 0.f, v0a = 0.f, v1a = 0.f;
   for (int r0 = 0; r0 < a.Nq; r0 += 64) {
     int row = r0 + lane;
     float p = 0.f, ds = 0.f;
@@ -205,6 +207,7 @@ bwd_dkv_generic_kernel(GenArgs a) {
       if (lane + 64 < a.d) { v1a = __builtin_fmaf(pj, ld(gr + lane + 64), v1a); k1a = __builtin_fmaf(dsj, ld(qr + lane + 64), k1a); }
     }
   }
+  }
   float* dk = a.dK + kr_i * a.d;
   float* dv = a.dV + kr_i * a.d;
   if (lane < a.d) {
@@ -221,7 +224,7 @@ static GenArgs make_args(const KParams& p) {
   GenArgs a = {};
   a.Nq = p.Nq; a.Nc = p.Nc; a.d = p.d; a.BH = p.B * p.H;
   a.causal = p.causal; a.scale = p.scale; a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
-  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch;
+  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.group = p.group;
   return a;
 }
 static inline int launch_status() { return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH; }
@@ -257,7 +260,7 @@ int launch_bwd_dkv_generic(const KParams& p, int dtype, const void* Q, const voi
                            int acc_dkv, hipStream_t s) {
   GenArgs a = make_args(p);
   a.Q = Q; a.K = K; a.V = V; a.dO = dO; a.lse = lse; a.D = D; a.dK = dK; a.dV = dV; a.acc_dkv = acc_dkv;
-  long long wk = (long long)p.B * p.H * p.Nc;
+  long long wk = (long long)p.B * p.H / p.group * p.Nc;
   if (wk == 0) return BURST_OK;
   if ((wk + 3) / 4 > 0x7fffffffLL) return BURST_ERR_SHAPE;
   unsigned blocks = (unsigned)((wk + 3) / 4);

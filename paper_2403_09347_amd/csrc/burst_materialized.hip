@@ -22,6 +22,7 @@ struct MatArgs {
   float scale;
   long long q_off, k_off, window;
   const uint8_t* bmask; int bsize, bpitch;   // block mask (nullptr = none)
+  int group;                                 // query heads per key/value head
 };
 
 // ---- step 1, bf16, d = 128: one wavefront = a 32 x 32 block of S (8 MFMAs over d)
@@ -33,7 +34,7 @@ mat_scores_mfma_kernel(MatArgs a) {
   const int k0 = (blockIdx.x * 4 + w) * 32;
   if (k0 >= a.Ncp) return;
   const bf16* Qh = (const bf16*)a.Q + (size_t)head * a.Nq * 128;
-  const bf16* Kh = (const bf16*)a.K + (size_t)head * a.Nc * 128;
+  const bf16* Kh = (const bf16*)a.K + (size_t)(head / a.group) * a.Nc * 128;
   const int qrow = q0 + lr, krow = k0 + lr;
   f32x16 acc;
 #pragma unroll
@@ -71,7 +72,7 @@ mat_scores_generic_kernel(MatArgs a) {
     float s = 0.f;
     if (c < a.Nc) {
       const T* q = (const T*)a.Q + ((size_t)head * a.Nq + r) * a.d;
-      const T* k = (const T*)a.K + ((size_t)head * a.Nc + c) * a.d;
+      const T* k = (const T*)a.K + ((size_t)(head / a.group) * a.Nc + c) * a.d;
       for (int t = 0; t < a.d; t++) s = __builtin_fmaf((float)q[t], (float)k[t], s);
     }
     a.S[idx] = s * a.scale;
@@ -135,7 +136,7 @@ mat_pv_merge_mfma_kernel(MatArgs a) {
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, lr = lane & 31, h = lane >> 5;
   const int head = blockIdx.y;
   const int q0 = blockIdx.x * 128 + w * 32;
-  const bf16* Vh = (const bf16*)a.V + (size_t)head * a.Nc * 128;
+  const bf16* Vh = (const bf16*)a.V + (size_t)(head / a.group) * a.Nc * 128;
   const bf16* Ph = (const bf16*)a.P + (size_t)head * a.Nq * a.Ncp;
   const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, (unsigned)a.Nc * 256u);
   const int ntiles = (a.Nc + 31) / 32;
@@ -251,7 +252,7 @@ mat_pv_merge_generic_kernel(MatArgs a) {
     const float m_ij = a.m_c[srow];
     if (m_ij == BURST_NEG_INF) continue;
     const T* p = (const T*)a.P + (size_t)srow * a.Ncp;
-    const T* v = (const T*)a.V + (size_t)head * a.Nc * a.d + col;
+    const T* v = (const T*)a.V + (size_t)(head / a.group) * a.Nc * a.d + col;
     float acc = 0.f;
     for (int c = 0; c < a.Nc; c++) acc = __builtin_fmaf((float)p[c], (float)v[(size_t)c * a.d], acc);
     const float m_old = a.m[srow];
@@ -293,7 +294,7 @@ int launch_fwd_materialized(const KParams& p, int dtype, bool mfma, const void* 
   a.Q = Q; a.K = K; a.V = V; a.O_acc = O_acc; a.m = m; a.l = l;
   a.Nq = p.Nq; a.Nc = p.Nc; a.Ncp = (p.Nc + 7) & ~7; a.d = p.d; a.BH = (long long)p.B * p.H;
   a.causal = p.causal; a.scale = p.scale; a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
-  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch;
+  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.group = p.group;
   const size_t rows = (size_t)a.BH * a.Nq;
   const size_t esize = dtype == BURST_BF16 ? 2 : 4;
   char* ws = (char*)workspace;

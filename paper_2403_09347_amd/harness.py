@@ -12,9 +12,10 @@ from . import binding as B
 class RingWalk:
     """Buffers and call sequence for one query slice against a list of chunks."""
 
-    def __init__(self, Q, scale, causal=False, q_off=0, window=0, block=0):
+    def __init__(self, Q, scale, causal=False, q_off=0, window=0, block=0, kv_heads=0):
         assert Q.dim() == 4
         self.Q = Q
+        self.kv_heads = int(kv_heads)    # heads of K / V when fewer than Q's (0 = the same)
         self.block = int(block)          # edge of the blocks of per-chunk block masks (0 = no masks)
         self.Bt, self.H, self.Nq, self.d = Q.shape
         self.scale, self.causal, self.q_off, self.window = float(scale), bool(causal), int(q_off), int(window)
@@ -28,7 +29,7 @@ class RingWalk:
 
     def params(self, Nc, k_off, mask=None):
         return B.params(self.Bt, self.H, self.Nq, Nc, self.d, self.Q.dtype, self.scale,
-                        self.causal, self.q_off, k_off, self.window, mask, self.block)
+                        self.causal, self.q_off, k_off, self.window, mask, self.block, self.kv_heads)
 
     # ---- forward (Alg. 1)
     def init(self):
@@ -73,8 +74,8 @@ class MaterializedWalk(RingWalk):
     """The forward walk with the chunk step that stores S_ij and P_ij in HBM (the paper's
     "w/o LAO" ablation): same state, same finalize, one workspace sized for the largest chunk."""
 
-    def __init__(self, Q, scale, causal=False, q_off=0, window=0, max_chunk_rows=0, block=0):
-        super().__init__(Q, scale, causal, q_off, window, block)
+    def __init__(self, Q, scale, causal=False, q_off=0, window=0, max_chunk_rows=0, block=0, kv_heads=0):
+        super().__init__(Q, scale, causal, q_off, window, block, kv_heads)
         self.workspace = None
         if max_chunk_rows:
             self._reserve(max_chunk_rows)

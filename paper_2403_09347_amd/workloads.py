@@ -141,16 +141,18 @@ def block_flags(n_row_blocks, n_col_blocks, kind="random", density=0.4, seed=0, 
 
 
 def make_case(B, H, d, Nq, chunk_rows, dtype="bf16", seed=0, device="cpu",
-              causal=False, q_off=0, k_offs=None, window=0, block=0, pattern="random", density=0.4):
+              causal=False, q_off=0, k_offs=None, window=0, block=0, pattern="random", density=0.4, kv_heads=0):
     """Free-form case for parity tests: `chunk_rows` lists the rows of each chunk.  With
     block > 0 the case carries one block-flag matrix per chunk ("flags": numpy, "masks": the
-    same on the device), blocks counted from the first row of the slice / of each chunk."""
+    same on the device), blocks counted from the first row of the slice / of each chunk.  With
+    kv_heads > 0 the K / V chunks have that many heads (grouped-query attention)."""
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)
     dt = torch.bfloat16 if dtype == "bf16" else torch.float32
     Q = _randn((B, H, Nq, d), gen, device, dt)
-    K = [_randn((B, H, n, d), gen, device, dt) for n in chunk_rows]
-    V = [_randn((B, H, n, d), gen, device, dt) for n in chunk_rows]
+    Hkv = kv_heads or H
+    K = [_randn((B, Hkv, n, d), gen, device, dt) for n in chunk_rows]
+    V = [_randn((B, Hkv, n, d), gen, device, dt) for n in chunk_rows]
     dO = _randn((B, H, Nq, d), gen, device, dt)
     if k_offs is None:
         k_offs, s = [], 0
@@ -159,6 +161,8 @@ def make_case(B, H, d, Nq, chunk_rows, dtype="bf16", seed=0, device="cpu",
             s += n
     case = {"Q": Q, "K": K, "V": V, "dO": dO, "k_offs": list(k_offs),
             "q_off": q_off, "causal": causal, "window": window, "scale": 1.0 / math.sqrt(d)}
+    if kv_heads:
+        case["kv_heads"] = kv_heads
     if block:
         nrb = -(-Nq // block)
         case["block"] = block

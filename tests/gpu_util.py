@@ -24,10 +24,12 @@ def positions(case):
 
 
 def head_inputs(case, b, h, rows=None):
+    """Inputs of query head h; with fewer key/value heads it uses key/value head h // group."""
     Q, dO = f64(case["Q"][b, h]), f64(case["dO"][b, h])
     d = Q.shape[1]
-    K = np.concatenate([f64(k[b, h]) for k in case["K"]]) if case["K"] else np.zeros((0, d))
-    V = np.concatenate([f64(v[b, h]) for v in case["V"]]) if case["V"] else np.zeros((0, d))
+    hk = h // (case["Q"].shape[1] // case["kv_heads"]) if case.get("kv_heads") else h
+    K = np.concatenate([f64(k[b, hk]) for k in case["K"]]) if case["K"] else np.zeros((0, d))
+    V = np.concatenate([f64(v[b, hk]) for v in case["V"]]) if case["V"] else np.zeros((0, d))
     qp = case["q_off"] + np.arange(Q.shape[0])
     if rows is not None:
         Q, dO, qp = Q[rows], dO[rows], qp[rows]
@@ -67,7 +69,9 @@ def check(name, got, ref, dtype, kind="abs"):
 
 def compare_all_heads(case, dtype, O, lse, dQ=None, dKs=None, dVs=None, heads=None):
     Bt, H = case["Q"].shape[:2]
+    group = H // case["kv_heads"] if case.get("kv_heads") else 1
     for b in range(Bt):
+        dK_sum = dV_sum = None                      # grouped heads: dK, dV of a key/value head sum over its group
         for h in (range(H) if heads is None else heads):
             Q, K, V, dO, qp, kp = head_inputs(case, b, h)
             pat = pattern_of(case)
@@ -80,7 +84,15 @@ def compare_all_heads(case, dtype, O, lse, dQ=None, dKs=None, dVs=None, heads=No
                                                            window=case.get("window", 0), pattern=pat)
                 check(f"dQ[{b},{h}]", f64(dQ[b, h]), dQ_ref, dtype)
                 d = Q.shape[1]
-                dK = np.concatenate([f64(x[b, h]) for x in dKs]) if dKs else np.zeros((0, d))
-                dV = np.concatenate([f64(x[b, h]) for x in dVs]) if dVs else np.zeros((0, d))
-                check(f"dK[{b},{h}]", dK, dK_ref, dtype)
-                check(f"dV[{b},{h}]", dV, dV_ref, dtype)
+                if group > 1:
+                    assert heads is None
+                    dK_sum = dK_ref if h % group == 0 else dK_sum + dK_ref
+                    dV_sum = dV_ref if h % group == 0 else dV_sum + dV_ref
+                    if h % group != group - 1:
+                        continue
+                    dK_ref, dV_ref = dK_sum, dV_sum
+                hk = h // group
+                dK = np.concatenate([f64(x[b, hk]) for x in dKs]) if dKs else np.zeros((0, d))
+                dV = np.concatenate([f64(x[b, hk]) for x in dVs]) if dVs else np.zeros((0, d))
+                check(f"dK[{b},{hk}]", dK, dK_ref, dtype)
+                check(f"dV[{b},{hk}]", dV, dV_ref, dtype)

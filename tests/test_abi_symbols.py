@@ -43,7 +43,7 @@ def test_binding_lists_the_same_exports():
     p = binding.params(1, 2, 3, 4, 128, "bf16", 0.5, True, 7, 9)
     assert (p.B, p.H, p.Nq, p.Nc, p.d, p.dtype, p.causal, p.q_off, p.k_off) == (1, 2, 3, 4, 128, 0, 1, 7, 9)
     assert ctypes.sizeof(p) == 72
-    assert (p.block_mask, p.block, p.reserved) == (None, 0, 0)
+    assert (p.block_mask, p.block, p.kv_heads) == (None, 0, 0)
 
 
 def test_argument_validation_without_gpu():
@@ -62,7 +62,7 @@ def test_argument_validation_without_gpu():
     bad = binding.params(1, 1, 16, 16, 128, "bf16", 0.5)
     bad.block_mask, bad.block = 4096, 48                        # block edge must be a multiple of 64
     assert lib.burst_local_fwd(null, null, null, null, null, null, ctypes.byref(bad), null) == -3
-    bad.block, bad.reserved = 64, 1                             # reserved must be 0
+    bad = binding.params(1, 6, 16, 16, 128, "bf16", 0.5, kv_heads=4)   # H must be a multiple of kv_heads
     assert lib.burst_local_fwd(null, null, null, null, null, null, ctypes.byref(bad), null) == -3
     ok = binding.params(1, 1, 16, 16, 128, "bf16", 0.5)
     assert lib.burst_state_init(null, null, null, ctypes.byref(ok), null) == -1      # NULL pointer

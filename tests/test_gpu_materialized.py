@@ -24,6 +24,8 @@ CASES = [
     ("f32", dict(B=1, H=1, d=128, Nq=40, chunk_rows=[70], causal=True, q_off=35, window=9)),
     ("bf16", dict(B=1, H=2, d=128, Nq=300, chunk_rows=[200, 140], block=64, pattern="random", density=0.5)),
     ("bf16", dict(B=1, H=1, d=128, Nq=260, chunk_rows=[260], block=128, pattern="band_global", causal=True)),
+    ("bf16", dict(B=1, H=4, kv_heads=2, d=128, Nq=200, chunk_rows=[150, 90], causal=True, q_off=100)),   # grouped heads
+    ("f32", dict(B=1, H=4, kv_heads=1, d=32, Nq=50, chunk_rows=[70])),
 ]
 
 
@@ -31,7 +33,7 @@ CASES = [
 def test_materialized_walk_against_the_oracle(dtype, spec):
     case = workloads.make_case(dtype=dtype, seed=61, device=DEV, **spec)
     walk = MaterializedWalk(case["Q"], case["scale"], case["causal"], case["q_off"], case.get("window", 0),
-                            block=case.get("block", 0))
+                            block=case.get("block", 0), kv_heads=case.get("kv_heads", 0))
     O, lse = walk.forward(case["K"], case["V"], case["k_offs"], masks=case.get("masks"))
     torch.cuda.synchronize()
     compare_all_heads(case, dtype, O, lse)

@@ -15,7 +15,7 @@ DEV = "cuda:0"
 
 def run_case(case, dtype, backward=True, use_D=True, order=None):
     walk = RingWalk(case["Q"], case["scale"], case["causal"], case["q_off"], case.get("window", 0),
-                    case.get("block", 0))
+                    case.get("block", 0), case.get("kv_heads", 0))
     masks = case.get("masks")
     O, lse = walk.forward(case["K"], case["V"], case["k_offs"], order=order, masks=masks)
     res = (O, lse, None, None, None)
@@ -84,6 +84,27 @@ def test_bf16_block_sparse_forward_backward(spec):
 def test_generic_kernels_block_sparse(dtype, spec):
     case = workloads.make_case(dtype=dtype, seed=37, device=DEV, **spec)
     _, (O, lse, dQ, dKs, dVs) = run_case(case, dtype)
+    compare_all_heads(case, dtype, O, lse, dQ, dKs, dVs)
+
+
+# Grouped-query attention (not in the paper): K, V, dK, dV with fewer heads than Q; dK, dV sum over the group.
+GQA_CASES = [
+    ("bf16", dict(B=1, H=4, kv_heads=2, d=128, Nq=256, chunk_rows=[200, 130])),               # dK/dV MFMA kernel: Nq % 64 == 0
+    ("bf16", dict(B=2, H=8, kv_heads=2, d=128, Nq=320, chunk_rows=[256, 100], causal=True, q_off=120)),
+    ("bf16", dict(B=1, H=6, kv_heads=1, d=128, Nq=384, chunk_rows=[300], causal=True, q_off=100, window=150)),
+    ("bf16", dict(B=1, H=4, kv_heads=2, d=128, Nq=300, chunk_rows=[260])),                    # ragged Nq: generic dK/dV kernel
+    ("bf16", dict(B=1, H=4, kv_heads=2, d=128, Nq=256, chunk_rows=[256, 192], block=64, pattern="random", density=0.5)),
+    ("f32", dict(B=1, H=4, kv_heads=2, d=32, Nq=90, chunk_rows=[70, 40], causal=True, q_off=30)),
+    # eight query heads per key/value head, several workgroups per head, a list of 256 query tiles per key block
+    ("bf16", dict(B=1, H=16, kv_heads=2, d=128, Nq=2048, chunk_rows=[1024, 1024], causal=True, q_off=1024)),
+]
+
+
+@pytest.mark.parametrize("dtype,spec", GQA_CASES, ids=lambda v: v if isinstance(v, str) else "-".join(f"{k}{x}" for k, x in v.items()))
+def test_grouped_query_heads(dtype, spec):
+    case = workloads.make_case(dtype=dtype, seed=53, device=DEV, **spec)
+    _, (O, lse, dQ, dKs, dVs) = run_case(case, dtype)
+    assert dKs[0].shape[1] == spec["kv_heads"]
     compare_all_heads(case, dtype, O, lse, dQ, dKs, dVs)
 
 
