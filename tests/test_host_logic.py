@@ -6,6 +6,7 @@ import subprocess
 import sys
 
 import numpy as np
+import pytest
 
 from paper_2403_09347_amd import workloads
 
@@ -76,3 +77,37 @@ def test_zigzag_assignment_balances_causal_work():
     spans = workloads.zigzag_spans(64, 4, 1)
     brute = sum(1 for first, rows in spans for q in range(first, first + rows) for k in range(64) if k <= q)
     assert workloads.causal_pairs(spans, 64) == brute
+
+
+def test_block_flag_generators_are_seeded_and_shaped():
+    a = workloads.block_flags(5, 9, "random", density=0.3, seed=4)
+    b = workloads.block_flags(5, 9, "random", density=0.3, seed=4)
+    assert a.shape == (5, 9) and a.dtype == np.uint8 and np.array_equal(a, b)
+    assert not np.array_equal(a, workloads.block_flags(5, 9, "random", density=0.3, seed=5))
+    assert workloads.block_flags(4, 4, "random", density=0.0).sum() == 0
+    band = workloads.block_flags(6, 6, "band")
+    assert all(band[i, j] == (abs(i - j) <= 1) for i in range(6) for j in range(6))
+    shifted = workloads.block_flags(3, 8, "band", diag_shift=4)         # the diagonal sits 4 blocks to the right
+    assert all(shifted[i, j] == (abs(j - 4 - i) <= 1) for i in range(3) for j in range(8))
+    bg = workloads.block_flags(5, 7, "band_global")
+    assert bg[:, 0].all() and bg[0].all() and bg[4, 2] == 0
+    with pytest.raises(ValueError):
+        workloads.block_flags(2, 2, "nope")
+
+
+def test_cases_with_block_flags_and_fewer_kv_heads():
+    case = workloads.make_case(B=1, H=4, d=16, Nq=100, chunk_rows=[70, 130], dtype="f32", seed=3,
+                               block=64, pattern="random", density=0.5, kv_heads=2)
+    assert case["K"][0].shape == (1, 2, 70, 16) and case["Q"].shape == (1, 4, 100, 16)
+    assert [f.shape for f in case["flags"]] == [(2, 2), (2, 3)]
+    assert all(np.array_equal(m.numpy(), f) for m, f in zip(case["masks"], case["flags"]))
+    again = workloads.make_case(B=1, H=4, d=16, Nq=100, chunk_rows=[70, 130], dtype="f32", seed=3,
+                                block=64, pattern="random", density=0.5, kv_heads=2)
+    assert all(np.array_equal(a, b) for a, b in zip(case["flags"], again["flags"]))
+
+
+def test_binding_rejects_host_masks_and_wrong_shapes():
+    import torch
+    from paper_2403_09347_amd import binding
+    with pytest.raises(ValueError):
+        binding.params(1, 1, 128, 128, 128, "bf16", 0.1, block_mask=torch.ones((2, 2), dtype=torch.uint8), block=64)
