@@ -73,6 +73,14 @@ WORKLOADS = [
 ]
 
 
+# Further shapes of the paper's experiments (not in the benchmark's list of configurations).
+EXTRA_WORKLOADS = [
+    # the single-device point of the latency-vs-devices experiment (Sec. 4, batch 1, 65,536 tokens,
+    # LLaMA-13B): with G = 1 there is one chunk and the method is plain tiled attention (Sec. 2.4)
+    Workload("llama13b_64k_G1", 1, 40, 128, 65536, 1, 65536, "bf16", False, 0, 1005),
+]
+
+
 def contiguous_spans(N, G, rank):
     """The paper's assignment (Sec. 2.2): rank r owns positions [r N/G, (r+1) N/G).
     Returns a list of (first position, rows)."""
@@ -98,7 +106,7 @@ def causal_pairs(spans, N):
 
 
 def by_name(name):
-    for w in WORKLOADS:
+    for w in WORKLOADS + EXTRA_WORKLOADS:
         if w.name == name:
             return w
     raise KeyError(name)

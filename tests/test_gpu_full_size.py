@@ -120,6 +120,16 @@ def test_llama7b_1m_G32_streaming_sampled_rows_and_identities():
     check_identities(w, inp, 0, dQ, dKs, dVs)
 
 
+def test_llama13b_64k_single_device_point():
+    """G = 1: one chunk of 65,536 keys, the single-device point of the paper's latency experiment;
+    the walk is then plain tiled attention (Sec. 2.4, last paragraph)."""
+    w = workloads.by_name("llama13b_64k_G1")
+    inp, k_offs, walk, O, lse, dQ, dKs, dVs = run_workload(w)
+    for h in (0, 21, 39):
+        check_sampled_rows(w, inp, h, O, lse, dQ, n_rows=32)
+    check_identities(w, inp, 17, dQ, dKs, dVs)
+
+
 def test_llama7b_32k_last_rank_causal_sliding_window():
     """Sec. 2.6 at full shape: the 7B slice of the last rank of a 32K ring, causal, window 6000:
     five of the eight chunks lie outside every row's window and are skipped, the others are cut
