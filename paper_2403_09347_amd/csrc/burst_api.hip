@@ -21,6 +21,11 @@ int launch_bwd_dq_generic(const KParams&, int, const void*, const void*, const v
                           const float*, float*, int, hipStream_t);
 int launch_bwd_dkv_generic(const KParams&, int, const void*, const void*, const void*, const void*, const float*,
                            const float*, float*, float*, int, hipStream_t);
+int launch_fwd_d64(const KParams&, const void*, const void*, const void*, float*, float*, float*, hipStream_t);
+int launch_bwd_dq_d64(const KParams&, const void*, const void*, const void*, const void*, const float*,
+                      const float*, float*, int, hipStream_t);
+int launch_bwd_dkv_d64(const KParams&, const void*, const void*, const void*, const void*, const float*,
+                       const float*, float*, float*, int, hipStream_t);
 size_t materialized_workspace_bytes(const KParams&, int);
 int launch_fwd_materialized(const KParams&, int, bool, const void*, const void*, const void*, float*, float*, float*,
                             void*, hipStream_t);
@@ -90,6 +95,14 @@ constexpr int kMaxMaskedRows = 8192 * 64;
 bool use_mfma(const burst_params* p) {
   return p->dtype == BURST_BF16 && p->d == 128 && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows;
 }
+// bf16, d = 64 without block flags has MFMA kernels of its own.
+#ifndef BURST_SMALL_D
+#define BURST_SMALL_D 64
+#endif
+bool use_d64(const burst_params* p) {
+  return p->dtype == BURST_BF16 && p->d == BURST_SMALL_D && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows &&
+         p->block_mask == nullptr;
+}
 // The dK/dV MFMA kernel walks the query tiles of all heads of a group as one list: whole 64-row
 // tiles per head and at most 8192 tiles in all; other grouped shapes take the generic kernel.
 bool dkv_mfma_ok(const burst_params* p, const KParams& k) {
@@ -140,6 +153,7 @@ int burst_local_fwd(const void* Q, const void* K_chunk, const void* V_chunk,
   REQUIRE_PTR(Q); REQUIRE_PTR(K_chunk); REQUIRE_PTR(V_chunk);
   REQUIRE_PTR(O_acc); REQUIRE_PTR(m); REQUIRE_PTR(l);
   if ((st = check_arch()) != BURST_OK) return st;
+  if (use_d64(p)) return burst::launch_fwd_d64(k, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
   if (use_mfma(p) && (p->block_mask == nullptr || p->Nc <= kMaxMaskedRows))
     return burst::launch_fwd_mfma(k, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
   return burst::launch_fwd_generic(k, p->dtype, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
@@ -243,6 +257,16 @@ static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const v
   }
   const bool mfma_dq = use_mfma(p) && (p->block_mask == nullptr || p->Nc <= kMaxMaskedRows);
   const bool mfma_dkv = use_mfma(p) && dkv_mfma_ok(p, k);
+  if (use_d64(p)) {
+    if (want_dq &&
+        (st = burst::launch_bwd_dq_d64(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)) != BURST_OK)
+      return st;
+    if (want_dkv &&
+        (st = burst::launch_bwd_dkv_d64(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk,
+                                        accumulate_dkv != 0, s)) != BURST_OK)
+      return st;
+    return BURST_OK;
+  }
   if (want_dq) {
     st = mfma_dq ? burst::launch_bwd_dq_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)
               : burst::launch_bwd_dq_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dQ,
@@ -317,6 +341,6 @@ const char* burst_strerror(int status) {
   }
 }
 
-int burst_version(void) { return 102; }
+int burst_version(void) { return 103; }
 
 }  // extern "C"

@@ -87,6 +87,32 @@ def test_generic_kernels_block_sparse(dtype, spec):
     compare_all_heads(case, dtype, O, lse, dQ, dKs, dVs)
 
 
+# bf16, d = 64: MFMA kernels of their own (32 rows or keys per wavefront, 64- and 32-key tiles).
+D64_CASES = [
+    dict(B=1, H=2, d=64, Nq=32, chunk_rows=[32]),
+    dict(B=1, H=3, d=64, Nq=300, chunk_rows=[200, 64, 331]),
+    dict(B=2, H=2, d=64, Nq=517, chunk_rows=[256, 1, 390]),
+    dict(B=1, H=9, d=64, Nq=128, chunk_rows=[512]),
+    dict(B=1, H=2, d=64, Nq=300, chunk_rows=[256, 192], causal=True, q_off=148),
+    dict(B=1, H=2, d=64, Nq=384, chunk_rows=[128, 128, 128], causal=True, q_off=0),
+    dict(B=1, H=1, d=64, Nq=100, chunk_rows=[64, 64], causal=True, q_off=-30),          # rows that see nothing
+    dict(B=1, H=2, d=64, Nq=600, chunk_rows=[256, 200, 344], causal=True, q_off=200, window=40),
+    dict(B=1, H=1, d=64, Nq=520, chunk_rows=[300, 300, 300], causal=False, q_off=100, window=130),
+    dict(B=1, H=1, d=64, Nq=300, chunk_rows=[128, 128, 128, 128], causal=True, q_off=2000, window=64,
+         k_offs=[0, 1800, 1928, 2200]),
+    dict(B=1, H=3, d=64, Nq=596, chunk_rows=[356], causal=True, q_off=107, window=1),
+    dict(B=1, H=6, kv_heads=2, d=64, Nq=300, chunk_rows=[260, 90], causal=True, q_off=100),   # grouped heads
+    dict(B=1, H=4, d=64, Nq=2048, chunk_rows=[2048]),                                   # many tiles, several workgroups
+]
+
+
+@pytest.mark.parametrize("spec", D64_CASES, ids=lambda s: "-".join(f"{k}{v}" for k, v in s.items()))
+def test_bf16_d64_forward_backward(spec):
+    case = workloads.make_case(dtype="bf16", seed=19, device=DEV, **spec)
+    _, (O, lse, dQ, dKs, dVs) = run_case(case, "bf16")
+    compare_all_heads(case, "bf16", O, lse, dQ, dKs, dVs)
+
+
 # Grouped-query attention (not in the paper): K, V, dK, dV with fewer heads than Q; dK, dV sum over the group.
 GQA_CASES = [
     ("bf16", dict(B=1, H=4, kv_heads=2, d=128, Nq=256, chunk_rows=[200, 130])),               # dK/dV MFMA kernel: Nq % 64 == 0
