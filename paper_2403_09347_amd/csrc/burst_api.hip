@@ -95,13 +95,16 @@ constexpr int kMaxMaskedRows = 8192 * 64;
 bool use_mfma(const burst_params* p) {
   return p->dtype == BURST_BF16 && p->d == 128 && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows;
 }
-// bf16, d = 64 without block flags has MFMA kernels of its own.
+// bf16, d = 64 has MFMA kernels of its own.
 #ifndef BURST_SMALL_D
 #define BURST_SMALL_D 64
 #endif
 bool use_d64(const burst_params* p) {
-  return p->dtype == BURST_BF16 && p->d == BURST_SMALL_D && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows &&
-         p->block_mask == nullptr;
+  if (!(p->dtype == BURST_BF16 && p->d == BURST_SMALL_D && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows)) return false;
+  if (p->block_mask == nullptr) return true;
+  // with block flags: lists of at most 4096 tiles (32 keys or rows each; rows of all heads of a group)
+  const long long group = (p->kv_heads > 0) ? p->H / p->kv_heads : 1;
+  return p->Nc <= 4096 * 32 && group * ((p->Nq + 31) / 32) <= 4096;
 }
 // The dK/dV MFMA kernel walks the query tiles of all heads of a group as one list: whole 64-row
 // tiles per head and at most 8192 tiles in all; other grouped shapes take the generic kernel.

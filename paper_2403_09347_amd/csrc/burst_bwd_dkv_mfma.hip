@@ -424,13 +424,15 @@ int launch_bwd_dkv_mfma(const KParams& p, const void* Q, const void* K, const vo
                         const void* dO, const float* lse, const float* D, float* dK, float* dV,
                         int acc_dkv, hipStream_t stream) {
   if (p.Nc <= 0) return BURST_OK;
-  static bool attr_set = false;
-  if (!attr_set) {
+  static bool attr_set[kMaxDevicesForAttr];
+  const int dev = current_device_slot();
+  if (dev < 0) return BURST_ERR_LAUNCH;
+  if (!attr_set[dev]) {
     if (hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             DKV_LDS_BYTES) != hipSuccess ||
         hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             DKV_LDS_BYTES + DKV_LIST_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
-    attr_set = true;
+    attr_set[dev] = true;
   }
   BwdArgs a = make_bwd_args(p, Q, K, V, dO, lse, D, nullptr, dK, dV, 0, acc_dkv);
   a.H = p.B * p.H / p.group;                       // workgroups are laid out over key/value heads

@@ -436,15 +436,17 @@ int launch_bwd_dq_mfma(const KParams& p, const void* Q, const void* K, const voi
   a.blocks_per_head = (p.Nq + DQ_BR - 1) / DQ_BR;
   long long nb = (long long)heads8 * a.blocks_per_head;
   if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;
-  static bool attr_set = false;
-  if (!attr_set) {
+  static bool attr_set[kMaxDevicesForAttr];
+  const int dev = current_device_slot();
+  if (dev < 0) return BURST_ERR_LAUNCH;
+  if (!attr_set[dev]) {
     if (hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             DQ_LDS_BYTES) != hipSuccess ||
         hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             DQ_LDS_BYTES) != hipSuccess ||
         hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             DQ_LDS_BYTES + DQ_LIST_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
-    attr_set = true;
+    attr_set[dev] = true;
   }
   if (a.bmask != nullptr) {
     if ((p.Nc + DQ_BC - 1) / DQ_BC > DQ_MAX_LIST) return BURST_ERR_SHAPE;

@@ -31,6 +31,15 @@ struct KParams {
   int group;             // query heads per key/value head (1 = every head has its own K, V)
 };
 
+// The opt-in to more than 64 KB of dynamic LDS is a per-device function attribute: launchers
+// keep one flag per device (index = current device, or -1 if it cannot be determined).
+constexpr int kMaxDevicesForAttr = 64;
+inline int current_device_slot() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevicesForAttr) return -1;
+  return dev;
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Cross-half exchange.  v_permlane32_swap exchanges the upper 32 lanes of its first operand

@@ -35,6 +35,7 @@ struct FwdArgsLite {
   int causal;
   float c;               // scale * log2(e)
   long long q_off, k_off, window;
+  const uint8_t* bmask; int bsize, bpitch;       // block flags (nullptr = none)
   int blocks_per_head;
 };
 
@@ -72,14 +73,43 @@ __device__ __forceinline__ void s_head_block(int bid, int blocks_per_head, int& 
   head = hx * 8 + xcd;
 }
 
+// Calls with block flags (paper Sec. 2.6) run the SPARSE instantiations: wavefront 0 first writes
+// the list of tiles that at least one wavefront of the workgroup can see into LDS (tile index plus
+// one bit per wavefront, list[0] = count, two end entries that name a tile past the data), the
+// loop then walks that list, and a wavefront whose bit is clear hides the whole tile.
+constexpr int S_MAX_LIST = 4096;                  // entries; longer masked calls take the generic kernels
+template <typename F>
+__device__ __forceinline__ int s_build_list(int* list, int w, int lane, int t_lo, int t_hi, int end_tile, F bits_of) {
+  if (w == 0) {
+    int n = 0;
+    for (int base = t_lo; base < t_hi; base += 64) {
+      const int t = base + lane;
+      int bits = 0;
+      if (t < t_hi) bits = bits_of(t);
+      const unsigned long long bal = __builtin_amdgcn_ballot_w64(bits != 0);
+      if (bits != 0) {
+        const int pos = n + __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0u));
+        list[1 + pos] = t | (bits << 20);
+      }
+      n += __builtin_popcountll(bal);
+    }
+    if (lane < 2) list[1 + n + lane] = end_tile;
+    if (lane == 0) list[0] = n;
+  }
+  __syncthreads();
+  return __builtin_amdgcn_readfirstlane(list[0]);
+}
+
 // ------------------------------------------------------------------------------- forward
 constexpr int SF_BR = 128;                        // query rows per workgroup (4 wavefronts x 32)
 constexpr int SF_BC = 64;                         // keys per tile
 constexpr int SF_TILE = SF_BC * S_ROWB;
 
+template <bool SPARSE>
 __global__ void __launch_bounds__(256, 2)
 burst_fwd_d64_kernel(FwdArgsLite a) {
   __shared__ __attribute__((aligned(16))) char smem[4 * SF_TILE];   // K[2], V[2]
+  extern __shared__ int s_list[];
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, lr = lane & 31, h = lane >> 5;
   int head, qb;
   s_head_block(blockIdx.x, a.blocks_per_head, head, qb);
@@ -91,13 +121,18 @@ burst_fwd_d64_kernel(FwdArgsLite a) {
 
   int Nc = a.Nc;
   long long k_off = a.k_off;
+  int t_lo = 0;
   if (a.window > 0) {                              // skip whole tiles before the window of the first row
     long long lo = a.q_off + (long long)qb * SF_BR - a.window + 1 - a.k_off;
     if (lo >= a.Nc) return;
     if (lo > 0) {
       const int skip = (int)(lo / SF_BC) * SF_BC;
-      Kh += (size_t)skip * S_D; Vh += (size_t)skip * S_D;
-      Nc -= skip; k_off += skip;
+      if constexpr (SPARSE) {
+        t_lo = skip / SF_BC;
+      } else {
+        Kh += (size_t)skip * S_D; Vh += (size_t)skip * S_D;
+        Nc -= skip; k_off += skip;
+      }
     }
   }
   int ntiles = (Nc + SF_BC - 1) / SF_BC;
@@ -108,6 +143,22 @@ burst_fwd_d64_kernel(FwdArgsLite a) {
     if (t < ntiles) ntiles = (int)t;
   }
   if (ntiles <= 0) return;
+  if constexpr (SPARSE) {
+    ntiles = s_build_list(s_list, w, lane, t_lo, ntiles, (Nc + SF_BC - 1) / SF_BC, [&](int t) {
+      int bits = 0;
+#pragma unroll
+      for (int ww = 0; ww < 4; ww++) {
+        const int row0 = qb * SF_BR + ww * 32;
+        if (row0 < a.Nq && a.bmask[(size_t)(row0 / a.bsize) * a.bpitch + (t * SF_BC) / a.bsize] != 0) bits |= 1 << ww;
+      }
+      return bits;
+    });
+    if (ntiles == 0) return;
+  }
+  auto entry_at = [&](int j) __attribute__((always_inline)) {      // walk position -> tile | wavefront bits << 20
+    if constexpr (SPARSE) return __builtin_amdgcn_readfirstlane(s_list[1 + j]);
+    else return j | (0xf << 20);
+  };
 
   bf16x8 qf[S_KS];
 #pragma unroll
@@ -142,13 +193,16 @@ burst_fwd_d64_kernel(FwdArgsLite a) {
   bf16x2 ones;
   ones[0] = (bf16)1.0f; ones[1] = (bf16)1.0f;
 
-  dma_tile(0, 0);
-  for (int kt = 0; kt < ntiles; kt++) {
-    __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0), lgkmcnt(0): tile kt landed, reads of tile kt-1 done
+  dma_tile(entry_at(0) & 0xfffff, 0);
+  for (int j = 0; j < ntiles; j++) {               // j = walk position, kt = tile
+    const int e = entry_at(j);
+    const int kt = e & 0xfffff;
+    const bool mine = ((e >> (20 + wu)) & 1) != 0;
+    __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0), lgkmcnt(0): the tile landed, reads of the one before are done
     __builtin_amdgcn_s_barrier();
-    if (kt + 1 < ntiles) dma_tile(kt + 1, (kt + 1) & 1);
-    const char* kl = smem + (kt & 1) * SF_TILE;
-    const char* vl = smem + (2 + (kt & 1)) * SF_TILE;
+    if (j + 1 < ntiles) dma_tile(entry_at(j + 1) & 0xfffff, (j + 1) & 1);
+    const char* kl = smem + (j & 1) * SF_TILE;
+    const char* vl = smem + (2 + (j & 1)) * SF_TILE;
     // S^T = K Q^T: register r of key block kb = key kt*64 + kb*32 + 8*(r/4) + 4h + r%4
     f32x16 s[2];
 #pragma unroll
@@ -163,12 +217,13 @@ burst_fwd_d64_kernel(FwdArgsLite a) {
     const long long tile_first_k = k_off + (long long)kt * SF_BC;
     const bool need_mask = (a.causal && tile_first_k + SF_BC - 1 > wave_first_q) ||
                            (a.window > 0 && tile_first_k < wave_last_q - a.window + 1) ||
-                           ((kt + 1) * SF_BC > Nc);
+                           ((kt + 1) * SF_BC > Nc) || !mine;
     if (need_mask) {
       const long long dd = (a.q_off - k_off) + (q0 + lr) - ((long long)kt * SF_BC + 4 * h);
       const int tail = Nc - 1 - (kt * SF_BC + 4 * h);
       int lim = a.causal ? (int)(dd < -1 ? -1 : (dd > 64 ? 64 : dd)) : 64;
       lim = lim < tail ? lim : tail;
+      if (!mine) lim = -1;
       const long long dl = dd - a.window + 1;
       const int lim_lo = a.window > 0 ? (int)(dl < -1 ? -1 : (dl > 64 ? 64 : dl)) : -1;
 #pragma unroll
@@ -252,9 +307,11 @@ constexpr int SQ_BR = 128;                        // query rows per workgroup
 constexpr int SQ_BC = 32;                         // keys per tile
 constexpr int SQ_TILE = SQ_BC * S_ROWB;
 
+template <bool SPARSE>
 __global__ void __launch_bounds__(256, 2)
 burst_bwd_dq_d64_kernel(BwdArgs a) {
   __shared__ __attribute__((aligned(16))) char smem[4 * SQ_TILE];   // K[2], V[2]
+  extern __shared__ int s_list[];
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, lr = lane & 31, h = lane >> 5;
   int head, qb;
   s_head_block(blockIdx.x, a.blocks_per_head, head, qb);
@@ -269,13 +326,18 @@ burst_bwd_dq_d64_kernel(BwdArgs a) {
   int Nc = a.Nc;
   long long k_off = a.k_off;
   bool nothing = false;
+  int t_lo = 0;
   if (a.window > 0) {
     long long lo = a.q_off + (long long)qb * SQ_BR - a.window + 1 - a.k_off;
     if (lo >= a.Nc) nothing = true;
     else if (lo > 0) {
       const int skip = (int)(lo / SQ_BC) * SQ_BC;
-      Kh += (size_t)skip * S_D; Vh += (size_t)skip * S_D;
-      Nc -= skip; k_off += skip;
+      if constexpr (SPARSE) {
+        t_lo = skip / SQ_BC;
+      } else {
+        Kh += (size_t)skip * S_D; Vh += (size_t)skip * S_D;
+        Nc -= skip; k_off += skip;
+      }
     }
   }
   int ntiles = nothing ? 0 : (Nc + SQ_BC - 1) / SQ_BC;
@@ -284,6 +346,22 @@ burst_bwd_dq_d64_kernel(BwdArgs a) {
     long long t = lim < 0 ? 0 : lim / SQ_BC + 1;
     if (t < ntiles) ntiles = (int)t;
   }
+
+  if constexpr (SPARSE) {
+    ntiles = s_build_list(s_list, w, lane, t_lo, ntiles, (Nc + SQ_BC - 1) / SQ_BC, [&](int t) {
+      int bits = 0;
+#pragma unroll
+      for (int ww = 0; ww < 4; ww++) {
+        const int row0 = qb * SQ_BR + ww * 32;
+        if (row0 < a.Nq && a.bmask[(size_t)(row0 / a.bsize) * a.bpitch + (t * SQ_BC) / a.bsize] != 0) bits |= 1 << ww;
+      }
+      return bits;
+    });
+  }
+  auto entry_at = [&](int j) __attribute__((always_inline)) {
+    if constexpr (SPARSE) return __builtin_amdgcn_readfirstlane(s_list[1 + j]);
+    else return j | (0xf << 20);
+  };
 
   f32x16 dq[S_DB];
 #pragma unroll
@@ -322,13 +400,16 @@ burst_bwd_dq_d64_kernel(BwdArgs a) {
     };
     const long long wave_first_q = a.q_off + q0;
 
-    dma_tile(0, 0);
-    for (int kt = 0; kt < ntiles; kt++) {
+    dma_tile(entry_at(0) & 0xfffff, 0);
+    for (int j = 0; j < ntiles; j++) {             // j = walk position, kt = tile
+      const int e = entry_at(j);
+      const int kt = e & 0xfffff;
+      const bool mine = ((e >> (20 + wu)) & 1) != 0;
       __builtin_amdgcn_s_waitcnt(0x0070);
       __builtin_amdgcn_s_barrier();
-      if (kt + 1 < ntiles) dma_tile(kt + 1, (kt + 1) & 1);
-      const char* kl = smem + (kt & 1) * SQ_TILE;
-      const char* vl = smem + (2 + (kt & 1)) * SQ_TILE;
+      if (j + 1 < ntiles) dma_tile(entry_at(j + 1) & 0xfffff, (j + 1) & 1);
+      const char* kl = smem + (j & 1) * SQ_TILE;
+      const char* vl = smem + (2 + (j & 1)) * SQ_TILE;
       // S^T = K Q^T, dP^T = V dO^T: register r = key kt*32 + 8*(r/4) + 4h + r%4
       f32x16 s, dp;
 #pragma unroll
@@ -341,12 +422,13 @@ burst_bwd_dq_d64_kernel(BwdArgs a) {
       const long long tile_first_k = k_off + (long long)kt * SQ_BC;
       const bool need_mask = (a.causal && tile_first_k + SQ_BC - 1 > wave_first_q) ||
                              (a.window > 0 && tile_first_k < wave_first_q + 31 - a.window + 1) ||
-                             ((kt + 1) * SQ_BC > Nc);
+                             ((kt + 1) * SQ_BC > Nc) || !mine;
       if (need_mask) {
         const long long dd = (a.q_off - k_off) + (q0 + lr) - ((long long)kt * SQ_BC + 4 * h);
         const int tail = Nc - 1 - (kt * SQ_BC + 4 * h);
         int lim = a.causal ? (int)(dd < -1 ? -1 : (dd > 64 ? 64 : dd)) : 64;
         lim = lim < tail ? lim : tail;
+        if (!mine) lim = -1;
         const long long dl = dd - a.window + 1;
         const int lim_lo = a.window > 0 ? (int)(dl < -1 ? -1 : (dl > 64 ? 64 : dl)) : -1;
 #pragma unroll
@@ -395,9 +477,11 @@ constexpr int SK_BR = 32;                         // query rows per tile
 constexpr int SK_TILE = SK_BR * S_ROWB;
 constexpr int SK_STAT = 4 * SK_TILE;              // per buffer: 32 x (-lse log2 e), 32 x D
 
+template <bool SPARSE>
 __global__ void __launch_bounds__(256, 2)
 burst_bwd_dkv_d64_kernel(BwdArgs a) {
   __shared__ __attribute__((aligned(16))) char smem[4 * SK_TILE + 2 * 64 * 4];   // Q[2], dO[2], statistics[2]
+  extern __shared__ int s_list[];
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, lr = lane & 31, h = lane >> 5;
   int kvhead, kblk;
   s_head_block(blockIdx.x, a.blocks_per_head, kvhead, kblk);
@@ -418,7 +502,31 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
     t_end = last_row < 0 ? 0 : (int)min((long long)t_end, last_row / SK_BR + 1);
   }
   const int per_head = t_end > t_begin ? t_end - t_begin : 0;
-  const int nwalk = per_head * a.group;
+  int nwalk = per_head * a.group;
+  if constexpr (SPARSE) {                          // entries count tiles over all heads of the group
+    nwalk = s_build_list(s_list, w, lane, 0, nwalk, 0, [&](int n) {
+      const int t = t_begin + n % (per_head > 0 ? per_head : 1);
+      const uint8_t* mrow = a.bmask + (size_t)((t * SK_BR) / a.bsize) * a.bpitch;
+      int bits = 0;
+#pragma unroll
+      for (int ww = 0; ww < 4; ww++) {
+        const int k0 = key_wg + ww * 32;
+        if (k0 < a.Nc && mrow[k0 / a.bsize] != 0) bits |= 1 << ww;
+      }
+      return bits;
+    });
+  }
+  // walk position -> (query head of the group, tile, this wavefront's bit)
+  auto locate = [&](int j, int& g, int& t) __attribute__((always_inline)) {
+    int n = j, bits = 0xf;
+    if constexpr (SPARSE) {
+      const int e = __builtin_amdgcn_readfirstlane(s_list[1 + j]);
+      n = e & 0xfffff; bits = e >> 20;
+    }
+    g = n / per_head;
+    t = t_begin + (n - g * per_head);
+    return bits;
+  };
 
   f32x16 dk[S_DB], dv[S_DB];
 #pragma unroll
@@ -450,7 +558,8 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
     // writes them to LDS at the end of the step (stat_commit).
     float stat_x = 0.f;
     auto fetch = [&](int n, int buf) __attribute__((always_inline)) {
-      const int g = n / per_head, t = t_begin + (n - g * per_head);
+      int g, t;
+      locate(n, g, t);
       const size_t hrow = (size_t)(kvhead * a.group + g) * a.Nq;
       if (tid < 64) {
         const int r = t * SK_BR + (tid & 31);
@@ -481,7 +590,8 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
       const int buf = n & 1;
       const char* ql = smem + buf * SK_TILE;
       const char* gl = smem + (2 + buf) * SK_TILE;
-      const int t = t_begin + n % per_head;
+      int g_unused, t;
+      const bool mine = ((locate(n, g_unused, t) >> wu) & 1) != 0;
       // S = Q K^T, dP = dO V^T: lane = key lr, register r = row t*32 + 8*(r/4) + 4h + r%4
       f32x16 s, dp;
 #pragma unroll
@@ -493,12 +603,12 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
       }
       const long long tile_first_q = a.q_off + (long long)t * SK_BR;
       const bool need_mask = (a.causal && wave_last_k > tile_first_q) ||
-                             (a.window > 0 && tile_first_q + SK_BR - 1 >= wave_first_k + a.window);
+                             (a.window > 0 && tile_first_q + SK_BR - 1 >= wave_first_k + a.window) || !mine;
       if (need_mask) {
         // visible iff key position <= row position (constant part >= lim) and row position <
         // key position + window (constant part <= lim2)
         const long long d = kpos - (tile_first_q + 4 * h);
-        const int lim = a.causal ? (int)(d < -1 ? -1 : (d > 64 ? 64 : d)) : -1;
+        const int lim = !mine ? 65 : a.causal ? (int)(d < -1 ? -1 : (d > 64 ? 64 : d)) : -1;
         const long long d2 = d + a.window - 1;
         const int lim2 = a.window > 0 ? (int)(d2 < -1 ? -1 : (d2 > 64 ? 64 : d2)) : 64;
 #pragma unroll
@@ -562,10 +672,17 @@ int launch_fwd_d64(const KParams& p, const void* Q, const void* K, const void* V
   a.Nq = p.Nq; a.Nc = p.Nc; a.H = p.B * p.H; a.group = p.group;
   a.causal = p.causal; a.c = p.scale * kLog2e;
   a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
+  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch;
   a.blocks_per_head = (p.Nq + SF_BR - 1) / SF_BR;
   const long long nb = (long long)((a.H + 7) / 8 * 8) * a.blocks_per_head;
   if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;
-  hipLaunchKernelGGL(burst_fwd_d64_kernel, dim3((unsigned)nb), dim3(256), 0, stream, a);
+  if (a.bmask != nullptr) {
+    const int entries = (p.Nc + SF_BC - 1) / SF_BC;
+    if (entries > S_MAX_LIST) return BURST_ERR_SHAPE;
+    hipLaunchKernelGGL(burst_fwd_d64_kernel<true>, dim3((unsigned)nb), dim3(256), (entries + 4) * 4, stream, a);
+  } else {
+    hipLaunchKernelGGL(burst_fwd_d64_kernel<false>, dim3((unsigned)nb), dim3(256), 0, stream, a);
+  }
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 
@@ -577,7 +694,13 @@ int launch_bwd_dq_d64(const KParams& p, const void* Q, const void* K, const void
   a.blocks_per_head = (p.Nq + SQ_BR - 1) / SQ_BR;
   const long long nb = (long long)((a.H + 7) / 8 * 8) * a.blocks_per_head;
   if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;
-  hipLaunchKernelGGL(burst_bwd_dq_d64_kernel, dim3((unsigned)nb), dim3(256), 0, stream, a);
+  if (a.bmask != nullptr) {
+    const int entries = (p.Nc + SQ_BC - 1) / SQ_BC;
+    if (entries > S_MAX_LIST) return BURST_ERR_SHAPE;
+    hipLaunchKernelGGL(burst_bwd_dq_d64_kernel<true>, dim3((unsigned)nb), dim3(256), (entries + 4) * 4, stream, a);
+  } else {
+    hipLaunchKernelGGL(burst_bwd_dq_d64_kernel<false>, dim3((unsigned)nb), dim3(256), 0, stream, a);
+  }
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 
@@ -590,7 +713,13 @@ int launch_bwd_dkv_d64(const KParams& p, const void* Q, const void* K, const voi
   a.blocks_per_head = (p.Nc + SK_BC - 1) / SK_BC;
   const long long nb = (long long)((a.H + 7) / 8 * 8) * a.blocks_per_head;
   if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;
-  hipLaunchKernelGGL(burst_bwd_dkv_d64_kernel, dim3((unsigned)nb), dim3(256), 0, stream, a);
+  if (a.bmask != nullptr) {
+    const long long entries = (long long)p.group * ((p.Nq + SK_BR - 1) / SK_BR);
+    if (entries > S_MAX_LIST) return BURST_ERR_SHAPE;
+    hipLaunchKernelGGL(burst_bwd_dkv_d64_kernel<true>, dim3((unsigned)nb), dim3(256), ((int)entries + 4) * 4, stream, a);
+  } else {
+    hipLaunchKernelGGL(burst_bwd_dkv_d64_kernel<false>, dim3((unsigned)nb), dim3(256), 0, stream, a);
+  }
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 

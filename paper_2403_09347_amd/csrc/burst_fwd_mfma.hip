@@ -503,13 +503,15 @@ int launch_fwd_mfma(const KParams& p, const void* Q, const void* K, const void* 
   int heads8 = ((a.H + 7) / 8) * 8;                // pad the head count to a multiple of 8 ids
   long long nblocks = (long long)heads8 * a.q_blocks;
   if (nblocks > 0x7fffffffLL) return BURST_ERR_SHAPE;
-  static bool attr_set = false;
-  if (!attr_set) {
+  static bool attr_set[kMaxDevicesForAttr];
+  const int dev = current_device_slot();
+  if (dev < 0) return BURST_ERR_LAUNCH;
+  if (!attr_set[dev]) {
     if (hipFuncSetAttribute((const void*)burst_fwd_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             2 * FWD_NBUF * FWD_TILE_BYTES) != hipSuccess ||
         hipFuncSetAttribute((const void*)burst_fwd_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                             2 * FWD_NBUF * FWD_TILE_BYTES + FWD_LIST_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
-    attr_set = true;
+    attr_set[dev] = true;
   }
   if (a.bmask != nullptr) {
     if ((p.Nc + FWD_BC - 1) / FWD_BC > FWD_MAX_LIST) return BURST_ERR_SHAPE;

@@ -103,6 +103,14 @@ D64_CASES = [
     dict(B=1, H=3, d=64, Nq=596, chunk_rows=[356], causal=True, q_off=107, window=1),
     dict(B=1, H=6, kv_heads=2, d=64, Nq=300, chunk_rows=[260, 90], causal=True, q_off=100),   # grouped heads
     dict(B=1, H=4, d=64, Nq=2048, chunk_rows=[2048]),                                   # many tiles, several workgroups
+    # block flags: lists of visible tiles
+    dict(B=1, H=2, d=64, Nq=300, chunk_rows=[200, 64, 331], block=64, pattern="random"),
+    dict(B=1, H=2, d=64, Nq=700, chunk_rows=[512, 300], block=128, pattern="random", density=0.3),
+    dict(B=1, H=2, d=64, Nq=640, chunk_rows=[640, 640], block=64, pattern="band", causal=True, q_off=640),
+    dict(B=1, H=1, d=64, Nq=520, chunk_rows=[300, 300, 300], block=64, pattern="random", density=0.6,
+         causal=True, q_off=380, window=200),
+    dict(B=1, H=4, kv_heads=2, d=64, Nq=256, chunk_rows=[256, 192], block=64, pattern="random", density=0.5),
+    dict(B=1, H=2, d=64, Nq=200, chunk_rows=[256], block=64, pattern="random", density=0.0),       # nothing visible
 ]
 
 
