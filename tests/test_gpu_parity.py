@@ -388,50 +388,82 @@ def test_error_codes_on_device_buffers():
     assert torch.all(x == 0)                                     # nothing was written
 
 
-def test_no_kernel_writes_outside_its_buffers():
-    """Every output buffer sits between guard bands filled with a pattern; after the whole path has run
-    on ragged shapes (tails in rows, keys and heads) the bands must be untouched, and so must the
-    read-only inputs."""
-    case = workloads.make_case(B=1, H=3, d=128, Nq=333, chunk_rows=[257, 95], dtype="bf16", seed=47, device=DEV,
-                               causal=True, q_off=40, window=200)
+GUARD_CASES = {
+    "d128": dict(B=1, H=3, d=128, Nq=333, chunk_rows=[257, 95], causal=True, q_off=40, window=200),
+    "d128-flags-grouped": dict(B=1, H=6, kv_heads=3, d=128, Nq=320, chunk_rows=[257, 95], causal=True, q_off=40,
+                               block=64, pattern="random", density=0.6),
+    "d64": dict(B=1, H=3, d=64, Nq=333, chunk_rows=[257, 95], causal=True, q_off=40, window=200),
+    "d64-flags-grouped": dict(B=1, H=6, kv_heads=2, d=64, Nq=301, chunk_rows=[200, 130], block=128, pattern="random",
+                              density=0.5),
+    "generic-f32": dict(B=1, H=2, d=48, Nq=77, chunk_rows=[65, 31], causal=True, q_off=20, dtype="f32"),
+}
+
+
+@pytest.mark.parametrize("name", list(GUARD_CASES))
+def test_no_kernel_writes_outside_its_buffers(name):
+    """Every output buffer (and the workspace of the stored-score step) sits between guard bands filled
+    with a pattern; after the whole path has run on ragged shapes (tails in rows, keys and heads) the
+    bands must be untouched, and so must the read-only inputs."""
+    spec = dict(GUARD_CASES[name])
+    dtype = spec.pop("dtype", "bf16")
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    case = workloads.make_case(dtype=dtype, seed=47, device=DEV, **spec)
     G = 4096                                    # guard elements on each side
-    def guarded(shape, dtype, fill=None):
+    def guarded(shape, dt, fill=None):
         n = int(np.prod(shape))
-        pat = 12345.0 if dtype != torch.bfloat16 else 77.0
-        flat = torch.full((n + 2 * G,), pat, device=DEV, dtype=dtype)
+        pat = 12345.0 if dt != torch.bfloat16 else 77.0
+        flat = torch.full((n + 2 * G,), pat, device=DEV, dtype=dt)
         view = flat[G:G + n].view(*shape)
         if fill is not None:
             view.fill_(fill)
         return flat, view, pat
     Bt, H, Nq, d = case["Q"].shape
     bufs = {}
-    for name, shape, dt in (("O_acc", (Bt, H, Nq, d), torch.float32), ("m", (Bt, H, Nq), torch.float32),
-                            ("l", (Bt, H, Nq), torch.float32), ("O", (Bt, H, Nq, d), torch.bfloat16),
-                            ("lse", (Bt, H, Nq), torch.float32), ("D", (Bt, H, Nq), torch.float32),
-                            ("dQ", (Bt, H, Nq, d), torch.float32)):
-        bufs[name] = guarded(shape, dt, 0.0 if name == "dQ" else None)
+    for nm, shape, dt in (("O_acc", (Bt, H, Nq, d), torch.float32), ("m", (Bt, H, Nq), torch.float32),
+                          ("l", (Bt, H, Nq), torch.float32), ("O", (Bt, H, Nq, d), tdt),
+                          ("lse", (Bt, H, Nq), torch.float32), ("D", (Bt, H, Nq), torch.float32),
+                          ("dQ", (Bt, H, Nq, d), torch.float32),
+                          ("O_acc2", (Bt, H, Nq, d), torch.float32), ("m2", (Bt, H, Nq), torch.float32),
+                          ("l2", (Bt, H, Nq), torch.float32)):
+        bufs[nm] = guarded(shape, dt, 0.0 if nm == "dQ" else None)
     dK = [guarded(tuple(k.shape), torch.float32) for k in case["K"]]
     dV = [guarded(tuple(k.shape), torch.float32) for k in case["K"]]
     inputs_before = [t.clone() for t in (case["Q"], case["dO"], *case["K"], *case["V"])]
-    prm = lambda Nc, ko: B.params(Bt, H, Nq, Nc, d, torch.bfloat16, case["scale"], True, case["q_off"], ko, case["window"])
+    masks = case.get("masks", [None] * len(case["K"]))
+    prm = lambda Nc, ko, mask=None: B.params(Bt, H, Nq, Nc, d, tdt, case["scale"], case["causal"], case["q_off"], ko,
+                                             case["window"], mask, case.get("block", 0), case.get("kv_heads", 0))
     v = {k: t[1] for k, t in bufs.items()}
     B.burst_state_init(v["O_acc"], v["m"], v["l"], prm(0, 0))
-    for K, V, ko in zip(case["K"], case["V"], case["k_offs"]):
-        B.burst_local_fwd(case["Q"], K, V, v["O_acc"], v["m"], v["l"], prm(K.shape[2], ko))
+    for K, V, ko, mk in zip(case["K"], case["V"], case["k_offs"], masks):
+        B.burst_local_fwd(case["Q"], K, V, v["O_acc"], v["m"], v["l"], prm(K.shape[2], ko, mk))
     B.burst_finalize(v["O_acc"], v["m"], v["l"], v["O"], v["lse"], prm(0, 0))
     B.burst_bwd_prepare(v["O"], case["dO"], v["D"], prm(0, 0))
-    for j, (K, V, ko) in enumerate(zip(case["K"], case["V"], case["k_offs"])):
+    for j, (K, V, ko, mk) in enumerate(zip(case["K"], case["V"], case["k_offs"], masks)):
         B.burst_local_bwd(case["Q"], K, V, v["O"], case["dO"], v["lse"], v["D"], v["dQ"], dK[j][1], dV[j][1],
-                          prm(K.shape[2], ko), accumulate_dq=True, accumulate_dkv=False)
+                          prm(K.shape[2], ko, mk), accumulate_dq=True, accumulate_dkv=False)
+    # the chunk step that stores S and P, with a workspace of exactly the size it asks for
+    B.burst_state_init(v["O_acc2"], v["m2"], v["l2"], prm(0, 0))
+    spaces = []
+    for K, V, ko, mk in zip(case["K"], case["V"], case["k_offs"], masks):
+        need = B.burst_materialized_workspace_bytes(prm(K.shape[2], ko, mk))
+        flat = torch.full((need + 2 * G,), 201, device=DEV, dtype=torch.uint8)
+        spaces.append((flat, need))
+        B.burst_local_fwd_materialized(case["Q"], K, V, v["O_acc2"], v["m2"], v["l2"], flat[G:G + need], prm(K.shape[2], ko, mk))
     torch.cuda.synchronize()
-    for name, (flat, view, pat) in list(bufs.items()) + [(f"dK{j}", t) for j, t in enumerate(dK)] + \
+    for nm, (flat, view, pat) in list(bufs.items()) + [(f"dK{j}", t) for j, t in enumerate(dK)] + \
             [(f"dV{j}", t) for j, t in enumerate(dV)]:
         n = view.numel()
-        assert bool((flat[:G] == pat).all()) and bool((flat[G + n:] == pat).all()), f"guard band of {name} was written"
+        assert bool((flat[:G] == pat).all()) and bool((flat[G + n:] == pat).all()), f"guard band of {nm} was written"
+    for flat, need in spaces:
+        assert bool((flat[:G] == 201).all()) and bool((flat[G + need:] == 201).all()), "guard band of the workspace was written"
     for before, now in zip(inputs_before, (case["Q"], case["dO"], *case["K"], *case["V"])):
         assert torch.equal(before, now)
-    # and the results are the right ones
-    compare_all_heads(case, "bf16", v["O"], v["lse"], v["dQ"], [t[1] for t in dK], [t[1] for t in dV])
+    # and the results are the right ones (the two forward paths agree with the oracle independently)
+    compare_all_heads(case, dtype, v["O"], v["lse"], v["dQ"], [t[1] for t in dK], [t[1] for t in dV])
+    O2, lse2 = torch.empty_like(v["O"]), torch.empty_like(v["lse"])
+    B.burst_finalize(v["O_acc2"], v["m2"], v["l2"], O2, lse2, prm(0, 0))
+    torch.cuda.synchronize()
+    compare_all_heads(case, dtype, O2, lse2)
 
 
 @pytest.mark.parametrize("rank", [0, 2, 3])
