@@ -427,8 +427,10 @@ burst_fwd_mfma_kernel(FwdArgs a) {
       if (i >= 12 && i < 28) {                     // row maxima of the next tile: 16 slices x 4 scores
         const int e = i - 12;                      // 0..15
         const int kb2 = e >> 3, r = (e & 7) * 2;
-        nmax0 = fmaxf(nmax0, fmaxf(sx[kb2][0][r], sx[kb2][0][r + 1]));
-        nmax1 = fmaxf(nmax1, fmaxf(sx[kb2][1][r], sx[kb2][1][r + 1]));
+        // (one three-operand maximum per two scores; written out because the compiler otherwise
+        // pairs the scores first and needs three instructions for four of them)
+        asm("v_max3_f32 %0, %1, %2, %3" : "=v"(nmax0) : "v"(nmax0), "v"(sx[kb2][0][r]), "v"(sx[kb2][0][r + 1]));
+        asm("v_max3_f32 %0, %1, %2, %3" : "=v"(nmax1) : "v"(nmax1), "v"(sx[kb2][1][r]), "v"(sx[kb2][1][r + 1]));
       }
       if (i == 28) mx[0] = max_both_halves(nmax0) * a.c;
       if (i == 29) mx[1] = max_both_halves(nmax1) * a.c;
