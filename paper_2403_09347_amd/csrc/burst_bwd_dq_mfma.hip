@@ -338,12 +338,12 @@ burst_bwd_dq_kernel(BwdArgs a) {
           // (the empty asm statements tie this slice's arithmetic between this slice's MFMA and
           // the next one: all of them are asm statements and keep their order)
           const int prb = i >> 3, r = 2 * (i & 7);
-          float x0 = s[prb][r], x1 = s[prb][r + 1];
-          asm volatile("" : "+v"(x0), "+v"(x1));
-          float p0 = fast_exp2(__builtin_fmaf(x0, a.c, nlse2[prb]));
-          float p1 = fast_exp2(__builtin_fmaf(x1, a.c, nlse2[prb]));
-          asm volatile("" : "+v"(p0), "+v"(p1));
-          s[prb][r] = p0; s[prb][r + 1] = p1;
+          // (anchored on the whole accumulator and computed in place: anchors on copies of single
+          // elements cost a register move per slice)
+          asm volatile("" : "+v"(s[prb]));
+          s[prb][r] = fast_exp2(__builtin_fmaf(s[prb][r], a.c, nlse2[prb]));
+          s[prb][r + 1] = fast_exp2(__builtin_fmaf(s[prb][r + 1], a.c, nlse2[prb]));
+          asm volatile("" : "+v"(s[prb]));
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -355,10 +355,9 @@ burst_bwd_dq_kernel(BwdArgs a) {
         // (the empty asm statements order this slice's arithmetic after the slice's MFMA, which is
         // an asm statement too: the compiler would otherwise clump two MFMAs and two slices of
         // vector work, and an in-order wavefront then stalls behind the second MFMA)
-        float x0 = dp[prb][r], x1 = dp[prb][r + 1];
-        asm volatile("" : "+v"(x0), "+v"(x1));
-        float d0 = s[prb][r] * x0;
-        float d1 = s[prb][r + 1] * x1;
+        asm volatile("" : "+v"(dp[prb]));
+        float d0 = s[prb][r] * dp[prb][r];
+        float d1 = s[prb][r + 1] * dp[prb][r + 1];
         bf16x2 pk;
         pk[0] = (bf16)d0; pk[1] = (bf16)d1;
         unsigned pu = __builtin_bit_cast(unsigned, pk);
