@@ -52,6 +52,26 @@ __device__ __forceinline__ void mfma32_dp_first(f32x16& acc, bf16x8 a, bf16x8& b
 __device__ __forceinline__ void mfma32_dp(f32x16& acc, bf16x8 a, bf16x8& b_resident) {
   asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %1, %0" : "+v"(acc), "+a"(b_resident) : "v"(a));
 }
+// The same MFMAs with two independent vector instructions of the slice's own work placed in
+// front of them inside one asm statement: whatever register copies the compiler puts before the
+// statement are then at least two instructions away from the MFMA, and no s_nop is needed.
+// t0 = x0 * c + n, t1 = x1 * c + n (the exponents of two scores), then the dP^T MFMA.
+__device__ __forceinline__ void fma2_mfma32_dp(f32x16& acc, bf16x8 a, bf16x8& b_resident, float& t0, float& t1,
+                                               float x0, float x1, float c, float n) {
+  asm volatile("v_fma_f32 %2, %5, %7, %8\n\tv_fma_f32 %3, %6, %7, %8\n\tv_mfma_f32_32x32x16_bf16 %0, %4, %1, %0"
+               : "+v"(acc), "+a"(b_resident), "=&v"(t0), "=&v"(t1) : "v"(a), "v"(x0), "v"(x1), "s"(c), "v"(n));
+}
+__device__ __forceinline__ void fma2_mfma32_dp_first(f32x16& acc, bf16x8 a, bf16x8& b_resident, const f32x16& start,
+                                                     float& t0, float& t1, float x0, float x1, float c, float n) {
+  asm volatile("v_fma_f32 %2, %6, %8, %9\n\tv_fma_f32 %3, %7, %8, %9\n\tv_mfma_f32_32x32x16_bf16 %0, %4, %1, %5"
+               : "=&v"(acc), "+a"(b_resident), "=&v"(t0), "=&v"(t1) : "v"(a), "v"(start), "v"(x0), "v"(x1), "s"(c), "v"(n));
+}
+// d0 = p0 * q0, d1 = p1 * q1 (two dS values), then a dQ^T MFMA on an AGPR accumulator.
+__device__ __forceinline__ void mul2_mfma32_acc(f32x16& acc, bf16x8 a, bf16x8 b, float& d0, float& d1,
+                                                float p0, float q0, float p1, float q1) {
+  asm volatile("v_mul_f32 %1, %5, %6\n\tv_mul_f32 %2, %7, %8\n\tv_mfma_f32_32x32x16_bf16 %0, %3, %4, %0"
+               : "+a"(acc), "=&v"(d0), "=&v"(d1) : "v"(a), "v"(b), "v"(p0), "v"(q0), "v"(p1), "v"(q1));
+}
 __device__ __forceinline__ void mfma_vgpr_fence(f32x16 (&acc)[2]) {
   asm volatile("s_nop 15\n\ts_nop 3" : "+v"(acc[0]), "+v"(acc[1]));
 }
@@ -257,8 +277,7 @@ burst_bwd_dq_kernel(BwdArgs a) {
           tq[tn % TRING][0] = lds_read_tr(kl_prev, (tn >> 2) * 16 * 256 + taddr[tn & 3][0]);
           tq[tn % TRING][1] = lds_read_tr(kl_prev, (tn >> 2) * 16 * 256 + taddr[tn & 3][1]);
         }
-        mfma32_acc(dq[rb][db], cat4(tq[tf % TRING][0], tq[tf % TRING][1]), dsp[rb][kg]);
-        extra(i);
+        extra(i, dq[rb][db], cat4(tq[tf % TRING][0], tq[tf % TRING][1]), dsp[rb][kg]);
         __builtin_amdgcn_sched_barrier(0);
       }
     };
@@ -297,6 +316,11 @@ burst_bwd_dq_kernel(BwdArgs a) {
         s[rb] = mfma32(kfq[ks % 3], qf[rb][ks], ks == 0 ? zero16 : s[rb]);
         __builtin_amdgcn_sched_barrier(0);
       }
+      // The exponents below are computed inside asm statements, where the compiler does not see
+      // that they read S^T: the last MFMA that wrote s[0] is one MFMA (32 cycles) and the mask test
+      // (some twenty instructions) ahead of the first such read, s[1] is first read eight slices
+      // later; the four idle cycles here are a margin on top of that.
+      asm volatile("s_nop 3" : "+v"(s[0]), "+v"(s[1]));
       // ---- masking (diagonal tiles, window edge, ragged key tail): rare.  A masked score becomes
       // -inf, its P and dS become 0.
       const long long tile_first_k = k_off + (long long)kt * DQ_BC;
@@ -332,17 +356,16 @@ burst_bwd_dq_kernel(BwdArgs a) {
       for (int i = 0; i < 16; i++) {
         const int ks = i >> 1, rb = i & 1;
         if (rb == 0 && ks + 2 < 8) vfq[(ks + 2) % 3] = lds_read_b128(vl, abase ^ ((ks + 2) << 5));
-        if (ks == 0) mfma32_dp_first(dp[rb], vfq[0], gfr[rb][0], negD[rb]);
-        else mfma32_dp(dp[rb], vfq[ks % 3], gfr[rb][ks]);
         {
-          // (the empty asm statements tie this slice's arithmetic between this slice's MFMA and
-          // the next one: all of them are asm statements and keep their order)
+          // the slice's MFMA with the exponents of score pair i computed right in front of it;
+          // the exponentials follow (the empty asm statement keeps them in this slice: asm
+          // statements keep their order)
           const int prb = i >> 3, r = 2 * (i & 7);
-          // (anchored on the whole accumulator and computed in place: anchors on copies of single
-          // elements cost a register move per slice)
-          asm volatile("" : "+v"(s[prb]));
-          s[prb][r] = fast_exp2(__builtin_fmaf(s[prb][r], a.c, nlse2[prb]));
-          s[prb][r + 1] = fast_exp2(__builtin_fmaf(s[prb][r + 1], a.c, nlse2[prb]));
+          float t0, t1;
+          if (ks == 0) fma2_mfma32_dp_first(dp[rb], vfq[0], gfr[rb][0], negD[rb], t0, t1, s[prb][r], s[prb][r + 1], a.c, nlse2[prb]);
+          else fma2_mfma32_dp(dp[rb], vfq[ks % 3], gfr[rb][ks], t0, t1, s[prb][r], s[prb][r + 1], a.c, nlse2[prb]);
+          s[prb][r] = fast_exp2(t0);
+          s[prb][r + 1] = fast_exp2(t1);
           asm volatile("" : "+v"(s[prb]));
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -350,14 +373,12 @@ burst_bwd_dq_kernel(BwdArgs a) {
       mfma_vgpr_fence(dp);     // the last dP^T MFMAs have written their accumulators
       // ---- slices 32..47: dQ^T(kt - 1) += K^T dS^T; dS^T = P^T o (dP^T - D) of score pair i of
       // tile kt rides along, and so do the DMA of tile kt + 3 and the first K reads of tile kt + 1
-      dq_phase(kl_prev, dsp, [&](int i) __attribute__((always_inline)) {
+      dq_phase(kl_prev, dsp, [&](int i, f32x16& acc, bf16x8 fa, bf16x8 fb) __attribute__((always_inline)) {
         const int prb = i >> 3, r = 2 * (i & 7), kg = r >> 3, t = r & 7;
-        // (the empty asm statements order this slice's arithmetic after the slice's MFMA, which is
-        // an asm statement too: the compiler would otherwise clump two MFMAs and two slices of
-        // vector work, and an in-order wavefront then stalls behind the second MFMA)
-        asm volatile("" : "+v"(dp[prb]));
-        float d0 = s[prb][r] * dp[prb][r];
-        float d1 = s[prb][r + 1] * dp[prb][r + 1];
+        // the slice's MFMA with the two dS products of score pair i right in front of it; the
+        // conversion follows (the empty asm statement below keeps it in this slice)
+        float d0, d1;
+        mul2_mfma32_acc(acc, fa, fb, d0, d1, s[prb][r], dp[prb][r], s[prb][r + 1], dp[prb][r + 1]);
         bf16x2 pk;
         pk[0] = (bf16)d0; pk[1] = (bf16)d1;
         unsigned pu = __builtin_bit_cast(unsigned, pk);
@@ -400,7 +421,9 @@ burst_bwd_dq_kernel(BwdArgs a) {
     // the dQ^T products of the last tile
     {
       const int kprev = (kslot == 0) ? DQ_KSLOTS - 1 : kslot - 1;
-      dq_phase(smem + kprev * DQ_TILE_BYTES, dsB, [&](int) __attribute__((always_inline)) {});
+      dq_phase(smem + kprev * DQ_TILE_BYTES, dsB, [&](int, f32x16& acc, bf16x8 fa, bf16x8 fb) __attribute__((always_inline)) {
+        mfma32_acc(acc, fa, fb);
+      });
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): no DMA may outlive the loop
   }
