@@ -42,6 +42,23 @@ struct FwdArgs {
   int group;             // query heads per key/value head (grouped-query attention; 1 = none)
 };
 
+
+// MFMA on an AGPR accumulator (see mfma32_acc) preceded, inside one asm statement, by two
+// independent vector instructions of the caller's own work: whatever register copies the compiler
+// puts before the statement are then at least two instructions away from the MFMA, which is what
+// the leading s_nop of mfma32_acc is for.  t0 = x0 * c + n, t1 = x1 * c + n ...
+__device__ __forceinline__ void fma2_mfma32_acc(f32x16& acc, bf16x8 a, bf16x8 b, float& t0, float& t1,
+                                                float x0, float x1, float c, float n) {
+  asm volatile("v_fma_f32 %1, %5, %7, %8\n\tv_fma_f32 %2, %6, %7, %8\n\tv_mfma_f32_32x32x16_bf16 %0, %3, %4, %0"
+               : "+a"(acc), "=&v"(t0), "=&v"(t1) : "v"(a), "v"(b), "v"(x0), "v"(x1), "s"(c), "v"(n));
+}
+// ... or m0 = max(m0, x00, x01), m1 = max(m1, x10, x11).
+__device__ __forceinline__ void max3x2_mfma32_acc(f32x16& acc, bf16x8 a, bf16x8 b, float& m0, float x00, float x01,
+                                                  float& m1, float x10, float x11) {
+  asm volatile("v_max3_f32 %1, %1, %5, %6\n\tv_max3_f32 %2, %2, %7, %8\n\tv_mfma_f32_32x32x16_bf16 %0, %3, %4, %0"
+               : "+a"(acc), "+v"(m0), "+v"(m1) : "v"(a), "v"(b), "v"(x00), "v"(x01), "v"(x10), "v"(x11));
+}
+
 // HBM -> LDS for one 64x128 bf16 tile (K or V) without staging registers.  One wave-wide
 // load writes 1024 contiguous LDS bytes (4 tile rows), lane i filling the 16 bytes at i*16;
 // which global granule a lane fetches is free, so lane i asks for the granule that the XOR
@@ -355,6 +372,16 @@ burst_fwd_mfma_kernel(FwdArgs a) {
     // 32 slices, 12 on the next 12, then the row maxima of the next tile.
     bf16x8 pf[2][4];       // P^T fragments (B operand): [row block][16-key group]
     bf16x4 vfq[PF + 1][2]; // V^T fragment halves
+    // second half of a pair whose exponents t0, t1 are already there
+    auto softmax_pair_tail = [&](int pidx, float t0, float t1) __attribute__((always_inline)) {
+      const int kg = pidx >> 3, srb = (pidx >> 2) & 1, t = (pidx & 3) * 2;
+      float p0 = fast_exp2(t0), p1 = fast_exp2(t1);
+      bf16x2 pk;
+      pk[0] = (bf16)p0; pk[1] = (bf16)p1;
+      lsum[srb] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, lsum[srb], false);
+      pf[srb][kg][t] = pk[0];
+      pf[srb][kg][t + 1] = pk[1];
+    };
     auto softmax_pair = [&](int pidx) __attribute__((always_inline)) {           // pidx = kg * 8 + rb * 4 + t / 2
       const int kg = pidx >> 3, srb = (pidx >> 2) & 1, t = (pidx & 3) * 2;
       const int skb = kg >> 1, r = 8 * (kg & 1) + t;
@@ -421,16 +448,24 @@ burst_fwd_mfma_kernel(FwdArgs a) {
         const bf16x4 va = vfq[pair % (PF + 1)][0], vb = vfq[pair % (PF + 1)][1];
         vf[0] = va[0]; vf[1] = va[1]; vf[2] = va[2]; vf[3] = va[3];
         vf[4] = vb[0]; vf[5] = vb[1]; vf[6] = vb[2]; vf[7] = vb[3];
-        mfma32_acc(o[rb][db], vf, pf[rb][kg]);
-      }
-      if (i < 12) softmax_pair(20 + i);
-      if (i >= 12 && i < 28) {                     // row maxima of the next tile: 16 slices x 4 scores
-        const int e = i - 12;                      // 0..15
-        const int kb2 = e >> 3, r = (e & 7) * 2;
-        // (one three-operand maximum per two scores; written out because the compiler otherwise
-        // pairs the scores first and needs three instructions for four of them)
-        asm("v_max3_f32 %0, %1, %2, %3" : "=v"(nmax0) : "v"(nmax0), "v"(sx[kb2][0][r]), "v"(sx[kb2][0][r + 1]));
-        asm("v_max3_f32 %0, %1, %2, %3" : "=v"(nmax1) : "v"(nmax1), "v"(sx[kb2][1][r]), "v"(sx[kb2][1][r + 1]));
+        // The MFMA of the slice with two vector instructions of the slice's own work in front
+        // of it inside the same asm statement (the exponents of a score pair, or the running row
+        // maxima of the next tile): they take the place of the two idle cycles an asm MFMA
+        // otherwise needs after whatever register copies the compiler put before the statement.
+        if (i < 12) {
+          const int pidx = 20 + i, pkg = pidx >> 3, srb = (pidx >> 2) & 1, t = (pidx & 3) * 2;
+          const int skb = pkg >> 1, r = 8 * (pkg & 1) + t;
+          float t0, t1;
+          fma2_mfma32_acc(o[rb][db], vf, pf[rb][kg], t0, t1, sc[skb][srb][r], sc[skb][srb][r + 1], a.c, nref[srb]);
+          softmax_pair_tail(pidx, t0, t1);
+        } else if (i < 28) {                       // row maxima of the next tile: 16 slices x 4 scores
+          const int e = i - 12;                    // 0..15
+          const int kb2 = e >> 3, r = (e & 7) * 2;
+          max3x2_mfma32_acc(o[rb][db], vf, pf[rb][kg], nmax0, sx[kb2][0][r], sx[kb2][0][r + 1],
+                            nmax1, sx[kb2][1][r], sx[kb2][1][r + 1]);
+        } else {
+          mfma32_acc(o[rb][db], vf, pf[rb][kg]);
+        }
       }
       if (i == 28) mx[0] = max_both_halves(nmax0) * a.c;
       if (i == 29) mx[1] = max_both_halves(nmax1) * a.c;
