@@ -240,8 +240,9 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     const long long wave_first_k = a.k_off + key0;
     const long long wave_last_k = wave_first_k + 31;
     const long long kpos = wave_first_k + lr;
-    constexpr int LEAD = 4, RING = LEAD + 2;       // A-operand reads run LEAD slices ahead
-    constexpr int TLEAD = 3, TRING = TLEAD + 1;    // transposed fragments run TLEAD slices ahead
+    constexpr int LEAD = 6, RING = LEAD + 2;       // A-operand reads run LEAD slices ahead
+    constexpr int TLEAD = 5, TRING = TLEAD + 1;    // transposed fragments run TLEAD slices ahead
+                                                   // (SQ counters showed 7 % of the wave time waiting for LDS at 4 / 3)
 
     // S and dP accumulators of the two row blocks.  They start at -lse/scale and -D of their
     // rows (register r of a block = row 8*(r/4) + 4h + r%4: four 128-bit broadcast reads per
