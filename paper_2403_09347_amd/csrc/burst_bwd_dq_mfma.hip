@@ -10,9 +10,9 @@
 // P is recomputed from the saved log-sum-exp; neither S, P nor dS is ever stored.
 //
 // One workgroup = 4 wavefronts = 256 query rows of one (batch, head); a wavefront owns 64
-// rows (their Q fragments stay in registers as B operands, their dO rows stay in LDS for the
-// whole kernel) and walks the chunk in tiles of 32 keys.  With S^T = K Q^T every lane owns one query row, so lse and D are
-// per-lane scalars, and the dS^T accumulators already have the B-operand layout that
+// rows (their Q fragments stay in VGPRs and their dO fragments in AGPRs as B operands for the
+// whole kernel) and walks the chunk in tiles of 32 keys.  With S^T = K Q^T every lane owns one
+// query row, so lse and D are per-lane scalars, and the dS^T accumulators already have the B-operand layout that
 // dQ^T += K^T dS^T needs (K^T comes through transposing LDS reads).  dQ^T accumulators are
 // pinned in AGPRs; K/V tiles are DMA-ed from HBM into LDS rings three tiles ahead, one barrier
 // per tile.  The 48 MFMAs of a tile run in three phases of 16, each carrying the vector work of
