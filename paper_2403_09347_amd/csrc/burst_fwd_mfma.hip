@@ -8,12 +8,14 @@
 //               one cross-half exchange; running max, sum and O rescale stay in registers
 //   O^T tile += V_tile^T P^T         (A = V^T through transposing LDS reads, B = P from the
 //               S^T accumulators, which already have the B-operand layout)
-// The wavefront runs at one wave per SIMD (512 registers), so matrix and vector work overlap
-// inside the wave: the loop is software-pipelined, the S^T MFMAs of tile j+1 are issued
-// together with the exp / sum / convert of tile j.  K and V tiles are DMA-ed from HBM straight
-// into LDS (buffer loads with the LDS modifier, no staging registers) into two rings of three
-// tiles each, two tiles ahead of their use (one barrier per tile).  The running max is only raised when a row's new maximum exceeds
-// it by more than 2^8 (P stays <= 2^8, exact in fp32/bf16 range), so the O rescale is rare.
+// The wavefront runs at one wave per SIMD (512 registers).  The loop is software-pipelined: the
+// S^T MFMAs of tile j+1 are issued in between the exp / sum / convert of tile j, so that neither
+// kind of instruction ever waits for a result of the other (measured: a wavefront's own matrix
+// and vector instructions do not execute concurrently, the gain is in the absent stalls).  K and
+// V tiles are DMA-ed from HBM straight into LDS (buffer loads with the LDS modifier, no staging
+// registers) into two rings of three tiles each, two tiles ahead of their use (one barrier per
+// tile).  The running max is only raised when a row's new maximum exceeds it by more than 2^8
+// (P stays <= 2^8, exact in fp32/bf16 range), so the O rescale is rare.
 // The chunk-local (O_ij, m_ij, l_ij) is merged into the state in HBM in the epilogue
 // (Alg. 1: m_new = max, rescale, add).  No S or P tile ever leaves registers.
 #include "burst_common.h"
@@ -364,9 +366,8 @@ burst_fwd_mfma_kernel(FwdArgs a) {
 
     // The 64 MFMAs of a tile (32 for S^T of the next tile, then 32 for O^T += V^T P^T) are
     // hand-interleaved with the vector work, one MFMA per slice, scheduling barriers between
-    // slices: the matrix and vector pipes of a SIMD only run concurrently when their
-    // instructions alternate in the wave's instruction stream, and a slice hides about seven
-    // plain vector instructions (an exp counts double).  Vector work per tile: 32 "pairs"
+    // slices, so that every MFMA finds its operands ready and every vector instruction its
+    // inputs, whatever the latencies.  Vector work per tile: 32 "pairs"
     // (two scores: 2 fma, 2 exp, convert to packed bf16, row sum by dot product with ones),
     // ordered by key group so that P is ready when its MFMA comes; 20 pairs ride on the first
     // 32 slices, 12 on the next 12, then the row maxima of the next tile.
