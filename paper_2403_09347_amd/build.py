@@ -11,7 +11,8 @@ SOURCES = ["burst_api.hip", "burst_elementwise.hip", "burst_generic.hip",
            "burst_materialized.hip", "burst_d64_mfma.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-ffast-math", "-fno-finite-math-only", "-fno-honor-nans",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-mllvm", "-amdgpu-mfma-vgpr-form=1", "-Wno-unused-command-line-argument"]
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1", "-Wno-unused-command-line-argument",
+         "-Wno-inline-asm"]   # the DMA helper names M0 as clobbered, which the compiler reports as a reserved register
 
 
 def build(verbose=True, jobs=8):
