@@ -496,3 +496,19 @@ def test_zigzag_rank_against_the_oracle(rank):
         check(f"dQ[h{h}]", np.concatenate([f64(x[0, h]) for x in dQs]), dQ_ref, "bf16")
         check(f"dK[h{h}]", np.concatenate([f64(x[0, h]) for x in dKs]), dK_ref, "bf16")
         check(f"dV[h{h}]", np.concatenate([f64(x[0, h]) for x in dVs]), dV_ref, "bf16")
+
+
+def test_autograd_wrapper_against_the_oracle():
+    """The differentiable torch call (chunk walk forward, Alg. 2 walk backward) on a causal, grouped-head
+    case: outputs and the gradients autograd hands back, against the fp64 oracle."""
+    from paper_2403_09347_amd.autograd import burst_attention
+    case = workloads.make_case(B=1, H=4, kv_heads=2, d=128, Nq=320, chunk_rows=[256, 100], dtype="bf16", seed=59,
+                               device=DEV, causal=True, q_off=120)
+    q = case["Q"].clone().requires_grad_(True)
+    ks = [k.clone().requires_grad_(True) for k in case["K"]]
+    vs = [v.clone().requires_grad_(True) for v in case["V"]]
+    O, lse = burst_attention(q, ks, vs, causal=True, q_off=120)
+    (O.float() * case["dO"].float()).sum().backward()
+    torch.cuda.synchronize()
+    assert q.grad.dtype == torch.bfloat16 and ks[0].grad.shape == case["K"][0].shape
+    compare_all_heads(case, "bf16", O.detach(), lse, q.grad.float(), [k.grad.float() for k in ks], [v.grad.float() for v in vs])
