@@ -276,8 +276,9 @@ def test_chunk_order_and_split_merge():
     assert float((lse2 - lse0).abs().max()) < 1e-5
 
 
-def test_checkpoint_resume_and_determinism_are_bitwise():
-    case = workloads.make_case(B=1, H=3, d=128, Nq=260, chunk_rows=[100, 130, 90], dtype="bf16", seed=41, device=DEV,
+@pytest.mark.parametrize("d", [128, 64])
+def test_checkpoint_resume_and_determinism_are_bitwise(d):
+    case = workloads.make_case(B=1, H=3, d=d, Nq=260, chunk_rows=[100, 130, 90], dtype="bf16", seed=41, device=DEV,
                                causal=True, q_off=60)
     _, (O0, lse0, dQ0, dKs0, dVs0) = run_case(case, "bf16")
     keep = [t.clone() for t in (O0, lse0, dQ0, *dKs0, *dVs0)]
@@ -512,3 +513,33 @@ def test_autograd_wrapper_against_the_oracle():
     torch.cuda.synchronize()
     assert q.grad.dtype == torch.bfloat16 and ks[0].grad.shape == case["K"][0].shape
     compare_all_heads(case, "bf16", O.detach(), lse, q.grad.float(), [k.grad.float() for k in ks], [v.grad.float() for v in vs])
+
+
+def test_c_abi_called_with_raw_pointers():
+    """The boundary without the binding's helpers: the shared library loaded with ctypes, a parameter
+    block laid out by hand, raw device addresses, the default stream; result against the oracle."""
+    import ctypes
+    import struct
+    lib = ctypes.CDLL(B.LIB_PATH)
+    Bt, H, Nq, Nc, d = 1, 2, 96, 160, 128
+    case = workloads.make_case(B=Bt, H=H, d=d, Nq=Nq, chunk_rows=[Nc], dtype="bf16", seed=83, device=DEV, causal=True,
+                               q_off=64)
+    # burst_params: 7 x int32, float, 3 x int64, pointer, 2 x int32  (72 bytes)
+    blob = struct.pack("<7if3qQ2i", Bt, H, Nq, Nc, d, 0, 1, case["scale"], 64, 0, 0, 0, 0, 0)
+    assert len(blob) == 72
+    params = ctypes.create_string_buffer(blob)
+    O_acc = torch.empty((Bt, H, Nq, d), device=DEV, dtype=torch.float32)
+    m = torch.empty((Bt, H, Nq), device=DEV, dtype=torch.float32)
+    l = torch.empty_like(m)
+    O = torch.empty((Bt, H, Nq, d), device=DEV, dtype=torch.bfloat16)
+    lse = torch.empty_like(m)
+    ptr = lambda t: ctypes.c_void_p(t.data_ptr())
+    for fn in (lib.burst_state_init, lib.burst_local_fwd, lib.burst_finalize):
+        fn.restype = ctypes.c_int
+    torch.cuda.synchronize()                       # the calls below go to the default stream (NULL)
+    assert lib.burst_state_init(ptr(O_acc), ptr(m), ptr(l), params, None) == 0
+    assert lib.burst_local_fwd(ptr(case["Q"]), ptr(case["K"][0]), ptr(case["V"][0]), ptr(O_acc), ptr(m), ptr(l),
+                               params, None) == 0
+    assert lib.burst_finalize(ptr(O_acc), ptr(m), ptr(l), ptr(O), ptr(lse), params, None) == 0
+    torch.cuda.synchronize()
+    compare_all_heads(case, "bf16", O, lse)
