@@ -228,3 +228,61 @@ class SpanWalk:
                                   w.params(Ks[j].shape[2], k_offs[j]), accumulate_dq=True, accumulate_dkv=(i > 0))
             dQs.append(dQ)
         return dQs, dKs, dVs
+
+
+class KeyPinnedBackward:
+    """Alg. 2 in the orientation the paper prints (Sec. 2.3; double buffer of Sec. 2.5 / Alg. 4): this
+    device keeps K_i, V_i and accumulates dK_i, dV_i while the query-side payloads
+    (Q_j, dO_j, D_j, lse_j, dQ_j) of all devices pass through.  Each payload is copied from its
+    source (another HBM allocation or pinned host memory: the stand-in for the ring neighbour)
+    into one of two receive buffers on a copy stream while the previous one is processed; its
+    dQ_j gets this device's contribution added and is copied back (the "send")."""
+
+    def __init__(self, K_i, V_i, scale, causal=False, k_off=0, window=0):
+        self.K, self.V = K_i, V_i
+        self.Bt, self.Hkv, self.Nc, self.d = K_i.shape
+        self.scale, self.causal, self.k_off, self.window = float(scale), bool(causal), int(k_off), int(window)
+        dev = K_i.device
+        self.dK = torch.empty(tuple(K_i.shape), device=dev, dtype=torch.float32)
+        self.dV = torch.empty_like(self.dK)
+        self.copy_stream = torch.cuda.Stream(device=dev)
+
+    def backward(self, payloads):
+        """payloads: list of dicts with Q, dO [B,H,Nq_j,d], D, lse [B,H,Nq_j], dQ [B,H,Nq_j,d] fp32
+        (read, updated and written back) and q_off.  Returns (dK_i, dV_i)."""
+        dev = self.K.device
+        main = torch.cuda.current_stream(dev)
+        n = len(payloads)
+        bufs = [None, None]
+        ready = [torch.cuda.Event() for _ in range(n)]
+        done = [torch.cuda.Event() for _ in range(n)]
+        names = ("Q", "dO", "D", "lse", "dQ")
+
+        def fetch(j):
+            with torch.cuda.stream(self.copy_stream):
+                if j >= 2:
+                    self.copy_stream.wait_event(done[j - 2])      # the buffer's previous payload went back
+                src = payloads[j]
+                if bufs[j % 2] is None or any(bufs[j % 2][k].shape != src[k].shape for k in names):
+                    bufs[j % 2] = {k: torch.empty(tuple(src[k].shape), device=dev, dtype=src[k].dtype) for k in names}
+                for k in names:
+                    bufs[j % 2][k].copy_(src[k], non_blocking=True)
+                ready[j].record(self.copy_stream)
+
+        self.copy_stream.wait_stream(main)
+        if n:
+            fetch(0)
+        for j in range(n):
+            if j + 1 < n:
+                fetch(j + 1)
+            main.wait_event(ready[j])
+            b = bufs[j % 2]
+            H, Nq = b["Q"].shape[1], b["Q"].shape[2]
+            p = B.params(self.Bt, H, Nq, self.Nc, self.d, b["Q"].dtype, self.scale, self.causal,
+                         payloads[j]["q_off"], self.k_off, self.window, None, 0, self.Hkv if self.Hkv != H else 0)
+            B.burst_local_bwd(b["Q"], self.K, self.V, None, b["dO"], b["lse"], b["D"], b["dQ"], self.dK, self.dV, p,
+                              accumulate_dq=True, accumulate_dkv=(j > 0))
+            payloads[j]["dQ"].copy_(b["dQ"], non_blocking=True)  # on the compute stream, after the kernels
+            done[j].record(main)
+        return self.dK, self.dV
+
