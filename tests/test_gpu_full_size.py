@@ -200,3 +200,13 @@ def test_llama7b_32k_G8_block_sparse_band_plus_global():
         assert hidden.any()
         assert torch.count_nonzero(dKs[j][0, :, torch.from_numpy(hidden).to(DEV)]) == 0
         assert torch.count_nonzero(dVs[j][0, :, torch.from_numpy(hidden).to(DEV)]) == 0
+
+
+def test_d64_heads_at_the_benchmark_sequence_shape():
+    """The d = 64 kernels at 32 heads, 4096 rows against 4 chunks of 4096 keys, causal at the last rank:
+    sampled rows of several heads, identities on another."""
+    w = workloads.Workload("d64_16k_G4_rank3_causal", 1, 32, 64, 4096, 4, 4096, "bf16", True, 3 * 4096, 1006)
+    inp, k_offs, walk, O, lse, dQ, dKs, dVs = run_workload(w)
+    for h in (0, 14, 31):
+        check_sampled_rows(w, inp, h, O, lse, dQ)
+    check_identities(w, inp, 7, dQ, dKs, dVs)
