@@ -75,13 +75,16 @@ typedef struct burst_params {
   int64_t window;   /* 0 = none; w > 0: keys at positions <= query position - w are hidden */
   const uint8_t* block_mask; /* NULL = none; else DEVICE pointer to a row-major byte matrix
                               * [ceil(Nq / block)][ceil(Nc / block)] for THIS query slice x chunk
-                              * pair, shared by every batch entry and head: entry (i, j) = 0 hides
+                              * pair (one for all heads, or one per (batch, head), see
+                              * block_mask_stride): entry (i, j) = 0 hides
                               * keys j*block .. of the chunk from query rows i*block .. of the slice */
   int32_t block;    /* edge of a mask block in rows = keys; a positive multiple of 64 when
                      * block_mask != NULL, ignored otherwise */
   int32_t kv_heads; /* 0 or H: K, V, dK, dV have H heads.  Otherwise (grouped-query attention) they
                      * have kv_heads heads, [B, kv_heads, Nc, d]; H must be a multiple of kv_heads and
                      * query head h uses key/value head h / (H / kv_heads); dK, dV sum over the group */
+  int64_t block_mask_stride; /* bytes from one (batch, query head)'s flag matrix to the next, B*H
+                     * matrices in all; 0 = one matrix shared by every batch entry and head */
 } burst_params;
 
 /* Alg. 1, initialisation: O_acc = 0, l = 0, m = -inf.

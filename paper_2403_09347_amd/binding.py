@@ -28,7 +28,7 @@ class BurstParams(ctypes.Structure):
         ("d", ctypes.c_int32), ("dtype", ctypes.c_int32), ("causal", ctypes.c_int32),
         ("scale", ctypes.c_float), ("q_off", ctypes.c_int64), ("k_off", ctypes.c_int64),
         ("window", ctypes.c_int64), ("block_mask", ctypes.c_void_p), ("block", ctypes.c_int32),
-        ("kv_heads", ctypes.c_int32),
+        ("kv_heads", ctypes.c_int32), ("block_mask_stride", ctypes.c_int64),
     ]
 
 
@@ -89,18 +89,25 @@ def version():
 
 def params(B, H, Nq, Nc, d, dtype, scale, causal=False, q_off=0, k_off=0, window=0, block_mask=None, block=0,
            kv_heads=0):
-    """block_mask: a contiguous uint8 device tensor [ceil(Nq/block), ceil(Nc/block)] (or None); the
-    caller keeps it alive and unchanged until the kernels that use these parameters have run."""
+    """block_mask: a contiguous uint8 device tensor [ceil(Nq/block), ceil(Nc/block)] shared by all
+    heads, or [B, H, ceil(Nq/block), ceil(Nc/block)] with one matrix per (batch, query head) (or
+    None); the caller keeps it alive and unchanged until the kernels that use these parameters
+    have run."""
     code = {torch.bfloat16: BURST_BF16, torch.float32: BURST_F32, "bf16": BURST_BF16, "f32": BURST_F32}.get(dtype, dtype)
-    ptr = None
+    ptr, stride = None, 0
     if block_mask is not None:
         if block_mask.dtype != torch.uint8 or not block_mask.is_cuda or not block_mask.is_contiguous():
             raise ValueError("block_mask: contiguous uint8 device tensor expected")
-        if block <= 0 or tuple(block_mask.shape) != (-(-Nq // block), -(-Nc // block)):
-            raise ValueError("block_mask: shape must be [ceil(Nq/block), ceil(Nc/block)]")
+        if block <= 0:
+            raise ValueError("block_mask needs block > 0")
+        one = (-(-Nq // block), -(-Nc // block))
+        if tuple(block_mask.shape) == (B, H) + one:
+            stride = one[0] * one[1]
+        elif tuple(block_mask.shape) != one:
+            raise ValueError("block_mask: shape must be [ceil(Nq/block), ceil(Nc/block)], alone or after [B, H]")
         ptr = block_mask.data_ptr()
     return BurstParams(B, H, Nq, Nc, d, code, 1 if causal else 0, scale, q_off, k_off, window, ptr,
-                       block if block_mask is not None else 0, kv_heads)
+                       block if block_mask is not None else 0, kv_heads, stride)
 
 
 def _ptr(t):

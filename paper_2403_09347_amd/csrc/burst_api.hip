@@ -72,10 +72,14 @@ int check_params(const burst_params* p, KParams* k) {
     if (p->kv_heads < 0 || p->H % p->kv_heads != 0) return BURST_ERR_SHAPE;
     k->group = p->H / p->kv_heads;
   }
-  k->bmask = nullptr; k->bsize = 64; k->bpitch = 0;
+  k->bmask = nullptr; k->bsize = 64; k->bpitch = 0; k->bhstride = 0;
   if (p->block_mask != nullptr) {
     if (p->block <= 0 || p->block % 64 != 0) return BURST_ERR_SHAPE;
     k->bmask = p->block_mask; k->bsize = p->block; k->bpitch = (p->Nc + p->block - 1) / p->block;
+    k->bhstride = p->block_mask_stride;
+    // one matrix per (batch, head): they must not overlap
+    const long long matrix = (long long)((p->Nq + p->block - 1) / p->block) * k->bpitch;
+    if (k->bhstride != 0 && k->bhstride < matrix) return BURST_ERR_SHAPE;
   }
   return BURST_OK;
 }
@@ -344,6 +348,6 @@ const char* burst_strerror(int status) {
   }
 }
 
-int burst_version(void) { return 103; }
+int burst_version(void) { return 104; }
 
 }  // extern "C"

@@ -16,6 +16,7 @@ struct BwdArgs {
   long long window;      // 0 = none; else keys at positions <= query position - window are hidden
   const uint8_t* bmask;  // block flags [ceil(Nq / bsize)][bpitch], nullptr = none (paper Sec. 2.6)
   int bsize, bpitch;     // bsize: a multiple of 64
+  long long bhstride;    // bytes between the flag matrices of consecutive query heads (0 = shared)
   int group;             // query heads per key/value head (grouped-query attention; 1 = none)
   int blocks_per_head;
   int acc_dq, acc_dkv;
@@ -30,7 +31,7 @@ inline BwdArgs make_bwd_args(const KParams& p, const void* Q, const void* K, con
   a.Nq = p.Nq; a.Nc = p.Nc; a.H = p.B * p.H;
   a.causal = p.causal; a.c = p.scale * kLog2e; a.scale = p.scale;
   a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
-  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.group = p.group;
+  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.bhstride = p.bhstride; a.group = p.group;
   a.blocks_per_head = 0; a.acc_dq = acc_dq; a.acc_dkv = acc_dkv;
   return a;
 }

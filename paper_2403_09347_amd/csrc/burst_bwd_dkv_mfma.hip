@@ -106,7 +106,7 @@ burst_bwd_dkv_kernel(BwdArgs a) {
             if (a.bmask == nullptr) {
               bits = 0xf;
             } else {
-              const uint8_t* mrow = a.bmask + (size_t)((t * DKV_BR) / a.bsize) * a.bpitch;
+              const uint8_t* mrow = a.bmask + (size_t)(head * group + g) * a.bhstride + (size_t)((t * DKV_BR) / a.bsize) * a.bpitch;
 #pragma unroll
               for (int ww = 0; ww < 4; ww++) {
                 const int k0 = key_wg + ww * 32;

@@ -141,6 +141,7 @@ burst_bwd_dq_kernel(BwdArgs a) {
   if constexpr (SPARSE) {
     const int end_tile = (Nc + DQ_BC - 1) / DQ_BC;               // a tile past the chunk
     if (w == 0) {
+      const uint8_t* const bm = a.bmask + (size_t)head * a.bhstride;
       int n = 0;
       for (int base = t_lo; base < ntiles; base += 64) {
         const int kt = base + lane;
@@ -150,7 +151,7 @@ burst_bwd_dq_kernel(BwdArgs a) {
 #pragma unroll
           for (int ww = 0; ww < 4; ww++) {
             const int row0 = qb * DQ_BR + ww * 64;
-            if (row0 < a.Nq && a.bmask[(size_t)(row0 / a.bsize) * a.bpitch + col] != 0) bits |= 1 << ww;
+            if (row0 < a.Nq && bm[(size_t)(row0 / a.bsize) * a.bpitch + col] != 0) bits |= 1 << ww;
           }
         }
         const unsigned long long bal = __builtin_amdgcn_ballot_w64(bits != 0);

@@ -28,6 +28,7 @@ struct KParams {
   long long window;      // 0 = none
   const uint8_t* bmask;  // block mask [ceil(Nq/bsize)][bpitch] (nullptr = none), bpitch = ceil(Nc/bsize)
   int bsize, bpitch;
+  long long bhstride;    // bytes between the flag matrices of consecutive (batch, query head)s; 0 = shared
   int group;             // query heads per key/value head (1 = every head has its own K, V)
 };
 

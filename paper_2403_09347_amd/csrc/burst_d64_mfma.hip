@@ -36,6 +36,7 @@ struct FwdArgsLite {
   float c;               // scale * log2(e)
   long long q_off, k_off, window;
   const uint8_t* bmask; int bsize, bpitch;       // block flags (nullptr = none)
+  long long bhstride;                            // bytes between heads' flag matrices (0 = shared)
   int blocks_per_head;
 };
 
@@ -149,7 +150,7 @@ burst_fwd_d64_kernel(FwdArgsLite a) {
 #pragma unroll
       for (int ww = 0; ww < 4; ww++) {
         const int row0 = qb * SF_BR + ww * 32;
-        if (row0 < a.Nq && a.bmask[(size_t)(row0 / a.bsize) * a.bpitch + (t * SF_BC) / a.bsize] != 0) bits |= 1 << ww;
+        if (row0 < a.Nq && (a.bmask + (size_t)head * a.bhstride)[(size_t)(row0 / a.bsize) * a.bpitch + (t * SF_BC) / a.bsize] != 0) bits |= 1 << ww;
       }
       return bits;
     });
@@ -353,7 +354,7 @@ burst_bwd_dq_d64_kernel(BwdArgs a) {
 #pragma unroll
       for (int ww = 0; ww < 4; ww++) {
         const int row0 = qb * SQ_BR + ww * 32;
-        if (row0 < a.Nq && a.bmask[(size_t)(row0 / a.bsize) * a.bpitch + (t * SQ_BC) / a.bsize] != 0) bits |= 1 << ww;
+        if (row0 < a.Nq && (a.bmask + (size_t)head * a.bhstride)[(size_t)(row0 / a.bsize) * a.bpitch + (t * SQ_BC) / a.bsize] != 0) bits |= 1 << ww;
       }
       return bits;
     });
@@ -505,8 +506,9 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
   int nwalk = per_head * a.group;
   if constexpr (SPARSE) {                          // entries count tiles over all heads of the group
     nwalk = s_build_list(s_list, w, lane, 0, nwalk, 0, [&](int n) {
+      const int g = n / (per_head > 0 ? per_head : 1);
       const int t = t_begin + n % (per_head > 0 ? per_head : 1);
-      const uint8_t* mrow = a.bmask + (size_t)((t * SK_BR) / a.bsize) * a.bpitch;
+      const uint8_t* mrow = a.bmask + (size_t)(kvhead * a.group + g) * a.bhstride + (size_t)((t * SK_BR) / a.bsize) * a.bpitch;
       int bits = 0;
 #pragma unroll
       for (int ww = 0; ww < 4; ww++) {
@@ -672,7 +674,7 @@ int launch_fwd_d64(const KParams& p, const void* Q, const void* K, const void* V
   a.Nq = p.Nq; a.Nc = p.Nc; a.H = p.B * p.H; a.group = p.group;
   a.causal = p.causal; a.c = p.scale * kLog2e;
   a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
-  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch;
+  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.bhstride = p.bhstride;
   a.blocks_per_head = (p.Nq + SF_BR - 1) / SF_BR;
   const long long nb = (long long)((a.H + 7) / 8 * 8) * a.blocks_per_head;
   if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;

@@ -41,6 +41,7 @@ struct FwdArgs {
   int q_blocks;          // ceil(Nq / FWD_BR)
   const uint8_t* bmask;  // block flags [ceil(Nq / bsize)][bpitch], nullptr = none (paper Sec. 2.6)
   int bsize, bpitch;     // bsize: a multiple of 64, so a wavefront's 64 rows and a key tile lie in one block
+  long long bhstride;    // bytes between the flag matrices of consecutive heads (0 = shared)
   int group;             // query heads per key/value head (grouped-query attention; 1 = none)
 };
 
@@ -167,6 +168,7 @@ burst_fwd_mfma_kernel(FwdArgs a) {
   if constexpr (SPARSE) {
     const int end_tile = (Nc + FWD_BC - 1) / FWD_BC;             // a tile past the chunk
     if (w == 0) {
+      const uint8_t* const bm = a.bmask + (size_t)head * a.bhstride;
       int n = 0;
       for (int base = t_lo; base < ntiles; base += 64) {
         const int kt = base + lane;
@@ -176,7 +178,7 @@ burst_fwd_mfma_kernel(FwdArgs a) {
 #pragma unroll
           for (int ww = 0; ww < 4; ww++) {
             const int row0 = qb * FWD_BR + ww * 64;
-            if (row0 < a.Nq && a.bmask[(size_t)(row0 / a.bsize) * a.bpitch + col] != 0) bits |= 1 << ww;
+            if (row0 < a.Nq && bm[(size_t)(row0 / a.bsize) * a.bpitch + col] != 0) bits |= 1 << ww;
           }
         }
         const unsigned long long bal = __builtin_amdgcn_ballot_w64(bits != 0);
@@ -537,7 +539,7 @@ int launch_fwd_mfma(const KParams& p, const void* Q, const void* K, const void* 
   a.c = p.scale * kLog2e;
   a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
   a.q_blocks = (p.Nq + FWD_BR - 1) / FWD_BR;
-  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.group = p.group;
+  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.bhstride = p.bhstride; a.group = p.group;
   int heads8 = ((a.H + 7) / 8) * 8;                // pad the head count to a multiple of 8 ids
   long long nblocks = (long long)heads8 * a.q_blocks;
   if (nblocks > 0x7fffffffLL) return BURST_ERR_SHAPE;

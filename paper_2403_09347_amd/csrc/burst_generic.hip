@@ -19,16 +19,17 @@ struct GenArgs {
   long long q_off, k_off;
   long long window;
   const uint8_t* bmask; int bsize, bpitch;        // block mask (nullptr = none)
+  long long bhstride;                             // bytes between heads' flag matrices (0 = shared)
   int group;                                      // query heads per key/value head
   int acc_dq, acc_dkv;
 };
 
 // Visibility of key `key` of the chunk from query row `row` of the slice (both in range).
-__device__ __forceinline__ bool visible(const GenArgs& a, int row, int key) {
+__device__ __forceinline__ bool visible(const GenArgs& a, int head, int row, int key) {
   const long long qpos = a.q_off + row, kpos = a.k_off + key;
   if (a.causal && kpos > qpos) return false;
   if (a.window != 0 && kpos <= qpos - a.window) return false;
-  if (a.bmask != nullptr && a.bmask[(size_t)(row / a.bsize) * a.bpitch + key / a.bsize] == 0) return false;
+  if (a.bmask != nullptr && a.bmask[(size_t)head * a.bhstride + (size_t)(row / a.bsize) * a.bpitch + key / a.bsize] == 0) return false;
   return true;
 }
 
@@ -64,7 +65,7 @@ fwd_generic_kernel(GenArgs a) {
   float m_run = BURST_NEG_INF, l_run = 0.f, o0 = 0.f, o1 = 0.f;   // dims lane and lane + 64
   for (int k0 = 0; k0 < a.Nc; k0 += 64) {
     int key = k0 + lane;
-    bool vis = key < a.Nc && visible(a, row, key);
+    bool vis = key < a.Nc && visible(a, head, row, key);
     float s = BURST_NEG_INF;
     if (vis) {
       float acc = 0.f;
@@ -129,7 +130,7 @@ bwd_dq_generic_kernel(GenArgs a) {
   float q0 = 0.f, q1 = 0.f;
   for (int k0 = 0; k0 < a.Nc; k0 += 64) {
     int key = k0 + lane;
-    bool vis = key < a.Nc && lse != BURST_NEG_INF && visible(a, row, key);
+    bool vis = key < a.Nc && lse != BURST_NEG_INF && visible(a, head, row, key);
     float ds = 0.f;
     if (vis) {
       float sa = 0.f, dp = 0.f;
@@ -184,7 +185,7 @@ bwd_dkv_generic_kernel(GenArgs a) {
   for (int r0 = 0; r0 < a.Nq; r0 += 64) {
     int row = r0 + lane;
     float p = 0.f, ds = 0.f;
-    if (row < a.Nq && visible(a, row, key)) {
+    if (row < a.Nq && visible(a, head, row, key)) {
       float lse = lseh[row];
       if (lse != BURST_NEG_INF) {
         float sa = 0.f, dp = 0.f;
@@ -224,7 +225,7 @@ static GenArgs make_args(const KParams& p) {
   GenArgs a = {};
   a.Nq = p.Nq; a.Nc = p.Nc; a.d = p.d; a.BH = p.B * p.H;
   a.causal = p.causal; a.scale = p.scale; a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
-  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.group = p.group;
+  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.bhstride = p.bhstride; a.group = p.group;
   return a;
 }
 static inline int launch_status() { return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH; }

@@ -22,6 +22,7 @@ struct MatArgs {
   float scale;
   long long q_off, k_off, window;
   const uint8_t* bmask; int bsize, bpitch;   // block mask (nullptr = none)
+  long long bhstride;                        // bytes between heads' flag matrices (0 = shared)
   int group;                                 // query heads per key/value head
 };
 
@@ -107,7 +108,7 @@ mat_softmax_kernel(MatArgs a) {
   if (a.window > 0) lo = qpos - a.window + 1 - a.k_off > 0 ? qpos - a.window + 1 - a.k_off : 0;
   if (hi < 0) hi = 0;
   if (lo > hi) lo = hi;
-  const uint8_t* brow = a.bmask == nullptr ? nullptr : a.bmask + (size_t)(r / a.bsize) * a.bpitch;
+  const uint8_t* brow = a.bmask == nullptr ? nullptr : a.bmask + (size_t)(row / a.Nq) * a.bhstride + (size_t)(r / a.bsize) * a.bpitch;
   auto seen = [&](long long c) { return c >= lo && c < hi && (brow == nullptr || brow[c / a.bsize] != 0); };
   float mx = BURST_NEG_INF;
   for (long long c = lo + lane; c < hi; c += 64)
@@ -294,7 +295,7 @@ int launch_fwd_materialized(const KParams& p, int dtype, bool mfma, const void* 
   a.Q = Q; a.K = K; a.V = V; a.O_acc = O_acc; a.m = m; a.l = l;
   a.Nq = p.Nq; a.Nc = p.Nc; a.Ncp = (p.Nc + 7) & ~7; a.d = p.d; a.BH = (long long)p.B * p.H;
   a.causal = p.causal; a.scale = p.scale; a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
-  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.group = p.group;
+  a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.bhstride = p.bhstride; a.group = p.group;
   const size_t rows = (size_t)a.BH * a.Nq;
   const size_t esize = dtype == BURST_BF16 ? 2 : 4;
   char* ws = (char*)workspace;

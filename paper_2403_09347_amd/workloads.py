@@ -149,11 +149,13 @@ def block_flags(n_row_blocks, n_col_blocks, kind="random", density=0.4, seed=0, 
 
 
 def make_case(B, H, d, Nq, chunk_rows, dtype="bf16", seed=0, device="cpu",
-              causal=False, q_off=0, k_offs=None, window=0, block=0, pattern="random", density=0.4, kv_heads=0):
+              causal=False, q_off=0, k_offs=None, window=0, block=0, pattern="random", density=0.4, kv_heads=0,
+              per_head_flags=False):
     """Free-form case for parity tests: `chunk_rows` lists the rows of each chunk.  With
     block > 0 the case carries one block-flag matrix per chunk ("flags": numpy, "masks": the
     same on the device), blocks counted from the first row of the slice / of each chunk.  With
-    kv_heads > 0 the K / V chunks have that many heads (grouped-query attention)."""
+    kv_heads > 0 the K / V chunks have that many heads (grouped-query attention).  With
+    per_head_flags every (batch, query head) has a flag matrix of its own: [B, H, blocks, blocks]."""
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)
     dt = torch.bfloat16 if dtype == "bf16" else torch.float32
@@ -174,8 +176,15 @@ def make_case(B, H, d, Nq, chunk_rows, dtype="bf16", seed=0, device="cpu",
     if block:
         nrb = -(-Nq // block)
         case["block"] = block
-        case["flags"] = [block_flags(nrb, -(-n // block), pattern, density, seed + 101 * j,
-                                     diag_shift=(q_off - k_offs[j]) // block if pattern != "random" else 0)
-                         for j, n in enumerate(chunk_rows)]
+        import numpy as np
+
+        def one(j, n, bh):
+            return block_flags(nrb, -(-n // block), pattern, density, seed + 101 * j + 7919 * bh,
+                               diag_shift=(q_off - k_offs[j]) // block if pattern != "random" else 0)
+        if per_head_flags:
+            case["flags"] = [np.stack([one(j, n, bh) for bh in range(B * H)]).reshape(B, H, nrb, -1)
+                             for j, n in enumerate(chunk_rows)]
+        else:
+            case["flags"] = [one(j, n, 0) for j, n in enumerate(chunk_rows)]
         case["masks"] = [torch.from_numpy(f).to(device).contiguous() for f in case["flags"]]
     return case

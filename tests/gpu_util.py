@@ -36,12 +36,13 @@ def head_inputs(case, b, h, rows=None):
     return Q, K, V, dO, qp, positions(case)
 
 
-def pattern_of(case, rows=None):
-    """Boolean [Nq, total keys] expansion of the case's per-chunk block flags (None if it has none)."""
+def pattern_of(case, rows=None, b=0, h=0):
+    """Boolean [Nq, total keys] expansion of the case's per-chunk block flags (None if it has none);
+    of batch entry b, query head h when the case carries one flag matrix per head."""
     if "flags" not in case:
         return None
     nq = case["Q"].shape[2]
-    pat = np.concatenate([orc.block_visibility(nq, k.shape[2], f, case["block"])
+    pat = np.concatenate([orc.block_visibility(nq, k.shape[2], f[b, h] if f.ndim == 4 else f, case["block"])
                           for f, k in zip(case["flags"], case["K"])], axis=1)
     return pat if rows is None else pat[rows]
 
@@ -74,7 +75,7 @@ def compare_all_heads(case, dtype, O, lse, dQ=None, dKs=None, dVs=None, heads=No
         dK_sum = dV_sum = None                      # grouped heads: dK, dV of a key/value head sum over its group
         for h in (range(H) if heads is None else heads):
             Q, K, V, dO, qp, kp = head_inputs(case, b, h)
-            pat = pattern_of(case)
+            pat = pattern_of(case, b=b, h=h)
             O_ref, lse_ref = orc.full_forward(Q, K, V, case["scale"], case["causal"], qp, kp,
                                               window=case.get("window", 0), pattern=pat)
             check(f"O[{b},{h}]", f64(O[b, h]), O_ref, dtype)

@@ -42,8 +42,8 @@ def test_binding_lists_the_same_exports():
     assert sorted(binding.EXPORTS) == declared_symbols()
     p = binding.params(1, 2, 3, 4, 128, "bf16", 0.5, True, 7, 9)
     assert (p.B, p.H, p.Nq, p.Nc, p.d, p.dtype, p.causal, p.q_off, p.k_off) == (1, 2, 3, 4, 128, 0, 1, 7, 9)
-    assert ctypes.sizeof(p) == 72
-    assert (p.block_mask, p.block, p.kv_heads) == (None, 0, 0)
+    assert ctypes.sizeof(p) == 80
+    assert (p.block_mask, p.block, p.kv_heads, p.block_mask_stride) == (None, 0, 0, 0)
 
 
 def test_argument_validation_without_gpu():
@@ -61,6 +61,9 @@ def test_argument_validation_without_gpu():
     assert lib.burst_local_fwd(null, null, null, null, null, null, ctypes.byref(bad), null) == -3
     bad = binding.params(1, 1, 16, 16, 128, "bf16", 0.5)
     bad.block_mask, bad.block = 4096, 48                        # block edge must be a multiple of 64
+    assert lib.burst_local_fwd(null, null, null, null, null, null, ctypes.byref(bad), null) == -3
+    bad = binding.params(1, 2, 128, 128, 128, "bf16", 0.5)
+    bad.block_mask, bad.block, bad.block_mask_stride = 4096, 64, 3   # per-head matrices (2 x 2 bytes) would overlap
     assert lib.burst_local_fwd(null, null, null, null, null, null, ctypes.byref(bad), null) == -3
     bad = binding.params(1, 6, 16, 16, 128, "bf16", 0.5, kv_heads=4)   # H must be a multiple of kv_heads
     assert lib.burst_local_fwd(null, null, null, null, null, null, ctypes.byref(bad), null) == -3

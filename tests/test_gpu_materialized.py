@@ -26,6 +26,8 @@ CASES = [
     ("bf16", dict(B=1, H=1, d=128, Nq=260, chunk_rows=[260], block=128, pattern="band_global", causal=True)),
     ("bf16", dict(B=1, H=4, kv_heads=2, d=128, Nq=200, chunk_rows=[150, 90], causal=True, q_off=100)),   # grouped heads
     ("f32", dict(B=1, H=4, kv_heads=1, d=32, Nq=50, chunk_rows=[70])),
+    ("bf16", dict(B=2, H=2, d=128, Nq=200, chunk_rows=[150, 90], block=64, pattern="random", density=0.5,
+                  per_head_flags=True)),
 ]
 
 

@@ -67,6 +67,13 @@ SPARSE_CASES = [
     dict(B=1, H=1, d=128, Nq=520, chunk_rows=[300, 300, 300], block=64, pattern="random", density=0.6,
          causal=True, q_off=380, window=200),
     dict(B=1, H=2, d=128, Nq=200, chunk_rows=[256, 256], block=64, pattern="random", density=0.0),   # nothing visible
+    # one flag matrix per (batch, head)
+    dict(B=2, H=3, d=128, Nq=517, chunk_rows=[256, 390], block=64, pattern="random", density=0.5, per_head_flags=True),
+    dict(B=1, H=4, d=128, Nq=512, chunk_rows=[300, 300], block=128, pattern="random", density=0.4, per_head_flags=True,
+         kv_heads=2, causal=True, q_off=200),
+    dict(B=1, H=4, d=64, Nq=300, chunk_rows=[200, 331], block=64, pattern="random", density=0.5, per_head_flags=True),
+    dict(B=2, H=4, d=64, Nq=256, chunk_rows=[256, 130], block=64, pattern="random", density=0.4, per_head_flags=True,
+         kv_heads=1, causal=True, q_off=130),
 ]
 
 
@@ -79,6 +86,8 @@ def test_bf16_block_sparse_forward_backward(spec):
 
 @pytest.mark.parametrize("dtype,spec", [
     ("f32", dict(B=1, H=2, d=32, Nq=150, chunk_rows=[100, 90], block=64, pattern="random", density=0.5)),
+    ("f32", dict(B=2, H=4, d=32, Nq=150, chunk_rows=[100, 90], block=64, pattern="random", density=0.5,
+                 per_head_flags=True, kv_heads=2)),
     ("bf16", dict(B=1, H=2, d=64, Nq=130, chunk_rows=[200], block=64, pattern="band_global", causal=True, q_off=70)),
 ])
 def test_generic_kernels_block_sparse(dtype, spec):

@@ -104,6 +104,12 @@ def test_cases_with_block_flags_and_fewer_kv_heads():
     again = workloads.make_case(B=1, H=4, d=16, Nq=100, chunk_rows=[70, 130], dtype="f32", seed=3,
                                 block=64, pattern="random", density=0.5, kv_heads=2)
     assert all(np.array_equal(a, b) for a, b in zip(case["flags"], again["flags"]))
+    per_head = workloads.make_case(B=2, H=4, d=16, Nq=100, chunk_rows=[70, 130], dtype="f32", seed=3,
+                                   block=64, pattern="random", density=0.5, kv_heads=2, per_head_flags=True)
+    assert [f.shape for f in per_head["flags"]] == [(2, 4, 2, 2), (2, 4, 2, 3)]
+    assert np.array_equal(per_head["flags"][0][0, 0], case["flags"][0])         # head 0 keeps the shared pattern
+    assert not np.array_equal(per_head["flags"][1][0, 1], per_head["flags"][1][1, 3])
+    assert per_head["masks"][1].shape == (2, 4, 2, 3)
 
 
 def test_binding_rejects_host_masks_and_wrong_shapes():
