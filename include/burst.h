@@ -13,9 +13,11 @@
  *     never frees caller memory and never synchronises the stream; every call
  *     only enqueues kernels on `stream` (a hipStream_t passed as void*, NULL =
  *     the default stream).  Pointers must be 16-byte aligned.
- *   - Tensors are dense, row-major [B, H, rows, d] (d contiguous); per-row
- *     vectors (m, l, lse, D) are [B, H, rows].  K, V, dK, dV may have fewer heads
- *     than Q (burst_params.kv_heads; not in the paper).
+ *   - Tensors are indexed [B, H, rows, d] with d contiguous; per-row vectors
+ *     (m, l, lse, D) are [B, H, rows].  fp32 tensors are always dense in that
+ *     order; the tensors of type `dtype` are too unless burst_params.q_strides /
+ *     kv_strides say otherwise.  K, V, dK, dV may have fewer heads than Q
+ *     (burst_params.kv_heads; not in the paper).
  *   - Q, K, V, O, dO have element type `dtype` (bf16 or fp32).  The running
  *     state, lse, D and all gradients are fp32.
  *   - Scores are S = scale * Q K^T (Eq. 1 has scale = 1/sqrt(d); Alg. 1/2 omit
@@ -85,6 +87,12 @@ typedef struct burst_params {
                      * query head h uses key/value head h / (H / kv_heads); dK, dV sum over the group */
   int64_t block_mask_stride; /* bytes from one (batch, query head)'s flag matrix to the next, B*H
                      * matrices in all; 0 = one matrix shared by every batch entry and head */
+  int64_t q_strides[3];  /* element strides {batch, head, row} of Q, dO and O (input and output);
+                     * all zero = contiguous [B, H, Nq, d].  The last dimension is always contiguous.
+                     * E.g. {Nq*H*d, d, H*d} addresses sequence-major [B, Nq, H, d] tensors (the
+                     * layout of Sec. 2.2's backward messages) without a copy.  Row stride >= d, each
+                     * stride a multiple of 16 bytes, none negative. */
+  int64_t kv_strides[3]; /* the same for K_chunk and V_chunk ({batch, head, row}; kv_heads heads) */
 } burst_params;
 
 /* Alg. 1, initialisation: O_acc = 0, l = 0, m = -inf.

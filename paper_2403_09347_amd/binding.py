@@ -29,6 +29,7 @@ class BurstParams(ctypes.Structure):
         ("scale", ctypes.c_float), ("q_off", ctypes.c_int64), ("k_off", ctypes.c_int64),
         ("window", ctypes.c_int64), ("block_mask", ctypes.c_void_p), ("block", ctypes.c_int32),
         ("kv_heads", ctypes.c_int32), ("block_mask_stride", ctypes.c_int64),
+        ("q_strides", ctypes.c_int64 * 3), ("kv_strides", ctypes.c_int64 * 3),
     ]
 
 
@@ -87,12 +88,24 @@ def version():
     return load().burst_version()
 
 
+def strides_of(t):
+    """(batch, head, row) element strides of a [B, H, rows, d] tensor whose last dimension is
+    contiguous, for params(); None if the tensor is contiguous.  Dimensions of size 1 (whose
+    stride addresses nothing) are given the row length."""
+    if t.dim() != 4 or (t.shape[3] > 1 and t.stride(3) != 1):
+        raise ValueError("a [B, H, rows, d] tensor with a contiguous last dimension expected")
+    if t.is_contiguous():
+        return None
+    return tuple(int(t.stride(i)) if t.shape[i] > 1 else int(t.shape[3]) for i in range(3))
+
+
 def params(B, H, Nq, Nc, d, dtype, scale, causal=False, q_off=0, k_off=0, window=0, block_mask=None, block=0,
-           kv_heads=0):
+           kv_heads=0, q_strides=None, kv_strides=None):
     """block_mask: a contiguous uint8 device tensor [ceil(Nq/block), ceil(Nc/block)] shared by all
     heads, or [B, H, ceil(Nq/block), ceil(Nc/block)] with one matrix per (batch, query head) (or
     None); the caller keeps it alive and unchanged until the kernels that use these parameters
-    have run."""
+    have run.  q_strides / kv_strides: (batch, head, row) element strides of Q, dO, O and of
+    K, V (see strides_of); None = contiguous."""
     code = {torch.bfloat16: BURST_BF16, torch.float32: BURST_F32, "bf16": BURST_BF16, "f32": BURST_F32}.get(dtype, dtype)
     ptr, stride = None, 0
     if block_mask is not None:
@@ -107,7 +120,8 @@ def params(B, H, Nq, Nc, d, dtype, scale, causal=False, q_off=0, k_off=0, window
             raise ValueError("block_mask: shape must be [ceil(Nq/block), ceil(Nc/block)], alone or after [B, H]")
         ptr = block_mask.data_ptr()
     return BurstParams(B, H, Nq, Nc, d, code, 1 if causal else 0, scale, q_off, k_off, window, ptr,
-                       block if block_mask is not None else 0, kv_heads, stride)
+                       block if block_mask is not None else 0, kv_heads, stride,
+                       (ctypes.c_int64 * 3)(*(q_strides or (0, 0, 0))), (ctypes.c_int64 * 3)(*(kv_strides or (0, 0, 0))))
 
 
 def _ptr(t):
@@ -118,6 +132,32 @@ def _ptr(t):
     if not t.is_contiguous():
         raise ValueError("contiguous tensor expected")
     return ctypes.c_void_p(t.data_ptr())
+
+
+def _strided(t, want):
+    """Pointer of a storage-type tensor that must lie in memory as the parameter block says."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("device tensor expected")
+    want = tuple(want)
+    if want == (0, 0, 0):
+        if not t.is_contiguous():
+            raise ValueError("contiguous tensor expected (or give its strides to params())")
+    else:
+        if t.dim() != 4 or (t.shape[3] > 1 and t.stride(3) != 1):
+            raise ValueError("a [B, H, rows, d] tensor with a contiguous last dimension expected")
+        if any(t.shape[i] > 1 and t.stride(i) != want[i] for i in range(3)):
+            raise ValueError(f"tensor strides {tuple(t.stride())} differ from the parameter block's {want}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _q(t, p):
+    return _strided(t, p.q_strides)
+
+
+def _kv(t, p):
+    return _strided(t, p.kv_strides)
 
 
 def _f32(t):
@@ -140,7 +180,7 @@ def burst_state_init(O_acc, m, l, p):
 
 
 def burst_local_fwd(Q, K_chunk, V_chunk, O_acc, m, l, p):
-    _check(load().burst_local_fwd(_ptr(Q), _ptr(K_chunk), _ptr(V_chunk), _f32(O_acc), _f32(m), _f32(l),
+    _check(load().burst_local_fwd(_q(Q, p), _kv(K_chunk, p), _kv(V_chunk, p), _f32(O_acc), _f32(m), _f32(l),
                                   ctypes.byref(p), _stream()), "burst_local_fwd")
 
 
@@ -150,13 +190,13 @@ def burst_materialized_workspace_bytes(p):
 
 def burst_local_fwd_materialized(Q, K_chunk, V_chunk, O_acc, m, l, workspace, p):
     """workspace: a contiguous uint8 device tensor (see burst_materialized_workspace_bytes)."""
-    _check(load().burst_local_fwd_materialized(_ptr(Q), _ptr(K_chunk), _ptr(V_chunk), _f32(O_acc), _f32(m), _f32(l),
+    _check(load().burst_local_fwd_materialized(_q(Q, p), _kv(K_chunk, p), _kv(V_chunk, p), _f32(O_acc), _f32(m), _f32(l),
                                                _ptr(workspace), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
                                                ctypes.byref(p), _stream()), "burst_local_fwd_materialized")
 
 
 def burst_finalize(O_acc, m, l, O_out, lse, p):
-    _check(load().burst_finalize(_f32(O_acc), _f32(m), _f32(l), _ptr(O_out), _f32(lse),
+    _check(load().burst_finalize(_f32(O_acc), _f32(m), _f32(l), _q(O_out, p), _f32(lse),
                                  ctypes.byref(p), _stream()), "burst_finalize")
 
 
@@ -166,25 +206,25 @@ def burst_merge_state(O_a, m_a, l_a, O_b, m_b, l_b, p):
 
 
 def burst_bwd_prepare(O, dO, D, p):
-    _check(load().burst_bwd_prepare(_ptr(O), _ptr(dO), _f32(D), ctypes.byref(p), _stream()), "burst_bwd_prepare")
+    _check(load().burst_bwd_prepare(_q(O, p), _q(dO, p), _f32(D), ctypes.byref(p), _stream()), "burst_bwd_prepare")
 
 
 def burst_local_bwd(Q, K_chunk, V_chunk, O, dO, lse, D, dQ, dK_chunk, dV_chunk, p,
                     accumulate_dq=True, accumulate_dkv=False):
-    _check(load().burst_local_bwd(_ptr(Q), _ptr(K_chunk), _ptr(V_chunk), _ptr(O), _ptr(dO), _f32(lse), _f32(D),
+    _check(load().burst_local_bwd(_q(Q, p), _kv(K_chunk, p), _kv(V_chunk, p), _q(O, p), _q(dO, p), _f32(lse), _f32(D),
                                   _f32(dQ), _f32(dK_chunk), _f32(dV_chunk),
                                   1 if accumulate_dq else 0, 1 if accumulate_dkv else 0,
                                   ctypes.byref(p), _stream()), "burst_local_bwd")
 
 
 def burst_local_bwd_dq(Q, K_chunk, V_chunk, dO, lse, D, dQ, p, accumulate_dq=True):
-    _check(load().burst_local_bwd_dq(_ptr(Q), _ptr(K_chunk), _ptr(V_chunk), _ptr(dO), _f32(lse), _f32(D),
+    _check(load().burst_local_bwd_dq(_q(Q, p), _kv(K_chunk, p), _kv(V_chunk, p), _q(dO, p), _f32(lse), _f32(D),
                                      _f32(dQ), 1 if accumulate_dq else 0, ctypes.byref(p), _stream()),
            "burst_local_bwd_dq")
 
 
 def burst_local_bwd_dkv(Q, K_chunk, V_chunk, dO, lse, D, dK_chunk, dV_chunk, p, accumulate_dkv=False):
-    _check(load().burst_local_bwd_dkv(_ptr(Q), _ptr(K_chunk), _ptr(V_chunk), _ptr(dO), _f32(lse), _f32(D),
+    _check(load().burst_local_bwd_dkv(_q(Q, p), _kv(K_chunk, p), _kv(V_chunk, p), _q(dO, p), _f32(lse), _f32(D),
                                       _f32(dK_chunk), _f32(dV_chunk), 1 if accumulate_dkv else 0,
                                       ctypes.byref(p), _stream()), "burst_local_bwd_dkv")
 

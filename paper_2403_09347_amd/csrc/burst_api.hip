@@ -72,6 +72,26 @@ int check_params(const burst_params* p, KParams* k) {
     if (p->kv_heads < 0 || p->H % p->kv_heads != 0) return BURST_ERR_SHAPE;
     k->group = p->H / p->kv_heads;
   }
+  // strides: all zero = contiguous [B, heads, rows, d]
+  {
+    const long long hk = p->H / k->group, d = p->d;
+    burst::Layout& L = k->lay;
+    L.heads = p->H; L.kv_heads = (int)hk;
+    const int64_t* q = p->q_strides; const int64_t* kv = p->kv_strides;
+    const long long unit = p->dtype == BURST_BF16 ? 8 : 4;     // 16-byte granules
+    if (q[0] == 0 && q[1] == 0 && q[2] == 0) {
+      L.qs_r = d; L.qs_h = (long long)p->Nq * d; L.qs_b = L.qs_h * p->H;
+    } else {
+      if (q[0] < 0 || q[1] < 0 || q[2] < d || q[0] % unit || q[1] % unit || q[2] % unit) return BURST_ERR_SHAPE;
+      L.qs_b = q[0]; L.qs_h = q[1]; L.qs_r = q[2];
+    }
+    if (kv[0] == 0 && kv[1] == 0 && kv[2] == 0) {
+      L.ks_r = d; L.ks_h = (long long)p->Nc * d; L.ks_b = L.ks_h * hk;
+    } else {
+      if (kv[0] < 0 || kv[1] < 0 || kv[2] < d || kv[0] % unit || kv[1] % unit || kv[2] % unit) return BURST_ERR_SHAPE;
+      L.ks_b = kv[0]; L.ks_h = kv[1]; L.ks_r = kv[2];
+    }
+  }
   k->bmask = nullptr; k->bsize = 64; k->bpitch = 0; k->bhstride = 0;
   if (p->block_mask != nullptr) {
     if (p->block <= 0 || p->block % 64 != 0) return BURST_ERR_SHAPE;
@@ -90,21 +110,28 @@ int check_params(const burst_params* p, KParams* k) {
     if (!aligned16(ptr)) return BURST_ERR_ALIGN;         \
   } while (0)
 
-// The MFMA kernels address a head's rows through 32-bit byte offsets (256 B per row, plus a few
-// tiles of prefetch past the end); longer slices or chunks take the generic kernels.
+// The MFMA kernels address a head's rows through 32-bit byte offsets (plus a few tiles of
+// prefetch past the end; dK/dV: the rows of all query heads of a group, from the first head's
+// row 0); longer or wider-strided slices or chunks take the generic kernels.
 constexpr int kMaxMfmaRows = 4 * 1024 * 1024;
+bool spans_fit(const burst_params* p, const KParams& k) {
+  const long long q = ((long long)p->Nq + 1024) * k.lay.qs_r * 2 + (long long)(k.group - 1) * k.lay.qs_h * 2;
+  const long long kv = ((long long)p->Nc + 1024) * k.lay.ks_r * 2;
+  return q <= 0xffffffffLL && kv <= 0xffffffffLL;
+}
 // With block flags the MFMA kernels keep a list of visible tiles in LDS (8192 tiles of 64 keys or
 // rows, or 16384 of 32 keys): longer masked slices or chunks take the generic kernels.
 constexpr int kMaxMaskedRows = 8192 * 64;
-bool use_mfma(const burst_params* p) {
-  return p->dtype == BURST_BF16 && p->d == 128 && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows;
+bool use_mfma(const burst_params* p, const KParams& k) {
+  return p->dtype == BURST_BF16 && p->d == 128 && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows && spans_fit(p, k);
 }
 // bf16, d = 64 has MFMA kernels of its own.
 #ifndef BURST_SMALL_D
 #define BURST_SMALL_D 64
 #endif
-bool use_d64(const burst_params* p) {
-  if (!(p->dtype == BURST_BF16 && p->d == BURST_SMALL_D && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows)) return false;
+bool use_d64(const burst_params* p, const KParams& k) {
+  if (!(p->dtype == BURST_BF16 && p->d == BURST_SMALL_D && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows &&
+        spans_fit(p, k))) return false;
   if (p->block_mask == nullptr) return true;
   // with block flags: lists of at most 4096 tiles (32 keys or rows each; rows of all heads of a group)
   const long long group = (p->kv_heads > 0) ? p->H / p->kv_heads : 1;
@@ -113,7 +140,7 @@ bool use_d64(const burst_params* p) {
 // The dK/dV MFMA kernel walks the query tiles of all heads of a group as one list: whole 64-row
 // tiles per head and at most 8192 tiles in all; other grouped shapes take the generic kernel.
 bool dkv_mfma_ok(const burst_params* p, const KParams& k) {
-  if (k.group > 1) return p->Nq % 64 == 0 && (long long)k.group * (p->Nq / 64) <= 8192 &&
+  if (k.group > 1) return p->Nq % 64 == 0 && (long long)k.group * (p->Nq / 64) <= 8192 && k.group <= 256 &&
                           (long long)k.group * p->Nq <= kMaxMfmaRows;
   return p->block_mask == nullptr || p->Nq <= kMaxMaskedRows;
 }
@@ -160,8 +187,8 @@ int burst_local_fwd(const void* Q, const void* K_chunk, const void* V_chunk,
   REQUIRE_PTR(Q); REQUIRE_PTR(K_chunk); REQUIRE_PTR(V_chunk);
   REQUIRE_PTR(O_acc); REQUIRE_PTR(m); REQUIRE_PTR(l);
   if ((st = check_arch()) != BURST_OK) return st;
-  if (use_d64(p)) return burst::launch_fwd_d64(k, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
-  if (use_mfma(p) && (p->block_mask == nullptr || p->Nc <= kMaxMaskedRows))
+  if (use_d64(p, k)) return burst::launch_fwd_d64(k, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
+  if (use_mfma(p, k) && (p->block_mask == nullptr || p->Nc <= kMaxMaskedRows))
     return burst::launch_fwd_mfma(k, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
   return burst::launch_fwd_generic(k, p->dtype, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
 }
@@ -186,7 +213,7 @@ int burst_local_fwd_materialized(const void* Q, const void* K_chunk, const void*
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return BURST_ERR_ALIGN;
   if (workspace_bytes < burst::materialized_workspace_bytes(k, p->dtype)) return BURST_ERR_SHAPE;
   if ((st = check_arch()) != BURST_OK) return st;
-  return burst::launch_fwd_materialized(k, p->dtype, use_mfma(p), Q, K_chunk, V_chunk, O_acc, m, l, workspace,
+  return burst::launch_fwd_materialized(k, p->dtype, use_mfma(p, k), Q, K_chunk, V_chunk, O_acc, m, l, workspace,
                                         (hipStream_t)stream);
 }
 
@@ -262,9 +289,9 @@ static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const v
     if ((st = burst::launch_bwd_prepare(k, p->dtype, O, dO, scratch, s)) != BURST_OK) return st;
     Duse = scratch;
   }
-  const bool mfma_dq = use_mfma(p) && (p->block_mask == nullptr || p->Nc <= kMaxMaskedRows);
-  const bool mfma_dkv = use_mfma(p) && dkv_mfma_ok(p, k);
-  if (use_d64(p)) {
+  const bool mfma_dq = use_mfma(p, k) && (p->block_mask == nullptr || p->Nc <= kMaxMaskedRows);
+  const bool mfma_dkv = use_mfma(p, k) && dkv_mfma_ok(p, k);
+  if (use_d64(p, k)) {
     if (want_dq &&
         (st = burst::launch_bwd_dq_d64(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)) != BURST_OK)
       return st;
@@ -348,6 +375,6 @@ const char* burst_strerror(int status) {
   }
 }
 
-int burst_version(void) { return 104; }
+int burst_version(void) { return 105; }
 
 }  // extern "C"

@@ -20,6 +20,7 @@ struct BwdArgs {
   int group;             // query heads per key/value head (grouped-query attention; 1 = none)
   int blocks_per_head;
   int acc_dq, acc_dkv;
+  Layout lay;            // strides of Q, dO and of K, V
 };
 
 inline BwdArgs make_bwd_args(const KParams& p, const void* Q, const void* K, const void* V,
@@ -33,6 +34,7 @@ inline BwdArgs make_bwd_args(const KParams& p, const void* Q, const void* K, con
   a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
   a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.bhstride = p.bhstride; a.group = p.group;
   a.blocks_per_head = 0; a.acc_dq = acc_dq; a.acc_dkv = acc_dkv;
+  a.lay = p.lay;
   return a;
 }
 

@@ -63,10 +63,12 @@ burst_bwd_dkv_kernel(BwdArgs a) {
   const int key0 = key_wg + w * 32;                // first key of this wavefront
   const int group = SPARSE ? a.group : 1;          // query heads that share this key/value head
   const int q_rows = group * a.Nq;                 // rows of the group's Q / dO / lse / D
-  const bf16* Qh = a.Q + (size_t)head * q_rows * 128;
-  const bf16* Gh = a.dO + (size_t)head * q_rows * 128;
-  const bf16* Kh = a.K + (size_t)head * a.Nc * 128;
-  const bf16* Vh = a.V + (size_t)head * a.Nc * 128;
+  const bf16* Qh = a.Q + a.lay.q_base(head * group);    // first query head of the group
+  const bf16* Gh = a.dO + a.lay.q_base(head * group);
+  const bf16* Kh = a.K + a.lay.kv_base(head);
+  const bf16* Vh = a.V + a.lay.kv_base(head);
+  const unsigned qpitch = (unsigned)a.lay.qs_r * 2u;             // bytes between query rows
+  const unsigned qtile = qpitch * DKV_BR;                        // ... between query tiles
   const float* lseh = a.lse + (size_t)head * q_rows;
   const float* Dh = a.D + (size_t)head * q_rows;
 
@@ -117,7 +119,7 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           const unsigned long long bal = __builtin_amdgcn_ballot_w64(bits != 0);
           if (bits != 0) {
             const int pos = n + __builtin_amdgcn_mbcnt_hi((unsigned)(bal >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)bal, 0u));
-            list[1 + pos] = (g * tiles_per_head + t) | (bits << 16);
+            list[1 + pos] = (g * tiles_per_head + t) | (bits << 16) | (g << 20);
           }
           n += __builtin_popcountll(bal);
         }
@@ -127,9 +129,15 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     __syncthreads();
     nwalk = __builtin_amdgcn_readfirstlane(list[0]);
   }
-  auto tile_at = [&](int j) __attribute__((always_inline)) {      // tile index of walk position j
-    if constexpr (SPARSE) return __builtin_amdgcn_readfirstlane(list[1 + j]) & 0xffff;
+  // walk position j -> its entry: the tile index in the low 16 bits and, SPARSE, the wavefront
+  // bits (16..19) and the head of the group (20..27)
+  auto entry_at = [&](int j) __attribute__((always_inline)) {
+    if constexpr (SPARSE) return __builtin_amdgcn_readfirstlane(list[1 + j]);
     else return t_begin + j;
+  };
+  auto tile_of = [&](int e) __attribute__((always_inline)) {
+    if constexpr (SPARSE) return e & 0xffff;
+    else return e;
   };
 
   if (nwalk > 0) {
@@ -142,8 +150,8 @@ burst_bwd_dkv_kernel(BwdArgs a) {
         bf16x8 z;
 #pragma unroll
         for (int t = 0; t < 8; t++) z[t] = (bf16)0.0f;
-        kf[ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Kh + (size_t)key * 128 + ks * 16 + h * 8) : z;
-        vf[ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Vh + (size_t)key * 128 + ks * 16 + h * 8) : z;
+        kf[ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Kh + (size_t)key * a.lay.ks_r + ks * 16 + h * 8) : z;
+        vf[ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Vh + (size_t)key * a.lay.ks_r + ks * 16 + h * 8) : z;
       }
     }
     // LDS addressing inside a 64-row tile.  A operands (128-bit): row rb*32 + lr, granule
@@ -160,18 +168,26 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           taddr[db][sx] = tile_off(8 * sx + 4 * h + (j16 >> 2), db * 4 + 2 * dh + ((j16 & 3) >> 1)) + (j16 & 1) * 8;
     }
     // DMA: a 64-row tile is 16 wave-loads of 4 rows; wavefront w issues loads 4w .. 4w+3
-    const __amdgpu_buffer_rsrc_t qrs = make_rsrc(Qh, (unsigned)q_rows * 256u);
-    const __amdgpu_buffer_rsrc_t grs = make_rsrc(Gh, (unsigned)q_rows * 256u);
+    // (the rows of the group's heads lie (head stride) apart: a tile of head g of the group starts
+    // g * gfix bytes away from where it would in one tensor of group * Nq rows)
+    const unsigned hbytes = (unsigned)a.lay.qs_h * 2u;
+    const unsigned gfix = hbytes - (unsigned)tiles_per_head * qtile;
+    const unsigned qbytes = a.Nq > 0 ? (unsigned)(group - 1) * hbytes + (unsigned)(a.Nq - 1) * qpitch + 256u : 0u;
+    const __amdgpu_buffer_rsrc_t qrs = make_rsrc(Qh, qbytes);
+    const __amdgpu_buffer_rsrc_t grs = make_rsrc(Gh, qbytes);
     const int wu = __builtin_amdgcn_readfirstlane(w);
     const unsigned lds0 = lds_addr(smem);
     int goff[4];
 #pragma unroll
     for (int il = 0; il < 4; il++) {
       int row = 16 * w + 4 * il + (lane >> 4);
-      goff[il] = row * 256 + (((lane & 15) ^ row_code(row)) << 4);
+      goff[il] = (int)(row * qpitch + (((lane & 15) ^ row_code(row)) << 4));
     }
-    auto dma_tile = [&](__amdgpu_buffer_rsrc_t rs, unsigned lds_tile, int il, int tile) __attribute__((always_inline)) {
-      dma_b128_to_lds(rs, lds_tile + (unsigned)(wu * 4 + il) * 1024u, tile * DKV_TILE_BYTES + goff[il]);
+    // `e`: an entry (see entry_at)
+    auto dma_tile = [&](__amdgpu_buffer_rsrc_t rs, unsigned lds_tile, int il, int e) __attribute__((always_inline)) {
+      unsigned tile = (unsigned)tile_of(e) * qtile;
+      if constexpr (SPARSE) tile += (unsigned)((e >> 20) & 0xff) * gfix;
+      dma_b128_to_lds(rs, lds_tile + (unsigned)(wu * 4 + il) * 1024u, (int)tile + goff[il]);
     };
     // Per-row statistics of a tile travel like the tiles: wavefront 0 DMAs the 64 lse values,
     // wavefront 1 the 64 D values (rows past Nq read as 0; their Q and dO rows are 0 too, so they
@@ -221,7 +237,7 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     // t_begin .. t_begin + 2 into statistic slots 0 .. 2, the first two scaled right away
 #pragma unroll
     for (int t = 0; t < 2; t++) {
-      const int src = tile_at(t);
+      const int src = entry_at(t);
 #pragma unroll
       for (int il = 0; il < 4; il++) {
         dma_tile(qrs, lds0 + DKV_LDS_Q + t * DKV_TILE_BYTES, il, src);
@@ -229,7 +245,7 @@ burst_bwd_dkv_kernel(BwdArgs a) {
       }
     }
 #pragma unroll
-    for (int t = 0; t < 3; t++) dma_rowstat(tile_at(t), t);
+    for (int t = 0; t < 3; t++) dma_rowstat(tile_of(entry_at(t)), t);
     __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0), lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
     scale_rowstat(0);
@@ -262,14 +278,16 @@ burst_bwd_dkv_kernel(BwdArgs a) {
 
     int slot = 0;
     for (int n = 0; n < nwalk; n++) {                  // n = walk position; statistic slot n & 3 holds its tile
-      int t = t_begin + n, t2 = t + 2, t3 = t + 3;     // this tile, and the tiles whose rows / statistics are fetched now
+      // this tile, the entry of the tile whose rows are fetched now, the tile whose statistics are
+      int t = t_begin + n, t2 = t + 2, t3 = t + 3, t_in_head = t;
       bool mine = true;                                // SPARSE: this wavefront's keys are visible to the tile
       if constexpr (SPARSE) {
         const int e = __builtin_amdgcn_readfirstlane(list[1 + n]);
         t = e & 0xffff;
+        t_in_head = t - ((e >> 20) & 0xff) * tiles_per_head;
         mine = ((e >> (16 + wu)) & 1) != 0;
-        t2 = tile_at(n + 2);
-        t3 = tile_at(n + 3);
+        t2 = entry_at(n + 2);
+        t3 = tile_of(entry_at(n + 3));
       }
       const int slot1 = (slot == DKV_SLOTS - 1) ? 0 : slot + 1;
       const int slot2 = (slot1 == DKV_SLOTS - 1) ? 0 : slot1 + 1;
@@ -280,7 +298,7 @@ burst_bwd_dkv_kernel(BwdArgs a) {
       const float* lp_next = reinterpret_cast<const float*>(smem + DKV_LDS_L) + ((n + 1) & 3) * DKV_BR;
       const float* dp_next = reinterpret_cast<const float*>(smem + DKV_LDS_D) + ((n + 1) & 3) * DKV_BR;
       // (t counts tiles over all heads of the group; the position restarts with every head)
-      const long long tile_first_q = a.q_off + (long long)((SPARSE && group > 1) ? t % tiles_per_head : t) * DKV_BR;
+      const long long tile_first_q = a.q_off + (long long)t_in_head * DKV_BR;
       // (no branch around the MFMA phases: the AGPR-pinned accumulators must not become phi
       // values, the allocator would shuttle them through VGPRs every iteration)
       const bool need_mask = (a.causal && wave_last_k > tile_first_q) ||

@@ -101,10 +101,12 @@ burst_bwd_dq_kernel(BwdArgs a) {
     if (head >= a.H) return;
   }
   const int q0 = qb * DQ_BR + w * 64;
-  const bf16* Qh = a.Q + (size_t)head * a.Nq * 128;
-  const bf16* Gh = a.dO + (size_t)head * a.Nq * 128;
-  const bf16* Kh = a.K + (size_t)(head / a.group) * a.Nc * 128;
-  const bf16* Vh = a.V + (size_t)(head / a.group) * a.Nc * 128;
+  const bf16* Qh = a.Q + a.lay.q_base(head);
+  const bf16* Gh = a.dO + a.lay.q_base(head);
+  const bf16* Kh = a.K + a.lay.kv_base(head / a.group);
+  const bf16* Vh = a.V + a.lay.kv_base(head / a.group);
+  const unsigned kpitch = (unsigned)a.lay.ks_r * 2u;             // bytes between key rows
+  const unsigned ktile = kpitch * DQ_BC;                         // ... between key tiles
   const float* lseh = a.lse + (size_t)head * a.Nq;
   const float* Dh = a.D + (size_t)head * a.Nq;
   float* dQh = a.dQ + (size_t)head * a.Nq * 128;
@@ -124,7 +126,7 @@ burst_bwd_dq_kernel(BwdArgs a) {
       if constexpr (SPARSE) {
         t_lo = skip / DQ_BC;
       } else {
-        Kh += (size_t)skip * 128; Vh += (size_t)skip * 128;
+        Kh += (size_t)skip * a.lay.ks_r; Vh += (size_t)skip * a.lay.ks_r;
         Nc -= skip; k_off += skip;
       }
     }
@@ -202,8 +204,8 @@ burst_bwd_dq_kernel(BwdArgs a) {
         bf16x8 z;
 #pragma unroll
         for (int t = 0; t < 8; t++) z[t] = (bf16)0.0f;
-        qf[rb][ks] = ok ? *reinterpret_cast<const bf16x8*>(Qh + (size_t)row * 128 + ks * 16 + h * 8) : z;
-        gfr[rb][ks] = ok ? *reinterpret_cast<const bf16x8*>(Gh + (size_t)row * 128 + ks * 16 + h * 8) : z;
+        qf[rb][ks] = ok ? *reinterpret_cast<const bf16x8*>(Qh + (size_t)row * a.lay.qs_r + ks * 16 + h * 8) : z;
+        gfr[rb][ks] = ok ? *reinterpret_cast<const bf16x8*>(Gh + (size_t)row * a.lay.qs_r + ks * 16 + h * 8) : z;
       }
     }
     // LDS addressing.  A-operand reads (128-bit): row lr, granule 2*ks + h; since 2*ks and
@@ -219,18 +221,19 @@ burst_bwd_dq_kernel(BwdArgs a) {
           taddr[db][sx] = tile_off(8 * sx + 4 * h + (j16 >> 2), db * 4 + 2 * dh + ((j16 & 3) >> 1)) + (j16 & 1) * 8;
     }
     // DMA: a 32-key tile is 8 wave-loads of 4 rows; wavefront w issues loads 2w and 2w + 1
-    const __amdgpu_buffer_rsrc_t krs = make_rsrc(Kh, (unsigned)Nc * 256u);
-    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, (unsigned)Nc * 256u);
+    const unsigned kbytes = Nc > 0 ? (unsigned)(Nc - 1) * kpitch + 256u : 0u;   // up to the end of the last row
+    const __amdgpu_buffer_rsrc_t krs = make_rsrc(Kh, kbytes);
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, kbytes);
     const int wu = __builtin_amdgcn_readfirstlane(w);
     const unsigned lds0 = lds_addr(smem);
     int goff[2];
 #pragma unroll
     for (int il = 0; il < 2; il++) {
       int row = 8 * w + 4 * il + (lane >> 4);
-      goff[il] = row * 256 + (((lane & 15) ^ row_code(row)) << 4);
+      goff[il] = (int)(row * kpitch + (((lane & 15) ^ row_code(row)) << 4));
     }
     auto dma_tile = [&](__amdgpu_buffer_rsrc_t rs, unsigned lds_tile, int il, int tile) __attribute__((always_inline)) {
-      dma_b128_to_lds(rs, lds_tile + (unsigned)(wu * 2 + il) * 1024u, tile * DQ_TILE_BYTES + goff[il]);
+      dma_b128_to_lds(rs, lds_tile + (unsigned)(wu * 2 + il) * 1024u, (int)(tile * ktile) + goff[il]);
     };
     constexpr int VBASE = DQ_KSLOTS * DQ_TILE_BYTES;
 #pragma unroll

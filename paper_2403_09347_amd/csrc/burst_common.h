@@ -19,8 +19,38 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 #define BURST_NEG_INF (-__builtin_inff())
 
+// Where the storage-type tensors lie in memory: element strides between batch entries, heads
+// and rows of Q, dO, O (query side) and of K, V (key side); the last dimension is contiguous.
+// fp32 tensors (state, lse, D, gradients) are always contiguous [B, H, rows, d] / [B, H, rows].
+struct Layout {
+  long long qs_b, qs_h, qs_r;
+  long long ks_b, ks_h, ks_r;
+  int heads, kv_heads;             // heads per batch entry on either side
+  // element offset of row 0 of a head; `head` counts batch x heads
+  __host__ __device__ size_t q_base(int head) const {
+    const int b = head / heads;
+    return (size_t)b * qs_b + (size_t)(head - b * heads) * qs_h;
+  }
+  __host__ __device__ size_t kv_base(int kvhead) const {
+    const int b = kvhead / kv_heads;
+    return (size_t)b * ks_b + (size_t)(kvhead - b * kv_heads) * ks_h;
+  }
+};
+
+// Row r of the query-side tensors, r counting the rows of all (batch, head)s: element offset.
+struct QRows {
+  Layout lay;
+  int Nq, d, dense;                // dense: contiguous [B, H, Nq, d], the offset is r * d
+  __host__ __device__ size_t off(long long r) const {
+    if (dense) return (size_t)r * d;
+    const long long head = r / Nq;
+    return lay.q_base((int)head) + (size_t)(r - head * Nq) * lay.qs_r;
+  }
+};
+
 // Kernel-side copy of the call's parameters (plain data, passed by value).
 struct KParams {
+  Layout lay;
   int B, H, Nq, Nc, d;
   int causal;
   float scale;
@@ -30,6 +60,12 @@ struct KParams {
   int bsize, bpitch;
   long long bhstride;    // bytes between the flag matrices of consecutive (batch, query head)s; 0 = shared
   int group;             // query heads per key/value head (1 = every head has its own K, V)
+  QRows q_rows() const {
+    QRows q;
+    q.lay = lay; q.Nq = Nq; q.d = d;
+    q.dense = lay.qs_r == d && lay.qs_h == (long long)Nq * d && lay.qs_b == (long long)Nq * d * H;
+    return q;
+  }
 };
 
 // The opt-in to more than 64 KB of dynamic LDS is a per-device function attribute: launchers

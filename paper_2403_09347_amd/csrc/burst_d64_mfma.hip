@@ -38,6 +38,7 @@ struct FwdArgsLite {
   const uint8_t* bmask; int bsize, bpitch;       // block flags (nullptr = none)
   long long bhstride;                            // bytes between heads' flag matrices (0 = shared)
   int blocks_per_head;
+  Layout lay;                                    // strides of Q and of K, V
 };
 
 __device__ __forceinline__ int s_swz(int row) { return S_D == 64 ? ((row >> 1) & 7) : row_code(row); }
@@ -46,9 +47,14 @@ __device__ __forceinline__ int s_off(int row, int granule) {
 }
 // DMA of `rows8` groups of 8 tile rows: one wave-wide load moves 8 rows (1024 bytes); lane i
 // fills LDS slot i & 7 of row i >> 3 of the group and asks for the granule that belongs there.
-__device__ __forceinline__ int s_dma_off(int group, int lane) {
+// (pitch: bytes between rows of the tensor in HBM)
+__device__ __forceinline__ int s_dma_off(int group, int lane, unsigned pitch) {
   const int row = group * S_RPL + lane / S_GPR;
-  return row * S_ROWB + (((lane % S_GPR) ^ s_swz(row)) << 4);
+  return (int)(row * pitch + (((lane % S_GPR) ^ s_swz(row)) << 4));
+}
+// bytes a buffer descriptor must cover for `rows` rows `pitch` bytes apart
+__device__ __forceinline__ unsigned s_span(int rows, unsigned pitch) {
+  return rows > 0 ? (unsigned)(rows - 1) * pitch + (unsigned)S_ROWB : 0u;
 }
 // addresses of the transposing reads of a 16-row group (see the d = 128 forward kernel): the
 // 16-lane group (h, dh) reads rows 8*sx + 4*h + (0..3), columns db*32 + dh*16 + (0..15)
@@ -116,9 +122,10 @@ burst_fwd_d64_kernel(FwdArgsLite a) {
   s_head_block(blockIdx.x, a.blocks_per_head, head, qb);
   if (head >= a.H) return;
   const int q0 = qb * SF_BR + w * 32;
-  const bf16* Qh = a.Q + (size_t)head * a.Nq * S_D;
-  const bf16* Kh = a.K + (size_t)(head / a.group) * a.Nc * S_D;
-  const bf16* Vh = a.V + (size_t)(head / a.group) * a.Nc * S_D;
+  const bf16* Qh = a.Q + a.lay.q_base(head);
+  const bf16* Kh = a.K + a.lay.kv_base(head / a.group);
+  const bf16* Vh = a.V + a.lay.kv_base(head / a.group);
+  const unsigned kpitch = (unsigned)a.lay.ks_r * 2u;             // bytes between key rows
 
   int Nc = a.Nc;
   long long k_off = a.k_off;
@@ -131,7 +138,7 @@ burst_fwd_d64_kernel(FwdArgsLite a) {
       if constexpr (SPARSE) {
         t_lo = skip / SF_BC;
       } else {
-        Kh += (size_t)skip * S_D; Vh += (size_t)skip * S_D;
+        Kh += (size_t)skip * a.lay.ks_r; Vh += (size_t)skip * a.lay.ks_r;
         Nc -= skip; k_off += skip;
       }
     }
@@ -163,7 +170,7 @@ burst_fwd_d64_kernel(FwdArgsLite a) {
 
   bf16x8 qf[S_KS];
 #pragma unroll
-  for (int ks = 0; ks < S_KS; ks++) qf[ks] = s_load8(Qh + (size_t)(q0 + lr) * S_D + ks * 16 + h * 8, q0 + lr < a.Nq);
+  for (int ks = 0; ks < S_KS; ks++) qf[ks] = s_load8(Qh + (size_t)(q0 + lr) * a.lay.qs_r + ks * 16 + h * 8, q0 + lr < a.Nq);
   f32x16 o[S_DB];
 #pragma unroll
   for (int db = 0; db < S_DB; db++)
@@ -175,19 +182,19 @@ burst_fwd_d64_kernel(FwdArgsLite a) {
 #pragma unroll
   for (int ks = 0; ks < S_KS; ks++) kaddr[ks] = s_off(lr, 2 * ks + h);
   s_taddr(lane, taddr);
-  const __amdgpu_buffer_rsrc_t krs = make_rsrc(Kh, (unsigned)Nc * S_ROWB);
-  const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, (unsigned)Nc * S_ROWB);
+  const __amdgpu_buffer_rsrc_t krs = make_rsrc(Kh, s_span(Nc, kpitch));
+  const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, s_span(Nc, kpitch));
   const int wu = __builtin_amdgcn_readfirstlane(w);
   const unsigned lds0 = lds_addr(smem);
   constexpr int NL = SF_BC / S_RPL / 4;           // wave-wide loads per wavefront and tile
   int goff[NL];
 #pragma unroll
-  for (int il = 0; il < NL; il++) goff[il] = s_dma_off(w * NL + il, lane);
+  for (int il = 0; il < NL; il++) goff[il] = s_dma_off(w * NL + il, lane, kpitch);
   auto dma_tile = [&](int t, int buf) __attribute__((always_inline)) {
 #pragma unroll
     for (int il = 0; il < NL; il++) {
-      dma_b128_to_lds(krs, lds0 + buf * SF_TILE + (unsigned)(wu * NL + il) * 1024u, t * SF_TILE + goff[il]);
-      dma_b128_to_lds(vrs, lds0 + (2 + buf) * SF_TILE + (unsigned)(wu * NL + il) * 1024u, t * SF_TILE + goff[il]);
+      dma_b128_to_lds(krs, lds0 + buf * SF_TILE + (unsigned)(wu * NL + il) * 1024u, (int)(t * SF_BC * kpitch) + goff[il]);
+      dma_b128_to_lds(vrs, lds0 + (2 + buf) * SF_TILE + (unsigned)(wu * NL + il) * 1024u, (int)(t * SF_BC * kpitch) + goff[il]);
     }
   };
   const long long wave_first_q = a.q_off + q0, wave_last_q = wave_first_q + 31;
@@ -321,8 +328,9 @@ burst_bwd_dq_d64_kernel(BwdArgs a) {
   const int row = q0 + lr;
   const bool ok = row < a.Nq;
   const size_t srow = (size_t)head * a.Nq + (ok ? row : 0);
-  const bf16* Kh = a.K + (size_t)(head / a.group) * a.Nc * S_D;
-  const bf16* Vh = a.V + (size_t)(head / a.group) * a.Nc * S_D;
+  const bf16* Kh = a.K + a.lay.kv_base(head / a.group);
+  const bf16* Vh = a.V + a.lay.kv_base(head / a.group);
+  const unsigned kpitch = (unsigned)a.lay.ks_r * 2u;             // bytes between key rows
 
   int Nc = a.Nc;
   long long k_off = a.k_off;
@@ -336,7 +344,7 @@ burst_bwd_dq_d64_kernel(BwdArgs a) {
       if constexpr (SPARSE) {
         t_lo = skip / SQ_BC;
       } else {
-        Kh += (size_t)skip * S_D; Vh += (size_t)skip * S_D;
+        Kh += (size_t)skip * a.lay.ks_r; Vh += (size_t)skip * a.lay.ks_r;
         Nc -= skip; k_off += skip;
       }
     }
@@ -374,8 +382,9 @@ burst_bwd_dq_d64_kernel(BwdArgs a) {
     bf16x8 qf[S_KS], gf[S_KS];
 #pragma unroll
     for (int ks = 0; ks < S_KS; ks++) {
-      qf[ks] = s_load8(a.Q + srow * S_D + ks * 16 + h * 8, ok);
-      gf[ks] = s_load8(a.dO + srow * S_D + ks * 16 + h * 8, ok);
+      const size_t qrow = a.lay.q_base(head) + (size_t)(ok ? row : 0) * a.lay.qs_r;
+      qf[ks] = s_load8(a.Q + qrow + ks * 16 + h * 8, ok);
+      gf[ks] = s_load8(a.dO + qrow + ks * 16 + h * 8, ok);
     }
     const float lv = ok ? a.lse[srow] : BURST_NEG_INF;
     const float nlse2 = (lv == BURST_NEG_INF) ? BURST_NEG_INF : -lv * kLog2e;   // -inf: P = 0
@@ -384,19 +393,19 @@ burst_bwd_dq_d64_kernel(BwdArgs a) {
 #pragma unroll
     for (int ks = 0; ks < S_KS; ks++) kaddr[ks] = s_off(lr, 2 * ks + h);
     s_taddr(lane, taddr);
-    const __amdgpu_buffer_rsrc_t krs = make_rsrc(Kh, (unsigned)Nc * S_ROWB);
-    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, (unsigned)Nc * S_ROWB);
+    const __amdgpu_buffer_rsrc_t krs = make_rsrc(Kh, s_span(Nc, kpitch));
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, s_span(Nc, kpitch));
     const int wu = __builtin_amdgcn_readfirstlane(w);
     const unsigned lds0 = lds_addr(smem);
     constexpr int NL = SQ_BC / S_RPL / 4;         // wave-wide loads per wavefront and tile
     int goff[NL];
 #pragma unroll
-    for (int il = 0; il < NL; il++) goff[il] = s_dma_off(w * NL + il, lane);
+    for (int il = 0; il < NL; il++) goff[il] = s_dma_off(w * NL + il, lane, kpitch);
     auto dma_tile = [&](int t, int buf) __attribute__((always_inline)) {
 #pragma unroll
       for (int il = 0; il < NL; il++) {
-        dma_b128_to_lds(krs, lds0 + buf * SQ_TILE + (unsigned)(wu * NL + il) * 1024u, t * SQ_TILE + goff[il]);
-        dma_b128_to_lds(vrs, lds0 + (2 + buf) * SQ_TILE + (unsigned)(wu * NL + il) * 1024u, t * SQ_TILE + goff[il]);
+        dma_b128_to_lds(krs, lds0 + buf * SQ_TILE + (unsigned)(wu * NL + il) * 1024u, (int)(t * SQ_BC * kpitch) + goff[il]);
+        dma_b128_to_lds(vrs, lds0 + (2 + buf) * SQ_TILE + (unsigned)(wu * NL + il) * 1024u, (int)(t * SQ_BC * kpitch) + goff[il]);
       }
     };
     const long long wave_first_q = a.q_off + q0;
@@ -488,8 +497,9 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
   s_head_block(blockIdx.x, a.blocks_per_head, kvhead, kblk);
   if (kvhead >= a.H) return;                       // a.H counts key/value heads here
   const int key_wg = kblk * SK_BC, key0 = key_wg + w * 32;
-  const bf16* Kh = a.K + (size_t)kvhead * a.Nc * S_D;
-  const bf16* Vh = a.V + (size_t)kvhead * a.Nc * S_D;
+  const bf16* Kh = a.K + a.lay.kv_base(kvhead);
+  const bf16* Vh = a.V + a.lay.kv_base(kvhead);
+  const unsigned qpitch = (unsigned)a.lay.qs_r * 2u;             // bytes between query rows
 
   // query tiles of one head to visit (causal: rows before the first key see nothing; window:
   // rows too far behind the last key neither), then the same range for every head of the group
@@ -540,8 +550,8 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
     bf16x8 kf[S_KS], vf[S_KS];
 #pragma unroll
     for (int ks = 0; ks < S_KS; ks++) {
-      kf[ks] = s_load8(Kh + (size_t)(key0 + lr) * S_D + ks * 16 + h * 8, key0 + lr < a.Nc);
-      vf[ks] = s_load8(Vh + (size_t)(key0 + lr) * S_D + ks * 16 + h * 8, key0 + lr < a.Nc);
+      kf[ks] = s_load8(Kh + (size_t)(key0 + lr) * a.lay.ks_r + ks * 16 + h * 8, key0 + lr < a.Nc);
+      vf[ks] = s_load8(Vh + (size_t)(key0 + lr) * a.lay.ks_r + ks * 16 + h * 8, key0 + lr < a.Nc);
     }
     int qaddr[S_KS], taddr[S_DB][2];
 #pragma unroll
@@ -552,7 +562,7 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
     constexpr int NL = SK_BR / S_RPL / 4;         // wave-wide loads per wavefront and tile
     int goff[NL];
 #pragma unroll
-    for (int il = 0; il < NL; il++) goff[il] = s_dma_off(w * NL + il, lane);
+    for (int il = 0; il < NL; il++) goff[il] = s_dma_off(w * NL + il, lane, qpitch);
     float* const stat = reinterpret_cast<float*>(smem + SK_STAT);
     // walk position n -> (query head, tile); every wavefront DMAs its 8 rows of Q and dO.  The
     // first wavefront also fetches the 32 rows' statistics with plain loads issued BEFORE the
@@ -568,12 +578,13 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
         if (tid < 32) stat_x = r < a.Nq ? a.lse[hrow + r] : BURST_NEG_INF;
         else stat_x = r < a.Nq ? a.D[hrow + r] : 0.f;
       }
-      const __amdgpu_buffer_rsrc_t qrs = make_rsrc(a.Q + hrow * S_D, (unsigned)a.Nq * S_ROWB);
-      const __amdgpu_buffer_rsrc_t grs = make_rsrc(a.dO + hrow * S_D, (unsigned)a.Nq * S_ROWB);
+      const size_t hbase = a.lay.q_base(kvhead * a.group + g);
+      const __amdgpu_buffer_rsrc_t qrs = make_rsrc(a.Q + hbase, s_span(a.Nq, qpitch));
+      const __amdgpu_buffer_rsrc_t grs = make_rsrc(a.dO + hbase, s_span(a.Nq, qpitch));
 #pragma unroll
       for (int il = 0; il < NL; il++) {
-        dma_b128_to_lds(qrs, lds0 + buf * SK_TILE + (unsigned)(wu * NL + il) * 1024u, t * SK_TILE + goff[il]);
-        dma_b128_to_lds(grs, lds0 + (2 + buf) * SK_TILE + (unsigned)(wu * NL + il) * 1024u, t * SK_TILE + goff[il]);
+        dma_b128_to_lds(qrs, lds0 + buf * SK_TILE + (unsigned)(wu * NL + il) * 1024u, (int)(t * SK_BR * qpitch) + goff[il]);
+        dma_b128_to_lds(grs, lds0 + (2 + buf) * SK_TILE + (unsigned)(wu * NL + il) * 1024u, (int)(t * SK_BR * qpitch) + goff[il]);
       }
     };
     auto stat_commit = [&](int buf) __attribute__((always_inline)) {
@@ -675,6 +686,7 @@ int launch_fwd_d64(const KParams& p, const void* Q, const void* K, const void* V
   a.causal = p.causal; a.c = p.scale * kLog2e;
   a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
   a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.bhstride = p.bhstride;
+  a.lay = p.lay;
   a.blocks_per_head = (p.Nq + SF_BR - 1) / SF_BR;
   const long long nb = (long long)((a.H + 7) / 8 * 8) * a.blocks_per_head;
   if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;

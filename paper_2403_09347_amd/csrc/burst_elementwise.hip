@@ -20,7 +20,7 @@ state_init_kernel(float* __restrict__ O_acc, float* __restrict__ m, float* __res
 template <typename OutT, int VEC>
 __global__ void __launch_bounds__(256)
 finalize_kernel(const float* __restrict__ O_acc, const float* __restrict__ m, const float* __restrict__ l,
-                OutT* __restrict__ O_out, float* __restrict__ lse, long long n_rows, int d) {
+                OutT* __restrict__ O_out, float* __restrict__ lse, long long n_rows, int d, QRows qr) {
   const int per_row = d / VEC;
   long long total = n_rows * per_row;
   long long stride = (long long)gridDim.x * 256;
@@ -31,7 +31,7 @@ finalize_kernel(const float* __restrict__ O_acc, const float* __restrict__ m, co
     float inv = lv > 0.f ? 1.0f / lv : 0.f;
     if (c == 0) lse[row] = lv > 0.f ? m[row] + __logf(lv) : BURST_NEG_INF;
     const float* src = O_acc + row * d + c * VEC;
-    OutT* dst = O_out + row * d + c * VEC;
+    OutT* dst = O_out + qr.off(row) + c * VEC;
     if (VEC == 4) {
       f32x4 v = *reinterpret_cast<const f32x4*>(src);
       if (sizeof(OutT) == 4) {
@@ -109,15 +109,15 @@ merge_state_row_kernel(float* __restrict__ O_a, float* __restrict__ m_a, float* 
 template <typename T>
 __global__ void __launch_bounds__(256)
 bwd_prepare_kernel(const T* __restrict__ O, const T* __restrict__ dO, float* __restrict__ D,
-                   long long n_rows, int d) {
+                   long long n_rows, int d, QRows qr) {
   // one wavefront per row, lanes stride over the row in chunks of 4 elements when possible
   const int lane = threadIdx.x & 63;
   long long wave = ((long long)blockIdx.x * 256 + threadIdx.x) >> 6;
   long long nwaves = ((long long)gridDim.x * 256) >> 6;
   const bool vec = (d % 4) == 0;
   for (long long row = wave; row < n_rows; row += nwaves) {
-    const T* o = O + row * d;
-    const T* g = dO + row * d;
+    const T* o = O + qr.off(row);
+    const T* g = dO + qr.off(row);
     float acc = 0.f;
     if (vec) {
       for (int c = lane * 4; c < d; c += 256) {
@@ -144,7 +144,7 @@ bwd_prepare_kernel(const T* __restrict__ O, const T* __restrict__ dO, float* __r
 template <typename T>
 __global__ void __launch_bounds__(256)
 bwd_prepare_d128_kernel(const T* __restrict__ O, const T* __restrict__ dO, float* __restrict__ D,
-                        long long n_rows) {
+                        long long n_rows, QRows qr) {
   long long stride = (long long)gridDim.x * 256;
   long long total = n_rows * 32;
   long long total_pad = (total + 63) & ~63LL;      // keep whole wavefronts in the loop for the shuffles
@@ -152,14 +152,14 @@ bwd_prepare_d128_kernel(const T* __restrict__ O, const T* __restrict__ dO, float
     float acc = 0.f;
     long long row = k >> 5;
     if (k < total) {
-      int c = (int)(k & 31) * 4;
+      const size_t c = qr.off(row) + (size_t)(k & 31) * 4;
       if (sizeof(T) == 4) {
-        f32x4 a = *reinterpret_cast<const f32x4*>(O + row * 128 + c);
-        f32x4 b = *reinterpret_cast<const f32x4*>(dO + row * 128 + c);
+        f32x4 a = *reinterpret_cast<const f32x4*>(O + c);
+        f32x4 b = *reinterpret_cast<const f32x4*>(dO + c);
         for (int t = 0; t < 4; t++) acc += a[t] * b[t];
       } else {
-        bf16x4 a = *reinterpret_cast<const bf16x4*>(O + row * 128 + c);
-        bf16x4 b = *reinterpret_cast<const bf16x4*>(dO + row * 128 + c);
+        bf16x4 a = *reinterpret_cast<const bf16x4*>(O + c);
+        bf16x4 b = *reinterpret_cast<const bf16x4*>(dO + c);
         for (int t = 0; t < 4; t++) acc += (float)a[t] * (float)b[t];
       }
     }
@@ -207,11 +207,11 @@ int launch_finalize(const KParams& p, int dtype, const float* O_acc, const float
   bool vec = (p.d % 4) == 0;
   unsigned g = grid_for(rows * (vec ? p.d / 4 : p.d));
   if (dtype == BURST_BF16) {
-    if (vec) hipLaunchKernelGGL((finalize_kernel<bf16, 4>), dim3(g), dim3(256), 0, s, O_acc, m, l, (bf16*)O_out, lse, rows, p.d);
-    else hipLaunchKernelGGL((finalize_kernel<bf16, 1>), dim3(g), dim3(256), 0, s, O_acc, m, l, (bf16*)O_out, lse, rows, p.d);
+    if (vec) hipLaunchKernelGGL((finalize_kernel<bf16, 4>), dim3(g), dim3(256), 0, s, O_acc, m, l, (bf16*)O_out, lse, rows, p.d, p.q_rows());
+    else hipLaunchKernelGGL((finalize_kernel<bf16, 1>), dim3(g), dim3(256), 0, s, O_acc, m, l, (bf16*)O_out, lse, rows, p.d, p.q_rows());
   } else {
-    if (vec) hipLaunchKernelGGL((finalize_kernel<float, 4>), dim3(g), dim3(256), 0, s, O_acc, m, l, (float*)O_out, lse, rows, p.d);
-    else hipLaunchKernelGGL((finalize_kernel<float, 1>), dim3(g), dim3(256), 0, s, O_acc, m, l, (float*)O_out, lse, rows, p.d);
+    if (vec) hipLaunchKernelGGL((finalize_kernel<float, 4>), dim3(g), dim3(256), 0, s, O_acc, m, l, (float*)O_out, lse, rows, p.d, p.q_rows());
+    else hipLaunchKernelGGL((finalize_kernel<float, 1>), dim3(g), dim3(256), 0, s, O_acc, m, l, (float*)O_out, lse, rows, p.d, p.q_rows());
   }
   return launch_status();
 }
@@ -235,12 +235,12 @@ int launch_bwd_prepare(const KParams& p, int dtype, const void* O, const void* d
   if (rows == 0) return BURST_OK;
   if (p.d == 128) {
     unsigned g = grid_for(rows * 32);
-    if (dtype == BURST_BF16) hipLaunchKernelGGL((bwd_prepare_d128_kernel<bf16>), dim3(g), dim3(256), 0, s, (const bf16*)O, (const bf16*)dO, D, rows);
-    else hipLaunchKernelGGL((bwd_prepare_d128_kernel<float>), dim3(g), dim3(256), 0, s, (const float*)O, (const float*)dO, D, rows);
+    if (dtype == BURST_BF16) hipLaunchKernelGGL((bwd_prepare_d128_kernel<bf16>), dim3(g), dim3(256), 0, s, (const bf16*)O, (const bf16*)dO, D, rows, p.q_rows());
+    else hipLaunchKernelGGL((bwd_prepare_d128_kernel<float>), dim3(g), dim3(256), 0, s, (const float*)O, (const float*)dO, D, rows, p.q_rows());
   } else {
     unsigned g = grid_for(rows * 64);
-    if (dtype == BURST_BF16) hipLaunchKernelGGL((bwd_prepare_kernel<bf16>), dim3(g), dim3(256), 0, s, (const bf16*)O, (const bf16*)dO, D, rows, p.d);
-    else hipLaunchKernelGGL((bwd_prepare_kernel<float>), dim3(g), dim3(256), 0, s, (const float*)O, (const float*)dO, D, rows, p.d);
+    if (dtype == BURST_BF16) hipLaunchKernelGGL((bwd_prepare_kernel<bf16>), dim3(g), dim3(256), 0, s, (const bf16*)O, (const bf16*)dO, D, rows, p.d, p.q_rows());
+    else hipLaunchKernelGGL((bwd_prepare_kernel<float>), dim3(g), dim3(256), 0, s, (const float*)O, (const float*)dO, D, rows, p.d, p.q_rows());
   }
   return launch_status();
 }

@@ -43,6 +43,7 @@ struct FwdArgs {
   int bsize, bpitch;     // bsize: a multiple of 64, so a wavefront's 64 rows and a key tile lie in one block
   long long bhstride;    // bytes between the flag matrices of consecutive heads (0 = shared)
   int group;             // query heads per key/value head (grouped-query attention; 1 = none)
+  Layout lay;            // strides of Q and of K, V
 };
 
 
@@ -67,11 +68,12 @@ __device__ __forceinline__ void max3x2_mfma32_acc(f32x16& acc, bf16x8 a, bf16x8 
 // which global granule a lane fetches is free, so lane i asks for the granule that the XOR
 // layout places at its slot.  Each wavefront issues 4 such loads per tile (16 rows).
 // goff[il] is the lane's byte offset inside the tile for load il.
-__device__ __forceinline__ void tile_dma_offsets(int w, int lane, int (&goff)[4]) {
+// (pitch: bytes between rows of the tensor in HBM)
+__device__ __forceinline__ void tile_dma_offsets(int w, int lane, unsigned pitch, int (&goff)[4]) {
 #pragma unroll
   for (int il = 0; il < 4; il++) {
     int row = 16 * w + 4 * il + (lane >> 4);
-    goff[il] = row * 256 + (((lane & 15) ^ row_code(row)) << 4);
+    goff[il] = (int)(row * pitch + (((lane & 15) ^ row_code(row)) << 4));
   }
 }
 __device__ __forceinline__ void tile_dma(__amdgpu_buffer_rsrc_t rsrc, unsigned lds_tile, int w_uniform, int il,
@@ -126,9 +128,11 @@ burst_fwd_mfma_kernel(FwdArgs a) {
   }
 
   const int q0 = qb * FWD_BR + w * 64;             // first query row of this wave
-  const bf16* Qh = a.Q + (size_t)head * a.Nq * 128;
-  const bf16* Kh = a.K + (size_t)(head / a.group) * a.Nc * 128;
-  const bf16* Vh = a.V + (size_t)(head / a.group) * a.Nc * 128;
+  const bf16* Qh = a.Q + a.lay.q_base(head);
+  const bf16* Kh = a.K + a.lay.kv_base(head / a.group);
+  const bf16* Vh = a.V + a.lay.kv_base(head / a.group);
+  const unsigned kpitch = (unsigned)a.lay.ks_r * 2u;             // bytes between key rows
+  const unsigned ktile = kpitch * FWD_BC;                        // ... between key tiles
 
   // Sliding window: key tiles before the first one that the workgroup's first row can see are
   // skipped by moving the start of the chunk (pointers, length, global offset) forward by whole
@@ -144,7 +148,7 @@ burst_fwd_mfma_kernel(FwdArgs a) {
       if constexpr (SPARSE) {
         t_lo = skip / FWD_BC;
       } else {
-        Kh += (size_t)skip * 128; Vh += (size_t)skip * 128;
+        Kh += (size_t)skip * a.lay.ks_r; Vh += (size_t)skip * a.lay.ks_r;
         Nc -= skip; k_off += skip;
       }
     }
@@ -210,7 +214,7 @@ burst_fwd_mfma_kernel(FwdArgs a) {
       bf16x8 v;
 #pragma unroll
       for (int t = 0; t < 8; t++) v[t] = (bf16)0.0f;
-      if (row < a.Nq) v = *reinterpret_cast<const bf16x8*>(Qh + (size_t)row * 128 + ks * 16 + h * 8);
+      if (row < a.Nq) v = *reinterpret_cast<const bf16x8*>(Qh + (size_t)row * a.lay.qs_r + ks * 16 + h * 8);
       qf[rb][ks] = v;
     }
   }
@@ -245,19 +249,20 @@ burst_fwd_mfma_kernel(FwdArgs a) {
   // ---- prologue: K tiles 0..2 and V tiles 0..1 into LDS, S of tile 0.
   // LDS: K ring = tiles 0..2 of the buffer, V ring = tiles 3..5; tile t lives in slot t % 3.
   // Tiles past the end of the chunk read as zeros (buffer range check) and are never used.
-  const __amdgpu_buffer_rsrc_t krs = make_rsrc(Kh, (unsigned)Nc * 256u);
-  const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, (unsigned)Nc * 256u);
+  const unsigned kbytes = Nc > 0 ? (unsigned)(Nc - 1) * kpitch + 256u : 0u;   // up to the end of the last row
+  const __amdgpu_buffer_rsrc_t krs = make_rsrc(Kh, kbytes);
+  const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, kbytes);
   const int wu = __builtin_amdgcn_readfirstlane(w);
   const unsigned lds0 = lds_addr(smem);
   int goff[4];
-  tile_dma_offsets(w, lane, goff);
+  tile_dma_offsets(w, lane, kpitch, goff);
 #pragma unroll
   for (int t = 0; t < 3; t++) {
     const int src = tile_at(t);
 #pragma unroll
     for (int il = 0; il < 4; il++) {
-      tile_dma(krs, lds0 + t * FWD_TILE_BYTES, wu, il, src * FWD_TILE_BYTES + goff[il]);
-      if (t < 2) tile_dma(vrs, lds0 + (3 + t) * FWD_TILE_BYTES, wu, il, src * FWD_TILE_BYTES + goff[il]);
+      tile_dma(krs, lds0 + t * FWD_TILE_BYTES, wu, il, (int)(src * ktile) + goff[il]);
+      if (t < 2) tile_dma(vrs, lds0 + (3 + t) * FWD_TILE_BYTES, wu, il, (int)(src * ktile) + goff[il]);
     }
   }
   __builtin_amdgcn_s_waitcnt(0x0F70);              // vmcnt(0): this wavefront's DMA has landed
@@ -443,8 +448,8 @@ burst_fwd_mfma_kernel(FwdArgs a) {
       }
       if ((i & 3) == 1) {                          // 8 slots: one DMA of 4 tile rows each
         const int j = i >> 2;                      // 0..3 -> K of tile kt + 3, 4..7 -> V of tile kt + 2
-        if (j < 4) tile_dma(krs, k_dst, wu, j, kt3 * FWD_TILE_BYTES + goff[j]);
-        else tile_dma(vrs, v_dst, wu, j - 4, kt2 * FWD_TILE_BYTES + goff[j - 4]);
+        if (j < 4) tile_dma(krs, k_dst, wu, j, (int)(kt3 * ktile) + goff[j]);
+        else tile_dma(vrs, v_dst, wu, j - 4, (int)(kt2 * ktile) + goff[j - 4]);
       }
       {
         bf16x8 vf;
@@ -540,6 +545,7 @@ int launch_fwd_mfma(const KParams& p, const void* Q, const void* K, const void* 
   a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
   a.q_blocks = (p.Nq + FWD_BR - 1) / FWD_BR;
   a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.bhstride = p.bhstride; a.group = p.group;
+  a.lay = p.lay;
   int heads8 = ((a.H + 7) / 8) * 8;                // pad the head count to a multiple of 8 ids
   long long nblocks = (long long)heads8 * a.q_blocks;
   if (nblocks > 0x7fffffffLL) return BURST_ERR_SHAPE;

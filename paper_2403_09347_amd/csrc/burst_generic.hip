@@ -20,6 +20,7 @@ struct GenArgs {
   long long window;
   const uint8_t* bmask; int bsize, bpitch;        // block mask (nullptr = none)
   long long bhstride;                             // bytes between heads' flag matrices (0 = shared)
+  Layout lay;                                     // strides of Q, dO and of K, V
   int group;                                      // query heads per key/value head
   int acc_dq, acc_dkv;
 };
@@ -55,9 +56,9 @@ fwd_generic_kernel(GenArgs a) {
   const bool live = wave < total;
   if (!live) wave = 0;                             // keep every wavefront up to the barrier
   const int head = (int)(wave / a.Nq), row = (int)(wave % a.Nq);
-  const T* Qr = (const T*)a.Q + ((size_t)head * a.Nq + row) * a.d;
-  const T* Kh = (const T*)a.K + (size_t)(head / a.group) * a.Nc * a.d;
-  const T* Vh = (const T*)a.V + (size_t)(head / a.group) * a.Nc * a.d;
+  const T* Qr = (const T*)a.Q + a.lay.q_base(head) + (size_t)row * a.lay.qs_r;
+  const T* Kh = (const T*)a.K + a.lay.kv_base(head / a.group);
+  const T* Vh = (const T*)a.V + a.lay.kv_base(head / a.group);
   for (int t = lane; t < a.d; t += 64) qrow[w][t] = ld(Qr + t);
   __syncthreads();
   if (!live) return;
@@ -69,7 +70,7 @@ fwd_generic_kernel(GenArgs a) {
     float s = BURST_NEG_INF;
     if (vis) {
       float acc = 0.f;
-      const T* kr = Kh + (size_t)key * a.d;
+      const T* kr = Kh + (size_t)key * a.lay.ks_r;
       for (int t = 0; t < a.d; t++) acc = __builtin_fmaf(qrow[w][t], ld(kr + t), acc);
       s = acc * a.scale;
     }
@@ -84,7 +85,7 @@ fwd_generic_kernel(GenArgs a) {
     int nk = min(64, a.Nc - k0);
     for (int k = 0; k < nk; k++) {
       float pk = __shfl(p, k);
-      const T* vr = Vh + (size_t)(k0 + k) * a.d;
+      const T* vr = Vh + (size_t)(k0 + k) * a.lay.ks_r;
       if (lane < a.d) o0 = __builtin_fmaf(pk, ld(vr + lane), o0);
       if (lane + 64 < a.d) o1 = __builtin_fmaf(pk, ld(vr + lane + 64), o1);
     }
@@ -118,10 +119,10 @@ bwd_dq_generic_kernel(GenArgs a) {
   if (!live) wave = 0;
   const int head = (int)(wave / a.Nq), row = (int)(wave % a.Nq);
   size_t r = (size_t)head * a.Nq + row;
-  const T* Qr = (const T*)a.Q + r * a.d;
-  const T* Gr = (const T*)a.dO + r * a.d;
-  const T* Kh = (const T*)a.K + (size_t)(head / a.group) * a.Nc * a.d;
-  const T* Vh = (const T*)a.V + (size_t)(head / a.group) * a.Nc * a.d;
+  const T* Qr = (const T*)a.Q + a.lay.q_base(head) + (size_t)row * a.lay.qs_r;
+  const T* Gr = (const T*)a.dO + a.lay.q_base(head) + (size_t)row * a.lay.qs_r;
+  const T* Kh = (const T*)a.K + a.lay.kv_base(head / a.group);
+  const T* Vh = (const T*)a.V + a.lay.kv_base(head / a.group);
   for (int t = lane; t < a.d; t += 64) { qrow[w][t] = ld(Qr + t); grow[w][t] = ld(Gr + t); }
   __syncthreads();
   if (!live) return;
@@ -134,8 +135,8 @@ bwd_dq_generic_kernel(GenArgs a) {
     float ds = 0.f;
     if (vis) {
       float sa = 0.f, dp = 0.f;
-      const T* kr = Kh + (size_t)key * a.d;
-      const T* vr = Vh + (size_t)key * a.d;
+      const T* kr = Kh + (size_t)key * a.lay.ks_r;
+      const T* vr = Vh + (size_t)key * a.lay.ks_r;
       for (int t = 0; t < a.d; t++) {
         sa = __builtin_fmaf(qrow[w][t], ld(kr + t), sa);
         dp = __builtin_fmaf(grow[w][t], ld(vr + t), dp);
@@ -146,7 +147,7 @@ bwd_dq_generic_kernel(GenArgs a) {
     int nk = min(64, a.Nc - k0);
     for (int k = 0; k < nk; k++) {
       float dsk = __shfl(ds, k);
-      const T* kr = Kh + (size_t)(k0 + k) * a.d;
+      const T* kr = Kh + (size_t)(k0 + k) * a.lay.ks_r;
       if (lane < a.d) q0 = __builtin_fmaf(dsk, ld(kr + lane), q0);
       if (lane + 64 < a.d) q1 = __builtin_fmaf(dsk, ld(kr + lane + 64), q1);
     }
@@ -170,16 +171,16 @@ bwd_dkv_generic_kernel(GenArgs a) {
   if (!live) wave = 0;
   const int kvhead = (int)(wave / a.Nc), key = (int)(wave % a.Nc);
   size_t kr_i = (size_t)kvhead * a.Nc + key;
-  const T* Kr = (const T*)a.K + kr_i * a.d;
-  const T* Vr = (const T*)a.V + kr_i * a.d;
+  const T* Kr = (const T*)a.K + a.lay.kv_base(kvhead) + (size_t)key * a.lay.ks_r;
+  const T* Vr = (const T*)a.V + a.lay.kv_base(kvhead) + (size_t)key * a.lay.ks_r;
   for (int t = lane; t < a.d; t += 64) { krow[w][t] = ld(Kr + t); vrow[w][t] = ld(Vr + t); }
   __syncthreads();
   if (!live) return;
   float k0a = 0.f, k1a = 0.f, v0a = 0.f, v1a = 0.f;
   for (int g = 0; g < a.group; g++) {                        // the query heads that share this key/value head
   const int head = kvhead * a.group + g;
-  const T* Qh = (const T*)a.Q + (size_t)head * a.Nq * a.d;
-  const T* Gh = (const T*)a.dO + (size_t)head * a.Nq * a.d;
+  const T* Qh = (const T*)a.Q + a.lay.q_base(head);
+  const T* Gh = (const T*)a.dO + a.lay.q_base(head);
   const float* lseh = a.lse + (size_t)head * a.Nq;
   const float* Dh = a.D + (size_t)head * a.Nq;
   for (int r0 = 0; r0 < a.Nq; r0 += 64) {
@@ -189,8 +190,8 @@ bwd_dkv_generic_kernel(GenArgs a) {
       float lse = lseh[row];
       if (lse != BURST_NEG_INF) {
         float sa = 0.f, dp = 0.f;
-        const T* qr = Qh + (size_t)row * a.d;
-        const T* gr = Gh + (size_t)row * a.d;
+        const T* qr = Qh + (size_t)row * a.lay.qs_r;
+        const T* gr = Gh + (size_t)row * a.lay.qs_r;
         for (int t = 0; t < a.d; t++) {
           sa = __builtin_fmaf(ld(qr + t), krow[w][t], sa);
           dp = __builtin_fmaf(ld(gr + t), vrow[w][t], dp);
@@ -202,8 +203,8 @@ bwd_dkv_generic_kernel(GenArgs a) {
     int nr = min(64, a.Nq - r0);
     for (int j = 0; j < nr; j++) {
       float pj = __shfl(p, j), dsj = __shfl(ds, j);
-      const T* qr = Qh + (size_t)(r0 + j) * a.d;
-      const T* gr = Gh + (size_t)(r0 + j) * a.d;
+      const T* qr = Qh + (size_t)(r0 + j) * a.lay.qs_r;
+      const T* gr = Gh + (size_t)(r0 + j) * a.lay.qs_r;
       if (lane < a.d) { v0a = __builtin_fmaf(pj, ld(gr + lane), v0a); k0a = __builtin_fmaf(dsj, ld(qr + lane), k0a); }
       if (lane + 64 < a.d) { v1a = __builtin_fmaf(pj, ld(gr + lane + 64), v1a); k1a = __builtin_fmaf(dsj, ld(qr + lane + 64), k1a); }
     }
@@ -226,6 +227,7 @@ static GenArgs make_args(const KParams& p) {
   a.Nq = p.Nq; a.Nc = p.Nc; a.d = p.d; a.BH = p.B * p.H;
   a.causal = p.causal; a.scale = p.scale; a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
   a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.bhstride = p.bhstride; a.group = p.group;
+  a.lay = p.lay;
   return a;
 }
 static inline int launch_status() { return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH; }

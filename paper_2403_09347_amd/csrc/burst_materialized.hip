@@ -23,6 +23,7 @@ struct MatArgs {
   long long q_off, k_off, window;
   const uint8_t* bmask; int bsize, bpitch;   // block mask (nullptr = none)
   long long bhstride;                        // bytes between heads' flag matrices (0 = shared)
+  Layout lay;                                // strides of Q and of K, V
   int group;                                 // query heads per key/value head
 };
 
@@ -34,8 +35,8 @@ mat_scores_mfma_kernel(MatArgs a) {
   const int q0 = blockIdx.y * 32;
   const int k0 = (blockIdx.x * 4 + w) * 32;
   if (k0 >= a.Ncp) return;
-  const bf16* Qh = (const bf16*)a.Q + (size_t)head * a.Nq * 128;
-  const bf16* Kh = (const bf16*)a.K + (size_t)(head / a.group) * a.Nc * 128;
+  const bf16* Qh = (const bf16*)a.Q + a.lay.q_base(head);
+  const bf16* Kh = (const bf16*)a.K + a.lay.kv_base(head / a.group);
   const int qrow = q0 + lr, krow = k0 + lr;
   f32x16 acc;
 #pragma unroll
@@ -45,8 +46,8 @@ mat_scores_mfma_kernel(MatArgs a) {
     bf16x8 qa, kb;
 #pragma unroll
     for (int t = 0; t < 8; t++) { qa[t] = (bf16)0.0f; kb[t] = (bf16)0.0f; }
-    if (qrow < a.Nq) qa = *reinterpret_cast<const bf16x8*>(Qh + (size_t)qrow * 128 + ks * 16 + h * 8);
-    if (krow < a.Nc) kb = *reinterpret_cast<const bf16x8*>(Kh + (size_t)krow * 128 + ks * 16 + h * 8);
+    if (qrow < a.Nq) qa = *reinterpret_cast<const bf16x8*>(Qh + (size_t)qrow * a.lay.qs_r + ks * 16 + h * 8);
+    if (krow < a.Nc) kb = *reinterpret_cast<const bf16x8*>(Kh + (size_t)krow * a.lay.ks_r + ks * 16 + h * 8);
     acc = mfma32(qa, kb, acc);          // rows of the product = query rows, columns = keys
   }
   // register r of lane (lr, h) holds query row 8*(r/4) + 4h + r%4, key lr of the block
@@ -72,8 +73,8 @@ mat_scores_generic_kernel(MatArgs a) {
     const long long head = hr / a.Nq;
     float s = 0.f;
     if (c < a.Nc) {
-      const T* q = (const T*)a.Q + ((size_t)head * a.Nq + r) * a.d;
-      const T* k = (const T*)a.K + ((size_t)(head / a.group) * a.Nc + c) * a.d;
+      const T* q = (const T*)a.Q + a.lay.q_base((int)head) + (size_t)r * a.lay.qs_r;
+      const T* k = (const T*)a.K + a.lay.kv_base((int)(head / a.group)) + (size_t)c * a.lay.ks_r;
       for (int t = 0; t < a.d; t++) s = __builtin_fmaf((float)q[t], (float)k[t], s);
     }
     a.S[idx] = s * a.scale;
@@ -137,9 +138,10 @@ mat_pv_merge_mfma_kernel(MatArgs a) {
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, lr = lane & 31, h = lane >> 5;
   const int head = blockIdx.y;
   const int q0 = blockIdx.x * 128 + w * 32;
-  const bf16* Vh = (const bf16*)a.V + (size_t)(head / a.group) * a.Nc * 128;
+  const bf16* Vh = (const bf16*)a.V + a.lay.kv_base(head / a.group);
+  const unsigned vpitch = (unsigned)a.lay.ks_r * 2u;         // bytes between rows of V
   const bf16* Ph = (const bf16*)a.P + (size_t)head * a.Nq * a.Ncp;
-  const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, (unsigned)a.Nc * 256u);
+  const __amdgpu_buffer_rsrc_t vrs = make_rsrc(Vh, a.Nc > 0 ? (unsigned)(a.Nc - 1) * vpitch + 256u : 0u);
   const int ntiles = (a.Nc + 31) / 32;
   const int wu = __builtin_amdgcn_readfirstlane(w);
   const unsigned lds0 = lds_addr(smem);
@@ -147,7 +149,7 @@ mat_pv_merge_mfma_kernel(MatArgs a) {
 #pragma unroll
   for (int il = 0; il < 2; il++) {
     const int row = 8 * w + 4 * il + (lane >> 4);
-    goff[il] = row * 256 + (((lane & 15) ^ row_code(row)) << 4);
+    goff[il] = (int)(row * vpitch + (((lane & 15) ^ row_code(row)) << 4));
   }
   // transposing reads: 16-lane group (h, dh) reads tile rows kg*16 + 8h + 4s + (0..3), columns
   // db*32 + dh*16 + (0..15); lane lr = dh*16 + j16 ends up with column lr of the d block
@@ -188,7 +190,7 @@ mat_pv_merge_mfma_kernel(MatArgs a) {
 #pragma unroll
       for (int il = 0; il < 2; il++)
         dma_b128_to_lds(vrs, lds0 + (unsigned)(((t + 1) & 1) * MAT_VTILE_BYTES) + (unsigned)(wu * 2 + il) * 1024u,
-                        (t + 1) * MAT_VTILE_BYTES + goff[il]);
+                        (int)((t + 1) * 32 * vpitch) + goff[il]);
     }
     bf16x8 pf[2];
     pf[0] = load_p(t, 0);
@@ -253,9 +255,9 @@ mat_pv_merge_generic_kernel(MatArgs a) {
     const float m_ij = a.m_c[srow];
     if (m_ij == BURST_NEG_INF) continue;
     const T* p = (const T*)a.P + (size_t)srow * a.Ncp;
-    const T* v = (const T*)a.V + (size_t)(head / a.group) * a.Nc * a.d + col;
+    const T* v = (const T*)a.V + a.lay.kv_base((int)(head / a.group)) + col;
     float acc = 0.f;
-    for (int c = 0; c < a.Nc; c++) acc = __builtin_fmaf((float)p[c], (float)v[(size_t)c * a.d], acc);
+    for (int c = 0; c < a.Nc; c++) acc = __builtin_fmaf((float)p[c], (float)v[(size_t)c * a.lay.ks_r], acc);
     const float m_old = a.m[srow];
     const float m_new = fmaxf(m_old, m_ij);
     const float fa = fast_exp2((m_old - m_new) * kLog2e);
@@ -296,6 +298,7 @@ int launch_fwd_materialized(const KParams& p, int dtype, bool mfma, const void* 
   a.Nq = p.Nq; a.Nc = p.Nc; a.Ncp = (p.Nc + 7) & ~7; a.d = p.d; a.BH = (long long)p.B * p.H;
   a.causal = p.causal; a.scale = p.scale; a.q_off = p.q_off; a.k_off = p.k_off; a.window = p.window;
   a.bmask = p.bmask; a.bsize = p.bsize; a.bpitch = p.bpitch; a.bhstride = p.bhstride; a.group = p.group;
+  a.lay = p.lay;
   const size_t rows = (size_t)a.BH * a.Nq;
   const size_t esize = dtype == BURST_BF16 ? 2 : 4;
   char* ws = (char*)workspace;

@@ -23,20 +23,22 @@ class RingWalk:
         self.O_acc = torch.empty((self.Bt, self.H, self.Nq, self.d), device=dev, dtype=torch.float32)
         self.m = torch.empty((self.Bt, self.H, self.Nq), device=dev, dtype=torch.float32)
         self.l = torch.empty_like(self.m)
-        self.O = torch.empty_like(Q)
+        self.O = torch.empty_strided(Q.shape, Q.stride(), device=dev, dtype=Q.dtype)   # O and dO lie in memory like Q
         self.lse = torch.empty_like(self.m)
         self.D = torch.empty_like(self.m)
 
-    def params(self, Nc, k_off, mask=None):
+    def params(self, Nc, k_off, mask=None, K_c=None):
+        """K_c: the chunk the call is about (its strides go into the parameter block; Q's always do)."""
         return B.params(self.Bt, self.H, self.Nq, Nc, self.d, self.Q.dtype, self.scale,
-                        self.causal, self.q_off, k_off, self.window, mask, self.block, self.kv_heads)
+                        self.causal, self.q_off, k_off, self.window, mask, self.block, self.kv_heads,
+                        q_strides=B.strides_of(self.Q), kv_strides=None if K_c is None else B.strides_of(K_c))
 
     # ---- forward (Alg. 1)
     def init(self):
         B.burst_state_init(self.O_acc, self.m, self.l, self.params(0, 0))
 
     def step(self, K_c, V_c, k_off, mask=None):
-        B.burst_local_fwd(self.Q, K_c, V_c, self.O_acc, self.m, self.l, self.params(K_c.shape[2], k_off, mask))
+        B.burst_local_fwd(self.Q, K_c, V_c, self.O_acc, self.m, self.l, self.params(K_c.shape[2], k_off, mask, K_c))
 
     def finalize(self):
         B.burst_finalize(self.O_acc, self.m, self.l, self.O, self.lse, self.params(0, 0))
@@ -60,12 +62,14 @@ class RingWalk:
         if dKs is None:
             dKs = [torch.empty(K.shape, device=dev, dtype=torch.float32) for K in Ks]
             dVs = [torch.empty(V.shape, device=dev, dtype=torch.float32) for V in Vs]
+        if dO.stride() != self.Q.stride():         # dO and O lie in memory like Q
+            dO = torch.empty_strided(self.Q.shape, self.Q.stride(), device=dev, dtype=self.Q.dtype).copy_(dO)
         if use_D:
             self.prepare(dO)
         for j in range(len(Ks)):
             B.burst_local_bwd(self.Q, Ks[j], Vs[j], self.O, dO, self.lse, self.D if use_D else None,
                               dQ, dKs[j], dVs[j],
-                              self.params(Ks[j].shape[2], k_offs[j], None if masks is None else masks[j]),
+                              self.params(Ks[j].shape[2], k_offs[j], None if masks is None else masks[j], Ks[j]),
                               accumulate_dq=True, accumulate_dkv=False)
         return dQ, dKs, dVs
 
@@ -89,7 +93,7 @@ class MaterializedWalk(RingWalk):
     def step(self, K_c, V_c, k_off, mask=None):
         self._reserve(K_c.shape[2])
         B.burst_local_fwd_materialized(self.Q, K_c, V_c, self.O_acc, self.m, self.l, self.workspace,
-                                       self.params(K_c.shape[2], k_off, mask))
+                                       self.params(K_c.shape[2], k_off, mask, K_c))
 
     def stored_scores(self, Nc):
         """Views of S_ij (fp32) and P_ij (input type) of the last step: [B, H, Nq, Nc]."""

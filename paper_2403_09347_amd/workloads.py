@@ -148,14 +148,32 @@ def block_flags(n_row_blocks, n_col_blocks, kind="random", density=0.4, seed=0, 
     return f.astype(np.uint8)
 
 
+def relayout(x, layout):
+    """The same [B, H, rows, d] values in another memory layout: "head" (contiguous), "seq" (a
+    transposed view of a contiguous [B, rows, H, d] tensor: the layout of the backward messages
+    in paper Sec. 2.2) or "packed" (a view into slot 1 of a [B, rows, 3, H, d] tensor, as a fused
+    query/key/value projection leaves its output)."""
+    if layout == "head":
+        return x
+    if layout == "seq":
+        return x.transpose(1, 2).contiguous().transpose(1, 2)
+    if layout == "packed":
+        B, H, rows, d = x.shape
+        big = torch.zeros((B, rows, 3, H, d), dtype=x.dtype, device=x.device)
+        big[:, :, 1] = x.transpose(1, 2)
+        return big[:, :, 1].transpose(1, 2)
+    raise ValueError(layout)
+
+
 def make_case(B, H, d, Nq, chunk_rows, dtype="bf16", seed=0, device="cpu",
               causal=False, q_off=0, k_offs=None, window=0, block=0, pattern="random", density=0.4, kv_heads=0,
-              per_head_flags=False):
+              per_head_flags=False, layout="head"):
     """Free-form case for parity tests: `chunk_rows` lists the rows of each chunk.  With
     block > 0 the case carries one block-flag matrix per chunk ("flags": numpy, "masks": the
     same on the device), blocks counted from the first row of the slice / of each chunk.  With
     kv_heads > 0 the K / V chunks have that many heads (grouped-query attention).  With
-    per_head_flags every (batch, query head) has a flag matrix of its own: [B, H, blocks, blocks]."""
+    per_head_flags every (batch, query head) has a flag matrix of its own: [B, H, blocks, blocks].
+    layout: how Q, K, V, dO lie in memory (see relayout; the values do not depend on it)."""
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)
     dt = torch.bfloat16 if dtype == "bf16" else torch.float32
@@ -164,6 +182,8 @@ def make_case(B, H, d, Nq, chunk_rows, dtype="bf16", seed=0, device="cpu",
     K = [_randn((B, Hkv, n, d), gen, device, dt) for n in chunk_rows]
     V = [_randn((B, Hkv, n, d), gen, device, dt) for n in chunk_rows]
     dO = _randn((B, H, Nq, d), gen, device, dt)
+    Q, dO = relayout(Q, layout), relayout(dO, layout)
+    K, V = [relayout(x, layout) for x in K], [relayout(x, layout) for x in V]
     if k_offs is None:
         k_offs, s = [], 0
         for n in chunk_rows:

@@ -42,7 +42,7 @@ def test_binding_lists_the_same_exports():
     assert sorted(binding.EXPORTS) == declared_symbols()
     p = binding.params(1, 2, 3, 4, 128, "bf16", 0.5, True, 7, 9)
     assert (p.B, p.H, p.Nq, p.Nc, p.d, p.dtype, p.causal, p.q_off, p.k_off) == (1, 2, 3, 4, 128, 0, 1, 7, 9)
-    assert ctypes.sizeof(p) == 80
+    assert ctypes.sizeof(p) == 128
     assert (p.block_mask, p.block, p.kv_heads, p.block_mask_stride) == (None, 0, 0, 0)
 
 
@@ -64,6 +64,10 @@ def test_argument_validation_without_gpu():
     assert lib.burst_local_fwd(null, null, null, null, null, null, ctypes.byref(bad), null) == -3
     bad = binding.params(1, 2, 128, 128, 128, "bf16", 0.5)
     bad.block_mask, bad.block, bad.block_mask_stride = 4096, 64, 3   # per-head matrices (2 x 2 bytes) would overlap
+    assert lib.burst_local_fwd(null, null, null, null, null, null, ctypes.byref(bad), null) == -3
+    bad = binding.params(1, 2, 16, 16, 128, "bf16", 0.5, q_strides=(4096, 128, 64))    # row stride below d
+    assert lib.burst_local_fwd(null, null, null, null, null, null, ctypes.byref(bad), null) == -3
+    bad = binding.params(1, 2, 16, 16, 128, "bf16", 0.5, kv_strides=(4096, 132, 256))  # head stride not 16-byte aligned
     assert lib.burst_local_fwd(null, null, null, null, null, null, ctypes.byref(bad), null) == -3
     bad = binding.params(1, 6, 16, 16, 128, "bf16", 0.5, kv_heads=4)   # H must be a multiple of kv_heads
     assert lib.burst_local_fwd(null, null, null, null, null, null, ctypes.byref(bad), null) == -3

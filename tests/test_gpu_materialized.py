@@ -28,6 +28,8 @@ CASES = [
     ("f32", dict(B=1, H=4, kv_heads=1, d=32, Nq=50, chunk_rows=[70])),
     ("bf16", dict(B=2, H=2, d=128, Nq=200, chunk_rows=[150, 90], block=64, pattern="random", density=0.5,
                   per_head_flags=True)),
+    ("bf16", dict(B=2, H=2, d=128, Nq=200, chunk_rows=[150, 90], causal=True, q_off=100, layout="seq")),
+    ("f32", dict(B=1, H=4, kv_heads=2, d=32, Nq=50, chunk_rows=[70], layout="packed")),
 ]
 
 

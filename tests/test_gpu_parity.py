@@ -96,6 +96,39 @@ def test_generic_kernels_block_sparse(dtype, spec):
     compare_all_heads(case, dtype, O, lse, dQ, dKs, dVs)
 
 
+# Tensors that are not contiguous [B, H, rows, d]: sequence-major and packed-projection views.
+STRIDED_CASES = [
+    ("bf16", dict(B=2, H=3, d=128, Nq=517, chunk_rows=[256, 1, 390], layout="seq")),
+    ("bf16", dict(B=1, H=2, d=128, Nq=300, chunk_rows=[256, 192], causal=True, q_off=148, layout="packed")),
+    ("bf16", dict(B=1, H=2, d=128, Nq=520, chunk_rows=[300, 300, 300], causal=True, q_off=380, window=200, layout="seq")),
+    ("bf16", dict(B=2, H=4, d=128, Nq=512, chunk_rows=[300, 300], block=128, pattern="random", density=0.4,
+                  per_head_flags=True, kv_heads=2, causal=True, q_off=200, layout="seq")),
+    ("bf16", dict(B=1, H=6, d=128, Nq=256, chunk_rows=[200, 130], kv_heads=2, layout="packed")),
+    ("bf16", dict(B=1, H=6, d=128, Nq=250, chunk_rows=[200, 130], kv_heads=3, layout="seq")),   # dK/dV: generic kernel
+    ("bf16", dict(B=2, H=3, d=64, Nq=300, chunk_rows=[200, 64, 331], causal=True, q_off=250, layout="seq")),
+    ("bf16", dict(B=1, H=4, d=64, Nq=256, chunk_rows=[256, 130], block=64, pattern="random", density=0.5,
+                  kv_heads=2, layout="packed")),
+    ("f32", dict(B=2, H=2, d=32, Nq=150, chunk_rows=[100, 90], causal=True, q_off=60, layout="seq")),
+    ("f32", dict(B=1, H=4, d=128, Nq=70, chunk_rows=[50, 41], kv_heads=2, layout="packed")),
+    ("bf16", dict(B=1, H=2, d=32, Nq=100, chunk_rows=[77], layout="seq")),                      # generic bf16
+]
+
+
+@pytest.mark.parametrize("dtype,spec", STRIDED_CASES,
+                         ids=lambda v: v if isinstance(v, str) else "-".join(f"{k}{x}" for k, x in v.items()))
+def test_strided_tensors(dtype, spec):
+    case = workloads.make_case(dtype=dtype, seed=43, device=DEV, **spec)
+    assert not case["Q"].is_contiguous() and not case["K"][0].is_contiguous()
+    walk, (O, lse, dQ, dKs, dVs) = run_case(case, dtype)
+    assert O.stride() == case["Q"].stride()                    # O is written where Q's layout says
+    compare_all_heads(case, dtype, O, lse, dQ, dKs, dVs)
+    # the same values in contiguous tensors give bitwise the same results
+    same = workloads.make_case(dtype=dtype, seed=43, device=DEV, **{**spec, "layout": "head"})
+    _, (O2, lse2, dQ2, dKs2, dVs2) = run_case(same, dtype)
+    assert torch.equal(O, O2) and torch.equal(lse, lse2) and torch.equal(dQ, dQ2)
+    assert all(torch.equal(a, b) for a, b in zip(dKs + dVs, dKs2 + dVs2))
+
+
 # bf16, d = 64: MFMA kernels of their own (32 rows or keys per wavefront, 64- and 32-key tiles).
 D64_CASES = [
     dict(B=1, H=2, d=64, Nq=32, chunk_rows=[32]),
@@ -533,9 +566,9 @@ def test_c_abi_called_with_raw_pointers():
     Bt, H, Nq, Nc, d = 1, 2, 96, 160, 128
     case = workloads.make_case(B=Bt, H=H, d=d, Nq=Nq, chunk_rows=[Nc], dtype="bf16", seed=83, device=DEV, causal=True,
                                q_off=64)
-    # burst_params: 7 x int32, float, 3 x int64, pointer, 2 x int32  (72 bytes)
-    blob = struct.pack("<7if3qQ2i", Bt, H, Nq, Nc, d, 0, 1, case["scale"], 64, 0, 0, 0, 0, 0)
-    assert len(blob) == 72
+    # burst_params: 7 x int32, float, 3 x int64, pointer, 2 x int32, 7 x int64 (mask stride, 2 x 3 strides)
+    blob = struct.pack("<7if3qQ2i7q", Bt, H, Nq, Nc, d, 0, 1, case["scale"], 64, 0, 0, 0, 0, 0, *([0] * 7))
+    assert len(blob) == 128
     params = ctypes.create_string_buffer(blob)
     O_acc = torch.empty((Bt, H, Nq, d), device=DEV, dtype=torch.float32)
     m = torch.empty((Bt, H, Nq), device=DEV, dtype=torch.float32)

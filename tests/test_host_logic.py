@@ -112,6 +112,24 @@ def test_cases_with_block_flags_and_fewer_kv_heads():
     assert per_head["masks"][1].shape == (2, 4, 2, 3)
 
 
+def test_layouts_keep_the_values_and_binding_reads_their_strides():
+    import torch
+    from paper_2403_09347_amd import binding
+    head = workloads.make_case(B=2, H=3, d=16, Nq=10, chunk_rows=[7], dtype="f32", seed=5)
+    for layout, q_strides, k_strides in (("seq", (480, 16, 48), (336, 16, 48)),
+                                         ("packed", (1440, 16, 144), (1008, 16, 144))):
+        case = workloads.make_case(B=2, H=3, d=16, Nq=10, chunk_rows=[7], dtype="f32", seed=5, layout=layout)
+        assert torch.equal(case["Q"], head["Q"]) and torch.equal(case["V"][0], head["V"][0])
+        assert binding.strides_of(case["Q"]) == q_strides and binding.strides_of(case["K"][0]) == k_strides
+    assert binding.strides_of(head["Q"]) is None
+    one = torch.zeros((1, 1, 5, 16)).transpose(1, 2).transpose(1, 2)
+    assert binding.strides_of(one) is None
+    with pytest.raises(ValueError):
+        binding.strides_of(torch.zeros((2, 3, 4, 16)).transpose(2, 3))          # last dimension not contiguous
+    p = binding.params(2, 3, 10, 7, 16, "f32", 0.25, q_strides=(480, 16, 48))
+    assert tuple(p.q_strides) == (480, 16, 48) and tuple(p.kv_strides) == (0, 0, 0)
+
+
 def test_binding_rejects_host_masks_and_wrong_shapes():
     import torch
     from paper_2403_09347_amd import binding
