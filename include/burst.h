@@ -143,6 +143,12 @@ int burst_local_bwd(const void* Q, const void* K_chunk, const void* V_chunk,
                     int accumulate_dq, int accumulate_dkv,
                     const burst_params* p, void* stream);
 
+/* Device memory the library itself holds on behalf of calls with these parameters: 0 for every
+ * entry point that is given all its buffers (the tiled steps keep S and P in registers, Sec. 2.4,
+ * and need no workspace); B*H*Nq*4 bytes for burst_local_bwd with D == NULL (the buffer described
+ * above).  Returns 0 for an invalid parameter block. */
+size_t burst_workspace_bytes(const burst_params* p);
+
 /* The two halves of burst_local_bwd on their own, for callers that need only one side
  * (Alg. 2 with the query side travelling needs dQ_j from every device but dK_i, dV_i only
  * locally) or that time them separately.  Same arguments and conventions as above; D must

@@ -18,7 +18,7 @@ EXPORTS = [
     "burst_state_init", "burst_local_fwd", "burst_finalize", "burst_merge_state",
     "burst_bwd_prepare", "burst_local_bwd", "burst_local_bwd_dq", "burst_local_bwd_dkv", "burst_event_create", "burst_event_record",
     "burst_event_elapsed_ms", "burst_event_destroy", "burst_strerror", "burst_version",
-    "burst_materialized_workspace_bytes", "burst_local_fwd_materialized",
+    "burst_materialized_workspace_bytes", "burst_local_fwd_materialized", "burst_workspace_bytes",
 ]
 
 
@@ -57,6 +57,8 @@ def load():
     lib.burst_finalize.argtypes = [fp, fp, fp, vp, fp, pp, vp]
     lib.burst_materialized_workspace_bytes.argtypes = [pp]
     lib.burst_materialized_workspace_bytes.restype = ctypes.c_size_t
+    lib.burst_workspace_bytes.argtypes = [pp]
+    lib.burst_workspace_bytes.restype = ctypes.c_size_t
     lib.burst_local_fwd_materialized.argtypes = [vp, vp, vp, fp, fp, fp, vp, ctypes.c_size_t, pp, vp]
     lib.burst_local_fwd_materialized.restype = ctypes.c_int
     lib.burst_merge_state.argtypes = [fp, fp, fp, fp, fp, fp, pp, vp]
@@ -182,6 +184,10 @@ def burst_state_init(O_acc, m, l, p):
 def burst_local_fwd(Q, K_chunk, V_chunk, O_acc, m, l, p):
     _check(load().burst_local_fwd(_q(Q, p), _kv(K_chunk, p), _kv(V_chunk, p), _f32(O_acc), _f32(m), _f32(l),
                                   ctypes.byref(p), _stream()), "burst_local_fwd")
+
+
+def burst_workspace_bytes(p):
+    return int(load().burst_workspace_bytes(ctypes.byref(p)))
 
 
 def burst_materialized_workspace_bytes(p):

@@ -193,6 +193,12 @@ int burst_local_fwd(const void* Q, const void* K_chunk, const void* V_chunk,
   return burst::launch_fwd_generic(k, p->dtype, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
 }
 
+size_t burst_workspace_bytes(const burst_params* p) {
+  KParams k;
+  if (check_params(p, &k) != BURST_OK) return 0;
+  return (size_t)k.B * k.H * k.Nq * sizeof(float);
+}
+
 size_t burst_materialized_workspace_bytes(const burst_params* p) {
   KParams k;
   if (check_params(p, &k) != BURST_OK) return 0;

@@ -90,6 +90,8 @@ def test_materialized_workspace_size_without_gpu():
     assert binding.burst_materialized_workspace_bytes(p) == 1280 + 1280 + 2 * 256
     bad = binding.params(1, 1, 16, 16, 300, "bf16", 0.5)
     assert binding.burst_materialized_workspace_bytes(bad) == 0
+    assert binding.burst_workspace_bytes(binding.params(2, 3, 100, 40, 128, "bf16", 0.5)) == 2 * 3 * 100 * 4
+    assert binding.burst_workspace_bytes(bad) == 0
     lib = binding.load()
     null = ctypes.c_void_p(0)
     assert lib.burst_local_fwd_materialized(null, null, null, null, null, null, null, 0, ctypes.byref(bad), null) == -3

@@ -541,15 +541,19 @@ def test_zigzag_rank_against_the_oracle(rank):
         check(f"dV[h{h}]", np.concatenate([f64(x[0, h]) for x in dVs]), dV_ref, "bf16")
 
 
-def test_autograd_wrapper_against_the_oracle():
+@pytest.mark.parametrize("layout", ["head", "seq"])
+def test_autograd_wrapper_against_the_oracle(layout):
     """The differentiable torch call (chunk walk forward, Alg. 2 walk backward) on a causal, grouped-head
-    case: outputs and the gradients autograd hands back, against the fp64 oracle."""
+    case: outputs and the gradients autograd hands back, against the fp64 oracle.  "seq": the inputs
+    are transposed views of [B, rows, H, d] leaves, read in place."""
     from paper_2403_09347_amd.autograd import burst_attention
     case = workloads.make_case(B=1, H=4, kv_heads=2, d=128, Nq=320, chunk_rows=[256, 100], dtype="bf16", seed=59,
-                               device=DEV, causal=True, q_off=120)
-    q = case["Q"].clone().requires_grad_(True)
-    ks = [k.clone().requires_grad_(True) for k in case["K"]]
-    vs = [v.clone().requires_grad_(True) for v in case["V"]]
+                               device=DEV, causal=True, q_off=120, layout=layout)
+    leaf = lambda t: t.detach().clone(memory_format=torch.preserve_format).requires_grad_(True)
+    q = leaf(case["Q"])
+    ks = [leaf(k) for k in case["K"]]
+    vs = [leaf(v) for v in case["V"]]
+    assert q.stride() == case["Q"].stride()
     O, lse = burst_attention(q, ks, vs, causal=True, q_off=120)
     (O.float() * case["dO"].float()).sum().backward()
     torch.cuda.synchronize()
