@@ -88,9 +88,10 @@ def overlap_measurement(w, inp, source, reps):
 
 
 def ablation_measurement(w, inp, reps):
-    """Forward walk of the workload with the tiled chunk step and with the step that stores
-    S_ij and P_ij in HBM (the paper's "w/o LAO" ablation, Tables 2-3).  Times in ms, median of
-    `reps`; memory is the workspace one chunk step needs on top of the inputs and the state."""
+    """Forward and backward walks of the workload with the tiled chunk steps and with the steps that
+    store the matrices of a block pair in HBM (the paper's "w/o LAO" ablation, Tables 2-3).  Times
+    in ms, median of `reps`; memory is the workspace one chunk step needs on top of the inputs and
+    the state."""
     import statistics
     import torch
     from paper_2403_09347_amd.harness import MaterializedWalk, RingWalk
@@ -110,8 +111,16 @@ def ablation_measurement(w, inp, reps):
         return statistics.median(ts[1:])
     t_tiled = timed(lambda: tiled.forward(Ks, Vs, k_offs))
     t_stored = timed(lambda: stored.forward(Ks, Vs, k_offs))
+    fwd_ws = stored.workspace.numel() / 2**20
+    dQ = torch.zeros(Q.shape, device=Q.device, dtype=torch.float32)
+    dKs = [torch.empty(K.shape, device=Q.device, dtype=torch.float32) for K in Ks]
+    dVs = [torch.empty(K.shape, device=Q.device, dtype=torch.float32) for K in Ks]
+    t_tiled_b = timed(lambda: tiled.backward(Ks, Vs, k_offs, inp["dO"], dQ, dKs, dVs))
+    stored.O, stored.lse = tiled.O, tiled.lse
+    t_stored_b = timed(lambda: stored.backward(Ks, Vs, k_offs, inp["dO"], dQ, dKs, dVs))
     return {"tiled_forward_ms": t_tiled, "stored_forward_ms": t_stored, "slowdown": t_stored / t_tiled,
-            "stored_workspace_MiB": stored.workspace.numel() / 2**20,
+            "tiled_backward_ms": t_tiled_b, "stored_backward_ms": t_stored_b, "backward_slowdown": t_stored_b / t_tiled_b,
+            "stored_workspace_MiB": fwd_ws, "stored_backward_workspace_MiB": stored.workspace.numel() / 2**20,
             "tiled_workspace_MiB": 0.0,
             "inputs_and_state_MiB": (Q.numel() * Q.element_size() * (1 + 2 * len(Ks)) + tiled.O_acc.numel() * 4
                                      + 2 * tiled.m.numel() * 4) / 2**20}
@@ -142,7 +151,7 @@ def main():
                          "pool of that kind into two receive buffers on a second stream while the previous chunk "
                          "computes; adds an 'overlap' object to the JSON line")
     ap.add_argument("--ablation", action="store_true",
-                    help="also time the forward walk with the chunk step that stores S_ij and P_ij in HBM "
+                    help="also time the forward and backward walks with the chunk steps that store S_ij, P_ij, dP_ij, dS_ij in HBM "
                          "(the paper's 'w/o LAO' ablation); adds an 'ablation' object to the JSON line")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch a plain elementwise copy kernel of known size (256 MiB read, 256 MiB "

@@ -180,6 +180,22 @@ int burst_local_fwd_materialized(const void* Q, const void* K_chunk, const void*
                                  void* workspace, size_t workspace_bytes,
                                  const burst_params* p, void* stream);
 
+/* Alg. 2, one block pair, in the same untiled form (the backward of the "w/o LAO" variant): the
+ * seven steps of the loop body one after the other, S_ij, P_ij, dP_ij and dS_ij of the whole
+ * block pair stored in `workspace` between them.  Same arguments, masking and results as
+ * burst_local_bwd with D given (up to rounding).  workspace: device memory, 256-byte aligned,
+ * at least burst_materialized_bwd_workspace_bytes(p) bytes (B H Nq Nc (4 + 2 element sizes));
+ * afterwards it starts with dP_ij as fp32 [B,H,Nq,ceil8(Nc)], followed at the next 256-byte
+ * boundaries by P_ij and dS_ij in `dtype` with the same pitch (hidden entries and padding 0;
+ * dS_ij without the factor scale). */
+size_t burst_materialized_bwd_workspace_bytes(const burst_params* p);
+int burst_local_bwd_materialized(const void* Q, const void* K_chunk, const void* V_chunk,
+                                 const void* dO, const float* lse, const float* D,
+                                 float* dQ, float* dK_chunk, float* dV_chunk,
+                                 int accumulate_dq, int accumulate_dkv,
+                                 void* workspace, size_t workspace_bytes,
+                                 const burst_params* p, void* stream);
+
 /* Timing helper for harnesses that cannot create HIP events themselves:
  * records/queries events on the same stream the kernels are launched on.
  * burst_event_create returns an opaque handle (NULL on failure). */

@@ -214,12 +214,9 @@ def gao_bwd_prepare(O, dO):
     return (_f64(dO) * _f64(O)).sum(axis=1)
 
 
-def gao_local_backward(Q, K_c, V_c, dO, lse, D, scale, vis=None):
-    """Alg. 2, one block pair: returns (dQ contribution, dK_c, dV_c).
-
-    S = scale Q K_c^T; P = exp(S - lse); dV = P^T dO; dP = dO V_c^T;
-    dS = P o (dP - D); dK = scale dS^T Q; dQ = scale dS K_c.
-    """
+def gao_local_backward_matrices(Q, K_c, V_c, dO, lse, D, scale, vis=None):
+    """Alg. 2, one block pair, the matrices of the loop body: S = scale Q K_c^T;
+    P = exp(S - lse); dP = dO V_c^T; dS = P o (dP - D).  Returns (P, dP, dS)."""
     Q, K_c, V_c, dO = _f64(Q), _f64(K_c), _f64(V_c), _f64(dO)
     lse, D = _f64(lse), _f64(D)
     S = scale * (Q @ K_c.T)
@@ -228,9 +225,19 @@ def gao_local_backward(Q, K_c, V_c, dO, lse, D, scale, vis=None):
     live = np.isfinite(lse)                      # rows that saw at least one key
     ref = np.where(live, lse, 0.0)
     P = np.where(live[:, None], np.exp(S - ref[:, None]), 0.0)
-    dV = P.T @ dO
     dP = dO @ V_c.T
     dS = P * (dP - D[:, None])
+    return P, dP, dS
+
+
+def gao_local_backward(Q, K_c, V_c, dO, lse, D, scale, vis=None):
+    """Alg. 2, one block pair: returns (dQ contribution, dK_c, dV_c).
+
+    With P, dP, dS as above: dV = P^T dO; dK = scale dS^T Q; dQ = scale dS K_c.
+    """
+    P, _, dS = gao_local_backward_matrices(Q, K_c, V_c, dO, lse, D, scale, vis)
+    Q, K_c, dO = _f64(Q), _f64(K_c), _f64(dO)
+    dV = P.T @ dO
     dK = scale * (dS.T @ Q)
     dQ = scale * (dS @ K_c)
     return dQ, dK, dV

@@ -19,6 +19,7 @@ EXPORTS = [
     "burst_bwd_prepare", "burst_local_bwd", "burst_local_bwd_dq", "burst_local_bwd_dkv", "burst_event_create", "burst_event_record",
     "burst_event_elapsed_ms", "burst_event_destroy", "burst_strerror", "burst_version",
     "burst_materialized_workspace_bytes", "burst_local_fwd_materialized", "burst_workspace_bytes",
+    "burst_materialized_bwd_workspace_bytes", "burst_local_bwd_materialized",
 ]
 
 
@@ -57,10 +58,15 @@ def load():
     lib.burst_finalize.argtypes = [fp, fp, fp, vp, fp, pp, vp]
     lib.burst_materialized_workspace_bytes.argtypes = [pp]
     lib.burst_materialized_workspace_bytes.restype = ctypes.c_size_t
+    lib.burst_materialized_bwd_workspace_bytes.argtypes = [pp]
+    lib.burst_materialized_bwd_workspace_bytes.restype = ctypes.c_size_t
     lib.burst_workspace_bytes.argtypes = [pp]
     lib.burst_workspace_bytes.restype = ctypes.c_size_t
     lib.burst_local_fwd_materialized.argtypes = [vp, vp, vp, fp, fp, fp, vp, ctypes.c_size_t, pp, vp]
     lib.burst_local_fwd_materialized.restype = ctypes.c_int
+    lib.burst_local_bwd_materialized.argtypes = [vp, vp, vp, vp, fp, fp, fp, fp, fp, ctypes.c_int, ctypes.c_int,
+                                                 vp, ctypes.c_size_t, pp, vp]
+    lib.burst_local_bwd_materialized.restype = ctypes.c_int
     lib.burst_merge_state.argtypes = [fp, fp, fp, fp, fp, fp, pp, vp]
     lib.burst_bwd_prepare.argtypes = [vp, vp, fp, pp, vp]
     lib.burst_local_bwd.argtypes = [vp, vp, vp, vp, vp, fp, fp, fp, fp, fp, ctypes.c_int, ctypes.c_int, pp, vp]
@@ -199,6 +205,20 @@ def burst_local_fwd_materialized(Q, K_chunk, V_chunk, O_acc, m, l, workspace, p)
     _check(load().burst_local_fwd_materialized(_q(Q, p), _kv(K_chunk, p), _kv(V_chunk, p), _f32(O_acc), _f32(m), _f32(l),
                                                _ptr(workspace), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
                                                ctypes.byref(p), _stream()), "burst_local_fwd_materialized")
+
+
+def burst_materialized_bwd_workspace_bytes(p):
+    return int(load().burst_materialized_bwd_workspace_bytes(ctypes.byref(p)))
+
+
+def burst_local_bwd_materialized(Q, K_chunk, V_chunk, dO, lse, D, dQ, dK_chunk, dV_chunk, workspace, p,
+                                 accumulate_dq=True, accumulate_dkv=False):
+    """workspace: a contiguous uint8 device tensor (see burst_materialized_bwd_workspace_bytes)."""
+    _check(load().burst_local_bwd_materialized(_q(Q, p), _kv(K_chunk, p), _kv(V_chunk, p), _q(dO, p), _f32(lse), _f32(D),
+                                               _f32(dQ), _f32(dK_chunk), _f32(dV_chunk),
+                                               1 if accumulate_dq else 0, 1 if accumulate_dkv else 0,
+                                               _ptr(workspace), ctypes.c_size_t(workspace.numel() * workspace.element_size()),
+                                               ctypes.byref(p), _stream()), "burst_local_bwd_materialized")
 
 
 def burst_finalize(O_acc, m, l, O_out, lse, p):

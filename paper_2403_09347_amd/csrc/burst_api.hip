@@ -27,6 +27,9 @@ int launch_bwd_dq_d64(const KParams&, const void*, const void*, const void*, con
 int launch_bwd_dkv_d64(const KParams&, const void*, const void*, const void*, const void*, const float*,
                        const float*, float*, float*, int, hipStream_t);
 size_t materialized_workspace_bytes(const KParams&, int);
+size_t materialized_bwd_workspace_bytes(const KParams&, int);
+int launch_bwd_materialized(const KParams&, int, bool, const void*, const void*, const void*, const void*, const float*,
+                            const float*, float*, float*, float*, int, int, void*, hipStream_t);
 int launch_fwd_materialized(const KParams&, int, bool, const void*, const void*, const void*, float*, float*, float*,
                             void*, hipStream_t);
 }  // namespace burst
@@ -223,6 +226,43 @@ int burst_local_fwd_materialized(const void* Q, const void* K_chunk, const void*
                                         (hipStream_t)stream);
 }
 
+size_t burst_materialized_bwd_workspace_bytes(const burst_params* p) {
+  KParams k;
+  if (check_params(p, &k) != BURST_OK) return 0;
+  return burst::materialized_bwd_workspace_bytes(k, p->dtype);
+}
+
+int burst_local_bwd_materialized(const void* Q, const void* K_chunk, const void* V_chunk,
+                                 const void* dO, const float* lse, const float* D,
+                                 float* dQ, float* dK_chunk, float* dV_chunk,
+                                 int accumulate_dq, int accumulate_dkv,
+                                 void* workspace, size_t workspace_bytes,
+                                 const burst_params* p, void* stream) {
+  KParams k;
+  int st = check_params(p, &k);
+  if (st != BURST_OK) return st;
+  const long long bh = (long long)k.B * k.H;
+  const bool have_q = bh * k.Nq > 0, have_k = bh * k.Nc > 0;
+  if (!have_q && !have_k) return BURST_OK;
+  if (have_q) { REQUIRE_PTR(Q); REQUIRE_PTR(dO); REQUIRE_PTR(lse); REQUIRE_PTR(D); REQUIRE_PTR(dQ); }
+  if (have_k) { REQUIRE_PTR(K_chunk); REQUIRE_PTR(V_chunk); REQUIRE_PTR(dK_chunk); REQUIRE_PTR(dV_chunk); }
+  if ((st = check_arch()) != BURST_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  if (!have_q || !have_k) {                        // nothing to contract over: the contribution is zero
+    if (have_q && !accumulate_dq && (st = burst::launch_zero_fill(dQ, bh * k.Nq * k.d, s)) != BURST_OK) return st;
+    if (have_k && !accumulate_dkv) {
+      if ((st = burst::launch_zero_fill(dK_chunk, bh / k.group * k.Nc * k.d, s)) != BURST_OK) return st;
+      if ((st = burst::launch_zero_fill(dV_chunk, bh / k.group * k.Nc * k.d, s)) != BURST_OK) return st;
+    }
+    return BURST_OK;
+  }
+  REQUIRE_PTR(workspace);
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return BURST_ERR_ALIGN;
+  if (workspace_bytes < burst::materialized_bwd_workspace_bytes(k, p->dtype)) return BURST_ERR_SHAPE;
+  return burst::launch_bwd_materialized(k, p->dtype, use_mfma(p, k), Q, K_chunk, V_chunk, dO, lse, D, dQ, dK_chunk,
+                                        dV_chunk, accumulate_dq != 0, accumulate_dkv != 0, workspace, s);
+}
+
 int burst_finalize(const float* O_acc, const float* m, const float* l,
                    void* O_out, float* lse, const burst_params* p, void* stream) {
   KParams k;
@@ -381,6 +421,6 @@ const char* burst_strerror(int status) {
   }
 }
 
-int burst_version(void) { return 105; }
+int burst_version(void) { return 106; }
 
 }  // extern "C"

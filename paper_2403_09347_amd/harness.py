@@ -95,6 +95,39 @@ class MaterializedWalk(RingWalk):
         B.burst_local_fwd_materialized(self.Q, K_c, V_c, self.O_acc, self.m, self.l, self.workspace,
                                        self.params(K_c.shape[2], k_off, mask, K_c))
 
+    def backward(self, Ks, Vs, k_offs, dO, dQ=None, dKs=None, dVs=None, use_D=True, masks=None):
+        """Alg. 2 with every matrix of a block pair stored in HBM (D is always computed first)."""
+        dev = self.Q.device
+        if dQ is None:
+            dQ = torch.zeros((self.Bt, self.H, self.Nq, self.d), device=dev, dtype=torch.float32)
+        if dKs is None:
+            dKs = [torch.empty(K.shape, device=dev, dtype=torch.float32) for K in Ks]
+            dVs = [torch.empty(V.shape, device=dev, dtype=torch.float32) for V in Vs]
+        if dO.stride() != self.Q.stride():
+            dO = torch.empty_strided(self.Q.shape, self.Q.stride(), device=dev, dtype=self.Q.dtype).copy_(dO)
+        self.prepare(dO)
+        for j in range(len(Ks)):
+            p = self.params(Ks[j].shape[2], k_offs[j], None if masks is None else masks[j], Ks[j])
+            need = B.burst_materialized_bwd_workspace_bytes(p)
+            if self.workspace is None or self.workspace.numel() < need:
+                self.workspace = torch.empty(max(need, 256), device=dev, dtype=torch.uint8)
+            B.burst_local_bwd_materialized(self.Q, Ks[j], Vs[j], dO, self.lse, self.D, dQ, dKs[j], dVs[j],
+                                           self.workspace, p, accumulate_dq=True, accumulate_dkv=False)
+        return dQ, dKs, dVs
+
+    def stored_gradients(self, Nc):
+        """Views of dP_ij (fp32), P_ij and dS_ij (input type) of the last backward step: [B, H, Nq, Nc]."""
+        ncp = (Nc + 7) // 8 * 8
+        rows = self.Bt * self.H * self.Nq
+        es = self.Q.element_size()
+        a = (rows * ncp * 4 + 255) // 256 * 256
+        b = a + (rows * ncp * es + 255) // 256 * 256
+        shape = (self.Bt, self.H, self.Nq, ncp)
+        dP = self.workspace[: rows * ncp * 4].view(torch.float32).view(shape)
+        P = self.workspace[a: a + rows * ncp * es].view(self.Q.dtype).view(shape)
+        dS = self.workspace[b: b + rows * ncp * es].view(self.Q.dtype).view(shape)
+        return dP[..., :Nc], P[..., :Nc], dS[..., :Nc]
+
     def stored_scores(self, Nc):
         """Views of S_ij (fp32) and P_ij (input type) of the last step: [B, H, Nq, Nc]."""
         ncp = (Nc + 7) // 8 * 8

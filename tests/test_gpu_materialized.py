@@ -68,6 +68,45 @@ def test_workspace_holds_the_scores_and_probabilities_of_the_block_pair(dtype, d
         assert np.all(got[rows_with_keys].max(axis=1) == 1.0)      # the row maximum itself gives P = 1
 
 
+@pytest.mark.parametrize("dtype,spec", CASES, ids=lambda v: v if isinstance(v, str) else "-".join(f"{k}{x}" for k, x in v.items()))
+def test_materialized_backward_against_the_oracle(dtype, spec):
+    """Alg. 2 with the matrices of every block pair stored in HBM, after the tiled forward."""
+    case = workloads.make_case(dtype=dtype, seed=61, device=DEV, **spec)
+    walk = MaterializedWalk(case["Q"], case["scale"], case["causal"], case["q_off"], case.get("window", 0),
+                            block=case.get("block", 0), kv_heads=case.get("kv_heads", 0))
+    O, lse = RingWalk.forward(walk, case["K"], case["V"], case["k_offs"], masks=case.get("masks"))
+    dQ, dKs, dVs = walk.backward(case["K"], case["V"], case["k_offs"], case["dO"], masks=case.get("masks"))
+    torch.cuda.synchronize()
+    compare_all_heads(case, dtype, O, lse, dQ, dKs, dVs)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 32)])
+def test_workspace_holds_the_gradient_matrices_of_the_block_pair(dtype, d):
+    """After one backward step the workspace holds dP_ij = dO V^T, P_ij = exp(S_ij - lse) and
+    dS_ij = P_ij o (dP_ij - D) (Alg. 2, loop body), hidden entries of P_ij and dS_ij 0."""
+    Nq, Nc = 150, 203
+    case = workloads.make_case(B=1, H=2, d=d, Nq=Nq, chunk_rows=[Nc], dtype=dtype, seed=69, device=DEV,
+                               causal=True, q_off=90, window=120)
+    walk = MaterializedWalk(case["Q"], case["scale"], True, 90, 120)
+    O, lse = walk.forward(case["K"], case["V"], case["k_offs"])
+    walk.backward(case["K"], case["V"], case["k_offs"], case["dO"])
+    torch.cuda.synchronize()
+    dP, P, dS = walk.stored_gradients(Nc)
+    qp, kp = 90 + np.arange(Nq), case["k_offs"][0] + np.arange(Nc)
+    vis = orc.visibility(qp, kp, True, 120)
+    tol = 1e-4 if dtype == "f32" else 2 ** -7
+    for h in range(2):
+        Qh, Kh, Vh, Gh = (f64(case[k][0, h]) if k in ("Q", "dO") else f64(case[k][0][0, h]) for k in ("Q", "K", "V", "dO"))
+        O_ref, lse_ref = orc.full_forward(Qh, Kh, Vh, case["scale"], True, qp, kp, window=120)
+        D_ref = orc.gao_bwd_prepare(O_ref, Gh)
+        P_ref, dP_ref, dS_ref = orc.gao_local_backward_matrices(Qh, Kh, Vh, Gh, lse_ref, D_ref, case["scale"], vis)
+        assert np.max(np.abs(f64(dP[0, h]) - dP_ref)) <= (1e-4 if dtype == "f32" else 1e-3) * max(1.0, np.abs(dP_ref).max())
+        got_P, got_dS = f64(P[0, h]), f64(dS[0, h])
+        assert not got_P[~vis].any() and not got_dS[~vis].any()
+        assert np.max(np.abs(got_P - P_ref)) <= tol
+        assert np.max(np.abs(got_dS - dS_ref)) <= tol * max(1.0, np.abs(dS_ref).max())
+
+
 def test_materialized_and_tiled_steps_interleave_on_one_state():
     """Both chunk steps keep the same kind of state: a walk may mix them."""
     case = workloads.make_case(B=1, H=2, d=128, Nq=200, chunk_rows=[100, 150, 90], dtype="bf16", seed=71, device=DEV)

@@ -486,3 +486,30 @@ def test_block_pattern_all_ones_is_no_pattern_and_hidden_rows_get_nothing():
     dQ, dK, dV = orc.full_backward(Q, K, V, dO, 0.5, pattern=pat)
     assert np.all(dQ[:3] == 0) and np.all(dK[3:6] == 0) and np.all(dV[3:6] == 0)
     assert np.allclose(dV.sum(axis=0), dO[3:].sum(axis=0), atol=1e-13)      # visible rows of P sum to 1
+
+
+def test_block_pair_gradient_matrices_brute_force_and_row_identities():
+    """Alg. 2's P, dP, dS of one block pair: every entry against scalar loops with math.exp on a
+    tiny causal case; with one chunk holding all keys, rows of P sum to 1 and rows of dS to 0
+    (sum_c P (dP - D) = D - D), and the three products of the loop body rebuild the gradients."""
+    rng = np.random.default_rng(77)
+    nq, nk, d, scale = 5, 7, 3, 0.6
+    Q, K, V, dO = (rng.standard_normal(s) for s in ((nq, d), (nk, d), (nk, d), (nq, d)))
+    qp, kp = 2 + np.arange(nq), np.arange(nk)
+    vis = orc.visibility(qp, kp, True)
+    O, lse = orc.full_forward(Q, K, V, scale, True, qp, kp)
+    D = orc.gao_bwd_prepare(O, dO)
+    P, dP, dS = orc.gao_local_backward_matrices(Q, K, V, dO, lse, D, scale, vis)
+    for r in range(nq):
+        for c in range(nk):
+            s = scale * sum(Q[r, t] * K[c, t] for t in range(d))
+            p = math.exp(s - lse[r]) if kp[c] <= qp[r] else 0.0
+            dp = sum(dO[r, t] * V[c, t] for t in range(d))
+            assert abs(P[r, c] - p) < 1e-13 and abs(dP[r, c] - dp) < 1e-13
+            assert abs(dS[r, c] - p * (dp - D[r])) < 1e-13
+    assert np.allclose(P.sum(axis=1), 1.0, atol=1e-13) and np.allclose(dS.sum(axis=1), 0.0, atol=1e-13)
+    dQ, dK, dV = orc.gao_local_backward(Q, K, V, dO, lse, D, scale, vis)
+    assert np.allclose(dV, P.T @ dO) and np.allclose(dQ, scale * dS @ K) and np.allclose(dK, scale * dS.T @ Q)
+    ref = orc.full_backward(Q, K, V, dO, scale, True, qp, kp)
+    for got, want in zip((dQ, dK, dV), ref):
+        assert np.max(np.abs(got - want)) < 1e-12
