@@ -126,6 +126,39 @@ def ablation_measurement(w, inp, reps):
                                      + 2 * tiled.m.numel() * 4) / 2**20}
 
 
+def hbm_step_measurement(w, walk, dO, reps=20):
+    """The HBM-bound steps of the path (Alg. 1 initialisation, merge and last two steps; Alg. 2's D)
+    one by one: `reps` launches between two events on the launch stream, algorithmic bytes per
+    launch over the average duration, against the 8 TB/s peak.  The launches of one step run back
+    to back on the same buffers, so the last-level cache may serve part of the traffic."""
+    import torch
+    from paper_2403_09347_amd import binding as B
+    es = 2 if w.dtype == "bf16" else 4
+    rows = w.B * w.H * w.Nq
+    state = rows * (4 * w.d + 8)
+    other = (torch.empty_like(walk.O_acc), torch.empty_like(walk.m), torch.empty_like(walk.l))
+    p = walk.params(0, 0)
+    B.burst_state_init(*other, p)
+    steps = {
+        "state_init": (lambda: B.burst_state_init(*other, p), state),
+        "merge_state": (lambda: B.burst_merge_state(*other, walk.O_acc, walk.m, walk.l, p), 3 * state),
+        "finalize": (lambda: walk.finalize(), state + rows * (es * w.d + 4)),
+        "bwd_prepare": (lambda: walk.prepare(dO), rows * (2 * es * w.d + 4)),
+    }
+    out = {}
+    for name, (fn, nbytes) in steps.items():
+        fn()
+        a, b = B.Event(), B.Event()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        ms = a.elapsed_ms_until(b) / reps
+        gbs = nbytes / (ms * 1e-3) / 1e9
+        out[name] = {"avg_launch_ms": round(ms, 5), "bytes": nbytes, "GB/s": round(gbs, 1), "frac_of_8TB/s": round(gbs / 8000.0, 4)}
+    return out
+
+
 def measured_traffic(kernel, workload):
     """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary (None if absent)."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
@@ -261,6 +294,7 @@ def main():
         "fwd_kernels_ms": fwd_ms, "bwd_kernels_ms": bwd_ms,
         "roofline": roofline,
     }
+    out["hbm_steps"] = hbm_step_measurement(w, walk, dO)
     if args.overlap:
         out["overlap"] = overlap_measurement(w, inp, args.overlap, max(3, args.steps // 2))
     if args.ablation:
