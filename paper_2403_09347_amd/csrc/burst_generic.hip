@@ -178,37 +178,37 @@ bwd_dkv_generic_kernel(GenArgs a) {
   if (!live) return;
   float k0a = 0.f, k1a = 0.f, v0a = 0.f, v1a = 0.f;
   for (int g = 0; g < a.group; g++) {                        // the query heads that share this key/value head
-  const int head = kvhead * a.group + g;
-  const T* Qh = (const T*)a.Q + a.lay.q_base(head);
-  const T* Gh = (const T*)a.dO + a.lay.q_base(head);
-  const float* lseh = a.lse + (size_t)head * a.Nq;
-  const float* Dh = a.D + (size_t)head * a.Nq;
-  for (int r0 = 0; r0 < a.Nq; r0 += 64) {
-    int row = r0 + lane;
-    float p = 0.f, ds = 0.f;
-    if (row < a.Nq && visible(a, head, row, key)) {
-      float lse = lseh[row];
-      if (lse != BURST_NEG_INF) {
-        float sa = 0.f, dp = 0.f;
-        const T* qr = Qh + (size_t)row * a.lay.qs_r;
-        const T* gr = Gh + (size_t)row * a.lay.qs_r;
-        for (int t = 0; t < a.d; t++) {
-          sa = __builtin_fmaf(ld(qr + t), krow[w][t], sa);
-          dp = __builtin_fmaf(ld(gr + t), vrow[w][t], dp);
+    const int head = kvhead * a.group + g;
+    const T* Qh = (const T*)a.Q + a.lay.q_base(head);
+    const T* Gh = (const T*)a.dO + a.lay.q_base(head);
+    const float* lseh = a.lse + (size_t)head * a.Nq;
+    const float* Dh = a.D + (size_t)head * a.Nq;
+    for (int r0 = 0; r0 < a.Nq; r0 += 64) {
+      int row = r0 + lane;
+      float p = 0.f, ds = 0.f;
+      if (row < a.Nq && visible(a, head, row, key)) {
+        float lse = lseh[row];
+        if (lse != BURST_NEG_INF) {
+          float sa = 0.f, dp = 0.f;
+          const T* qr = Qh + (size_t)row * a.lay.qs_r;
+          const T* gr = Gh + (size_t)row * a.lay.qs_r;
+          for (int t = 0; t < a.d; t++) {
+            sa = __builtin_fmaf(ld(qr + t), krow[w][t], sa);
+            dp = __builtin_fmaf(ld(gr + t), vrow[w][t], dp);
+          }
+          p = expf(sa * a.scale - lse);
+          ds = p * (dp - Dh[row]);
         }
-        p = expf(sa * a.scale - lse);
-        ds = p * (dp - Dh[row]);
+      }
+      int nr = min(64, a.Nq - r0);
+      for (int j = 0; j < nr; j++) {
+        float pj = __shfl(p, j), dsj = __shfl(ds, j);
+        const T* qr = Qh + (size_t)(r0 + j) * a.lay.qs_r;
+        const T* gr = Gh + (size_t)(r0 + j) * a.lay.qs_r;
+        if (lane < a.d) { v0a = __builtin_fmaf(pj, ld(gr + lane), v0a); k0a = __builtin_fmaf(dsj, ld(qr + lane), k0a); }
+        if (lane + 64 < a.d) { v1a = __builtin_fmaf(pj, ld(gr + lane + 64), v1a); k1a = __builtin_fmaf(dsj, ld(qr + lane + 64), k1a); }
       }
     }
-    int nr = min(64, a.Nq - r0);
-    for (int j = 0; j < nr; j++) {
-      float pj = __shfl(p, j), dsj = __shfl(ds, j);
-      const T* qr = Qh + (size_t)(r0 + j) * a.lay.qs_r;
-      const T* gr = Gh + (size_t)(r0 + j) * a.lay.qs_r;
-      if (lane < a.d) { v0a = __builtin_fmaf(pj, ld(gr + lane), v0a); k0a = __builtin_fmaf(dsj, ld(qr + lane), k0a); }
-      if (lane + 64 < a.d) { v1a = __builtin_fmaf(pj, ld(gr + lane + 64), v1a); k1a = __builtin_fmaf(dsj, ld(qr + lane + 64), k1a); }
-    }
-  }
   }
   float* dk = a.dK + kr_i * a.d;
   float* dv = a.dV + kr_i * a.d;

@@ -129,6 +129,37 @@ def test_strided_tensors(dtype, spec):
     assert all(torch.equal(a, b) for a, b in zip(dKs + dVs, dKs2 + dVs2))
 
 
+def test_rows_too_far_apart_for_the_mfma_kernels_take_the_generic_ones():
+    """The MFMA kernels reach a head's rows through 32-bit byte offsets; a call whose rows lie 4 MiB
+    apart (64 rows + the prefetch margin > 4 GiB) must still be answered, by the generic kernels."""
+    case = workloads.make_case(B=1, H=1, d=128, Nq=64, chunk_rows=[96], dtype="bf16", seed=47, device=DEV, causal=True,
+                               q_off=40)
+    pitch = 1 << 21                                                   # elements between rows
+    def spread(x):
+        big = torch.zeros((x.shape[2] - 1) * pitch + 128, dtype=x.dtype, device=DEV)
+        view = big.as_strided(x.shape, (0, 0, pitch, 1))
+        view.copy_(x)
+        return view
+    far = dict(case, Q=spread(case["Q"]), dO=spread(case["dO"]))
+    p = B.params(1, 1, 64, 96, 128, "bf16", case["scale"], q_strides=B.strides_of(far["Q"]))
+    assert tuple(p.q_strides) == (128, 128, pitch)
+    _, (O, lse, dQ, dKs, dVs) = run_case(far, "bf16")
+    compare_all_heads(case, "bf16", O, lse, dQ, dKs, dVs)
+
+
+def test_unaligned_strides_are_rejected_on_the_device_path():
+    case = workloads.make_case(B=1, H=2, d=128, Nq=64, chunk_rows=[64], dtype="bf16", seed=53, device=DEV)
+    walk = RingWalk(case["Q"], case["scale"])
+    walk.init()
+    p = B.params(1, 2, 64, 64, 128, "bf16", case["scale"], kv_strides=(64 * 2 * 128, 64 * 128, 132))
+    with pytest.raises(ValueError):                                   # the binding compares tensor and block
+        B.burst_local_fwd(case["Q"], case["K"][0], case["V"][0], walk.O_acc, walk.m, walk.l, p)
+    odd = torch.zeros((1, 2, 64, 132), dtype=torch.bfloat16, device=DEV)[..., :128]
+    p = B.params(1, 2, 64, 64, 128, "bf16", case["scale"], kv_strides=B.strides_of(odd))
+    with pytest.raises(B.BurstError):                                 # the library checks the block
+        B.burst_local_fwd(case["Q"], odd, odd, walk.O_acc, walk.m, walk.l, p)
+
+
 # bf16, d = 64: MFMA kernels of their own (32 rows or keys per wavefront, 64- and 32-key tiles).
 D64_CASES = [
     dict(B=1, H=2, d=64, Nq=32, chunk_rows=[32]),
