@@ -159,6 +159,27 @@ def hbm_step_measurement(w, walk, dO, reps=20):
     return out
 
 
+def graph_measurement(w, inp, reps):
+    """The same step recorded once as a HIP graph and replayed (one launch per step) against the
+    eager step (one launch per kernel): wall-clock ms per step over `reps` steps each."""
+    import torch
+    from paper_2403_09347_amd.harness import GraphedStep, RingWalk
+    k_offs = [w.k_off(j) for j in range(w.G)]
+    walk = RingWalk(inp["Q"], w.scale, w.causal, w.q_off)
+    step = GraphedStep(walk, inp["K"], inp["V"], k_offs, inp["dO"])
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / reps
+    eager, graph = timed(step._run), timed(step.replay)
+    return {"eager_ms_per_step": eager, "graph_ms_per_step": graph, "speedup": eager / graph}
+
+
 def measured_traffic(kernel, workload):
     """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary (None if absent)."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
@@ -186,6 +207,9 @@ def main():
     ap.add_argument("--ablation", action="store_true",
                     help="also time the forward and backward walks with the chunk steps that store S_ij, P_ij, dP_ij, dS_ij in HBM "
                          "(the paper's 'w/o LAO' ablation); adds an 'ablation' object to the JSON line")
+    ap.add_argument("--graph", action="store_true",
+                    help="also record the step as one HIP graph and time its replays against the eager step; "
+                         "adds a 'graph' object to the JSON line")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch a plain elementwise copy kernel of known size (256 MiB read, 256 MiB "
                          "written) so that HBM counters of a profiler run can be scaled")
@@ -297,6 +321,8 @@ def main():
     out["hbm_steps"] = hbm_step_measurement(w, walk, dO)
     if args.overlap:
         out["overlap"] = overlap_measurement(w, inp, args.overlap, max(3, args.steps // 2))
+    if args.graph:
+        out["graph"] = graph_measurement(w, inp, max(20, args.steps))
     if args.ablation:
         out["ablation"] = ablation_measurement(w, inp, max(3, args.steps // 2))
     if not args.no_cpu_baseline:

@@ -239,6 +239,45 @@ class DoubleBufferedWalk(RingWalk):
 
 
 
+class GraphedStep:
+    """One whole step (Alg. 1 walk, then Alg. 2 walk) of a fixed shape recorded once as a HIP
+    graph and replayed with a single launch: for chunks short enough that the launches, not
+    the kernels, set the pace.  The graph reads and writes the tensors it was recorded on: new
+    inputs are copied INTO `walk.Q`, the chunk tensors and `dO`, results are read from
+    `walk.O`, `walk.lse`, `dQ`, `dKs`, `dVs`.  Every node is a kernel (the gradient buffer is
+    cleared by a fill kernel, nothing is allocated or memset while recording)."""
+
+    def __init__(self, walk, Ks, Vs, k_offs, dO, masks=None):
+        assert type(walk) is RingWalk
+        dev = walk.Q.device
+        self.walk, self.Ks, self.Vs, self.k_offs, self.masks = walk, list(Ks), list(Vs), list(k_offs), masks
+        self.dO = dO if dO.stride() == walk.Q.stride() else \
+            torch.empty_strided(walk.Q.shape, walk.Q.stride(), device=dev, dtype=walk.Q.dtype).copy_(dO)
+        self.dQ = torch.zeros((walk.Bt, walk.H, walk.Nq, walk.d), device=dev, dtype=torch.float32)
+        self.dKs = [torch.empty(K.shape, device=dev, dtype=torch.float32) for K in Ks]
+        self.dVs = [torch.empty(V.shape, device=dev, dtype=torch.float32) for V in Vs]
+        # eager once on a side stream: first calls set kernel attributes, which a recording cannot hold
+        side = torch.cuda.Stream(device=dev)
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self._run()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self._run()
+
+    def _run(self):
+        w = self.walk
+        w.forward(self.Ks, self.Vs, self.k_offs, masks=self.masks)
+        self.dQ.zero_()
+        w.backward(self.Ks, self.Vs, self.k_offs, self.dO, self.dQ, self.dKs, self.dVs, masks=self.masks)
+
+    def replay(self):
+        self.graph.replay()
+        return self.walk.O, self.walk.lse, self.dQ, self.dKs, self.dVs
+
+
 class SpanWalk:
     """A device whose query rows are several contiguous spans of the sequence, each its own tensor
     with its own global offset -- e.g. the two stripes of a load-balanced ("zig-zag") causal

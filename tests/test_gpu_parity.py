@@ -653,3 +653,34 @@ def test_whole_ring_emulated_with_the_paper_orientation_backward(source):
         dKs.append(dK_i); dVs.append(dV_i)
     dQ = torch.cat([p["dQ"].to(DEV) for p in payloads], dim=2)
     compare_all_heads(case, "bf16", torch.cat(O_parts, dim=2), torch.cat(lse_parts, dim=2), dQ, dKs, dVs)
+
+
+@pytest.mark.parametrize("dtype,spec", [
+    ("f32", dict(B=1, H=1, d=64, Nq=256, chunk_rows=[256] * 4)),                                     # the tiny fp32 configuration
+    ("bf16", dict(B=1, H=3, d=128, Nq=300, chunk_rows=[200, 64, 331], causal=True, q_off=295)),
+    ("bf16", dict(B=1, H=4, d=64, Nq=256, chunk_rows=[256, 130], block=64, pattern="random", density=0.5, kv_heads=2)),
+])
+def test_step_recorded_as_a_graph_replays_bitwise(dtype, spec):
+    """A whole step recorded as one HIP graph: three replays, each on new input values copied into
+    the recorded tensors, with eager work and synchronisations of its own between them, every
+    replay bitwise equal to the eager step on the same values; the last one also against the oracle."""
+    from paper_2403_09347_amd.harness import GraphedStep
+    case = workloads.make_case(dtype=dtype, seed=101, device=DEV, **spec)
+    args = (case["scale"], case["causal"], case["q_off"], case.get("window", 0), case.get("block", 0), case.get("kv_heads", 0))
+    walk = RingWalk(case["Q"].clone(), *args)
+    Ks, Vs, dO = [k.clone() for k in case["K"]], [v.clone() for v in case["V"]], case["dO"].clone()
+    step = GraphedStep(walk, Ks, Vs, case["k_offs"], dO, masks=case.get("masks"))
+    for rep in range(3):
+        fresh = workloads.make_case(dtype=dtype, seed=200 + rep, device=DEV, **spec) if rep < 2 else case
+        if "masks" in case:                                            # the recording holds the block flags
+            fresh = dict(fresh, masks=case["masks"], flags=case["flags"])
+        walk.Q.copy_(fresh["Q"]); dO.copy_(fresh["dO"])
+        for dst, src in zip(Ks + Vs, fresh["K"] + fresh["V"]):
+            dst.copy_(src)
+        O, lse, dQ, dKs, dVs = step.replay()
+        torch.cuda.synchronize()
+        got = [t.clone() for t in (O, lse, dQ, *dKs, *dVs)]
+        _, (O2, lse2, dQ2, dKs2, dVs2) = run_case(fresh, dtype)           # eager work between the replays
+        for a, b in zip(got, (O2, lse2, dQ2, *dKs2, *dVs2)):
+            assert torch.equal(a, b)
+    compare_all_heads(case, dtype, got[0], got[1], got[2], got[3:3 + len(Ks)], got[3 + len(Ks):])
