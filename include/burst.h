@@ -196,6 +196,14 @@ int burst_local_bwd_materialized(const void* Q, const void* K_chunk, const void*
                                  void* workspace, size_t workspace_bytes,
                                  const burst_params* p, void* stream);
 
+/* For tests and tuning (no counterpart in the paper): which of the two kernel families serves
+ * dense bf16, d = 128 forward and dQ calls.  0 = chosen per call from how well its workgroups
+ * fill the chip (the default); 1 = always the hand-scheduled kernels (256 query rows per
+ * workgroup); 2 = always the plainly written ones (128 rows per workgroup).  Process-wide;
+ * results of the two families agree within the tolerance, not bitwise.  Returns
+ * BURST_ERR_SHAPE for another value. */
+int burst_set_kernel_family(int family);
+
 /* Timing helper for harnesses that cannot create HIP events themselves:
  * records/queries events on the same stream the kernels are launched on.
  * burst_event_create returns an opaque handle (NULL on failure). */

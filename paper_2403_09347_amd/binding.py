@@ -19,7 +19,7 @@ EXPORTS = [
     "burst_bwd_prepare", "burst_local_bwd", "burst_local_bwd_dq", "burst_local_bwd_dkv", "burst_event_create", "burst_event_record",
     "burst_event_elapsed_ms", "burst_event_destroy", "burst_strerror", "burst_version",
     "burst_materialized_workspace_bytes", "burst_local_fwd_materialized", "burst_workspace_bytes",
-    "burst_materialized_bwd_workspace_bytes", "burst_local_bwd_materialized",
+    "burst_materialized_bwd_workspace_bytes", "burst_local_bwd_materialized", "burst_set_kernel_family",
 ]
 
 
@@ -190,6 +190,14 @@ def burst_state_init(O_acc, m, l, p):
 def burst_local_fwd(Q, K_chunk, V_chunk, O_acc, m, l, p):
     _check(load().burst_local_fwd(_q(Q, p), _kv(K_chunk, p), _kv(V_chunk, p), _f32(O_acc), _f32(m), _f32(l),
                                   ctypes.byref(p), _stream()), "burst_local_fwd")
+
+
+def burst_set_kernel_family(family):
+    """0 = automatic, 1 = hand-scheduled d = 128 kernels only, 2 = plainly written ones (see burst.h)."""
+    lib = load()
+    lib.burst_set_kernel_family.argtypes = [ctypes.c_int]
+    lib.burst_set_kernel_family.restype = ctypes.c_int
+    _check(lib.burst_set_kernel_family(int(family)), "burst_set_kernel_family")
 
 
 def burst_workspace_bytes(p):

@@ -1,5 +1,6 @@
 // C ABI (see include/burst.h): argument validation and dispatch to the kernels.
 #include <hip/hip_runtime.h>
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <mutex>
@@ -21,11 +22,18 @@ int launch_bwd_dq_generic(const KParams&, int, const void*, const void*, const v
                           const float*, float*, int, hipStream_t);
 int launch_bwd_dkv_generic(const KParams&, int, const void*, const void*, const void*, const void*, const float*,
                            const float*, float*, float*, int, hipStream_t);
-int launch_fwd_d64(const KParams&, const void*, const void*, const void*, float*, float*, float*, hipStream_t);
-int launch_bwd_dq_d64(const KParams&, const void*, const void*, const void*, const void*, const float*,
-                      const float*, float*, int, hipStream_t);
-int launch_bwd_dkv_d64(const KParams&, const void*, const void*, const void*, const void*, const float*,
-                       const float*, float*, float*, int, hipStream_t);
+namespace d64 {
+int launch_fwd(const KParams&, const void*, const void*, const void*, float*, float*, float*, hipStream_t);
+int launch_bwd_dq(const KParams&, const void*, const void*, const void*, const void*, const float*,
+                  const float*, float*, int, hipStream_t);
+int launch_bwd_dkv(const KParams&, const void*, const void*, const void*, const void*, const float*,
+                   const float*, float*, float*, int, hipStream_t);
+}  // namespace d64
+namespace d128p {
+int launch_fwd(const KParams&, const void*, const void*, const void*, float*, float*, float*, hipStream_t);
+int launch_bwd_dq(const KParams&, const void*, const void*, const void*, const void*, const float*,
+                  const float*, float*, int, hipStream_t);
+}  // namespace d128p
 size_t materialized_workspace_bytes(const KParams&, int);
 size_t materialized_bwd_workspace_bytes(const KParams&, int);
 int launch_bwd_materialized(const KParams&, int, bool, const void*, const void*, const void*, const void*, const float*,
@@ -129,16 +137,32 @@ bool use_mfma(const burst_params* p, const KParams& k) {
   return p->dtype == BURST_BF16 && p->d == 128 && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows && spans_fit(p, k);
 }
 // bf16, d = 64 has MFMA kernels of its own.
-#ifndef BURST_SMALL_D
-#define BURST_SMALL_D 64
-#endif
 bool use_d64(const burst_params* p, const KParams& k) {
-  if (!(p->dtype == BURST_BF16 && p->d == BURST_SMALL_D && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows &&
+  if (!(p->dtype == BURST_BF16 && p->d == 64 && p->Nq <= kMaxMfmaRows && p->Nc <= kMaxMfmaRows &&
         spans_fit(p, k))) return false;
   if (p->block_mask == nullptr) return true;
   // with block flags: lists of at most 4096 tiles (32 keys or rows each; rows of all heads of a group)
   const long long group = (p->kv_heads > 0) ? p->H / p->kv_heads : 1;
   return p->Nc <= 4096 * 32 && group * ((p->Nq + 31) / 32) <= 4096;
+}
+// The forward and dQ kernels for d = 128 run one 256-row workgroup per CU, so a call takes
+// ceil(workgroups / 256) rounds on the chip's 256 CUs.  When the last round is poorly filled
+// (less than 70 % of the CU slots of all rounds are used: short query slices, or a workgroup count
+// just above a multiple of 256) the plainly written kernels with 128 rows per workgroup and two
+// workgroups per CU do better: 1.3-1.5x (forward) and 1.1-1.25x (backward) at up to 128
+// workgroups, 15 % at 320; they lose 3-5 % where the rounds are full.  Calls with block flags
+// keep the list-driven kernels.
+#ifndef BURST_PLAIN128_FILL_PERCENT
+#define BURST_PLAIN128_FILL_PERCENT 70
+#endif
+std::atomic<int> g_kernel_family{0};            // burst_set_kernel_family
+bool use_plain128(const burst_params* p, const KParams& k) {
+  if (!use_mfma(p, k) || p->block_mask != nullptr) return false;
+  const int family = g_kernel_family.load(std::memory_order_relaxed);
+  if (family != 0) return family == 2;
+  const long long wgs = (long long)p->B * p->H * ((p->Nq + 255) / 256);
+  const long long rounds = (wgs + 255) / 256;
+  return wgs * 100 < (long long)BURST_PLAIN128_FILL_PERCENT * 256 * rounds;
 }
 // The dK/dV MFMA kernel walks the query tiles of all heads of a group as one list: whole 64-row
 // tiles per head and at most 8192 tiles in all; other grouped shapes take the generic kernel.
@@ -190,10 +214,17 @@ int burst_local_fwd(const void* Q, const void* K_chunk, const void* V_chunk,
   REQUIRE_PTR(Q); REQUIRE_PTR(K_chunk); REQUIRE_PTR(V_chunk);
   REQUIRE_PTR(O_acc); REQUIRE_PTR(m); REQUIRE_PTR(l);
   if ((st = check_arch()) != BURST_OK) return st;
-  if (use_d64(p, k)) return burst::launch_fwd_d64(k, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
+  if (use_d64(p, k)) return burst::d64::launch_fwd(k, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
+  if (use_plain128(p, k)) return burst::d128p::launch_fwd(k, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
   if (use_mfma(p, k) && (p->block_mask == nullptr || p->Nc <= kMaxMaskedRows))
     return burst::launch_fwd_mfma(k, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
   return burst::launch_fwd_generic(k, p->dtype, Q, K_chunk, V_chunk, O_acc, m, l, (hipStream_t)stream);
+}
+
+int burst_set_kernel_family(int family) {
+  if (family < 0 || family > 2) return BURST_ERR_SHAPE;
+  g_kernel_family.store(family, std::memory_order_relaxed);
+  return BURST_OK;
 }
 
 size_t burst_workspace_bytes(const burst_params* p) {
@@ -339,16 +370,17 @@ static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const v
   const bool mfma_dkv = use_mfma(p, k) && dkv_mfma_ok(p, k);
   if (use_d64(p, k)) {
     if (want_dq &&
-        (st = burst::launch_bwd_dq_d64(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)) != BURST_OK)
+        (st = burst::d64::launch_bwd_dq(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)) != BURST_OK)
       return st;
     if (want_dkv &&
-        (st = burst::launch_bwd_dkv_d64(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk,
+        (st = burst::d64::launch_bwd_dkv(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk,
                                         accumulate_dkv != 0, s)) != BURST_OK)
       return st;
     return BURST_OK;
   }
   if (want_dq) {
-    st = mfma_dq ? burst::launch_bwd_dq_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)
+    st = use_plain128(p, k) ? burst::d128p::launch_bwd_dq(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)
+       : mfma_dq ? burst::launch_bwd_dq_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)
               : burst::launch_bwd_dq_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dQ,
                                              accumulate_dq != 0, s);
     if (st != BURST_OK) return st;
@@ -421,6 +453,6 @@ const char* burst_strerror(int status) {
   }
 }
 
-int burst_version(void) { return 106; }
+int burst_version(void) { return 107; }
 
 }  // extern "C"

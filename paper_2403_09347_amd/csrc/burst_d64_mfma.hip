@@ -13,13 +13,20 @@
 //
 // LDS tile layout: rows of 128 bytes (8 granules of 16 bytes); granule g of row r sits at slot
 // g ^ ((r >> 1) & 7), which makes the 128-bit operand reads of 32 consecutive rows conflict-free.
+//
+// The head dimension is a compile-time constant of this source.  The same kernels compiled for
+// d = 128 (burst_d128_plain.hip) serve calls too small to fill the chip with the 256-row
+// workgroups of the hand-scheduled d = 128 kernels.
 #include "burst_bwd_common.h"
-
-namespace burst {
 
 #ifndef BURST_SMALL_D
 #define BURST_SMALL_D 64
+#define BURST_SMALL_NS d64
 #endif
+
+namespace burst {
+namespace BURST_SMALL_NS {
+
 constexpr int S_D = BURST_SMALL_D;
 constexpr int S_ROWB = S_D * 2;                   // bytes per row
 constexpr int S_KS = S_D / 16;                    // k-steps of a contraction over d
@@ -481,6 +488,7 @@ burst_bwd_dq_d64_kernel(BwdArgs a) {
   }
 }
 
+#ifndef BURST_SMALL_NO_DKV
 // ------------------------------------------------------------------------------- backward, dK / dV
 constexpr int SK_BC = 128;                        // keys per workgroup (4 wavefronts x 32)
 constexpr int SK_BR = 32;                         // query rows per tile
@@ -676,8 +684,10 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
   }
 }
 
+#endif  // BURST_SMALL_NO_DKV
+
 // ------------------------------------------------------------------------------- launchers
-int launch_fwd_d64(const KParams& p, const void* Q, const void* K, const void* V,
+int launch_fwd(const KParams& p, const void* Q, const void* K, const void* V,
                    float* O_acc, float* m, float* l, hipStream_t stream) {
   FwdArgsLite a;
   a.Q = (const bf16*)Q; a.K = (const bf16*)K; a.V = (const bf16*)V;
@@ -700,7 +710,7 @@ int launch_fwd_d64(const KParams& p, const void* Q, const void* K, const void* V
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 
-int launch_bwd_dq_d64(const KParams& p, const void* Q, const void* K, const void* V,
+int launch_bwd_dq(const KParams& p, const void* Q, const void* K, const void* V,
                       const void* dO, const float* lse, const float* D, float* dQ, int acc_dq,
                       hipStream_t stream) {
   if (p.Nq <= 0) return BURST_OK;
@@ -718,7 +728,8 @@ int launch_bwd_dq_d64(const KParams& p, const void* Q, const void* K, const void
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 
-int launch_bwd_dkv_d64(const KParams& p, const void* Q, const void* K, const void* V,
+#ifndef BURST_SMALL_NO_DKV
+int launch_bwd_dkv(const KParams& p, const void* Q, const void* K, const void* V,
                        const void* dO, const float* lse, const float* D, float* dK, float* dV,
                        int acc_dkv, hipStream_t stream) {
   if (p.Nc <= 0) return BURST_OK;
@@ -737,4 +748,7 @@ int launch_bwd_dkv_d64(const KParams& p, const void* Q, const void* K, const voi
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 
+#endif
+
+}  // namespace BURST_SMALL_NS
 }  // namespace burst

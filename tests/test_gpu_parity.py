@@ -13,6 +13,15 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
+@pytest.fixture(autouse=True, params=[1, 2], ids=["hand-scheduled", "plain"])
+def kernel_family(request):
+    """Every test of this file runs once with each of the two kernel families for dense bf16,
+    d = 128 calls (the automatic choice would give these small shapes to one of them only)."""
+    B.burst_set_kernel_family(request.param)
+    yield request.param
+    B.burst_set_kernel_family(0)
+
+
 def run_case(case, dtype, backward=True, use_D=True, order=None):
     walk = RingWalk(case["Q"], case["scale"], case["causal"], case["q_off"], case.get("window", 0),
                     case.get("block", 0), case.get("kv_heads", 0))
