@@ -146,23 +146,20 @@ bool use_d64(const burst_params* p, const KParams& k) {
   return p->Nc <= 4096 * 32 && group * ((p->Nq + 31) / 32) <= 4096;
 }
 // The forward and dQ kernels for d = 128 run one 256-row workgroup per CU, so a call takes
-// ceil(workgroups / 256) rounds on the chip's 256 CUs.  When the last round is poorly filled
-// (less than 70 % of the CU slots of all rounds are used: short query slices, or a workgroup count
-// just above a multiple of 256) the plainly written kernels with 128 rows per workgroup and two
-// workgroups per CU do better: 1.3-1.5x (forward) and 1.1-1.25x (backward) at up to 128
-// workgroups, 15 % at 320; they lose 3-5 % where the rounds are full.  Calls with block flags
-// keep the list-driven kernels.
-#ifndef BURST_PLAIN128_FILL_PERCENT
-#define BURST_PLAIN128_FILL_PERCENT 70
-#endif
+// ceil(workgroups / 256) rounds on the chip's 256 CUs.  When the last round is at most half full
+// (short query slices, or a workgroup count just above a multiple of 256) the plainly written
+// kernels with 128 rows per workgroup and two workgroups per CU do better: 1.3-1.5x (forward)
+// and 1.1-1.25x (backward) at up to 128 workgroups, 15 % at 320, 3-6 % (forward) at 384 .. 1152;
+// they lose 3-6 % where the rounds are full, and the gain fades as the rounds grow in number.
+// Calls with block flags keep the list-driven kernels.
 std::atomic<int> g_kernel_family{0};            // burst_set_kernel_family
 bool use_plain128(const burst_params* p, const KParams& k) {
   if (!use_mfma(p, k) || p->block_mask != nullptr) return false;
   const int family = g_kernel_family.load(std::memory_order_relaxed);
   if (family != 0) return family == 2;
   const long long wgs = (long long)p->B * p->H * ((p->Nq + 255) / 256);
-  const long long rounds = (wgs + 255) / 256;
-  return wgs * 100 < (long long)BURST_PLAIN128_FILL_PERCENT * 256 * rounds;
+  const long long last = wgs % 256;                // workgroups of the last round (0 = full)
+  return last != 0 && last <= 128 && wgs <= 1536;
 }
 // The dK/dV MFMA kernel walks the query tiles of all heads of a group as one list: whole 64-row
 // tiles per head and at most 8192 tiles in all; other grouped shapes take the generic kernel.
