@@ -97,6 +97,7 @@ burst_bwd_dq_kernel(BwdArgs a) {
     int xcd = bid & 7, idx = bid >> 3;
     int hx = idx / a.blocks_per_head;
     qb = idx - hx * a.blocks_per_head;
+    if (a.causal) qb = a.blocks_per_head - 1 - qb;   // longest blocks of a head first (see the forward kernel)
     head = hx * 8 + xcd;
     if (head >= a.H) return;
   }

@@ -128,6 +128,7 @@ burst_fwd_d64_kernel(FwdArgsLite a) {
   int head, qb;
   s_head_block(blockIdx.x, a.blocks_per_head, head, qb);
   if (head >= a.H) return;
+  if (a.causal) qb = a.blocks_per_head - 1 - qb;   // later blocks see more keys: the long ones start first
   const int q0 = qb * SF_BR + w * 32;
   const bf16* Qh = a.Q + a.lay.q_base(head);
   const bf16* Kh = a.K + a.lay.kv_base(head / a.group);
@@ -331,6 +332,7 @@ burst_bwd_dq_d64_kernel(BwdArgs a) {
   int head, qb;
   s_head_block(blockIdx.x, a.blocks_per_head, head, qb);
   if (head >= a.H) return;
+  if (a.causal) qb = a.blocks_per_head - 1 - qb;   // later blocks see more keys: the long ones start first
   const int q0 = qb * SQ_BR + w * 32;
   const int row = q0 + lr;
   const bool ok = row < a.Nq;

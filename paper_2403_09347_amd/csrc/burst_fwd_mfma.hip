@@ -123,6 +123,9 @@ burst_fwd_mfma_kernel(FwdArgs a) {
     int xcd = bid & 7, idx = bid >> 3;
     int hx = idx / a.q_blocks;
     qb = idx - hx * a.q_blocks;
+    // causal: the later a query block, the more key tiles it sees; the blocks of a head start
+    // in descending order so that the long ones do not end up in the last round
+    if (a.causal) qb = a.q_blocks - 1 - qb;
     head = hx * 8 + xcd;
     if (head >= a.H) return;                       // whole workgroup exits together
   }
