@@ -151,12 +151,16 @@ bool use_d64(const burst_params* p, const KParams& k) {
 // kernels with 128 rows per workgroup and two workgroups per CU do better: 1.3-1.5x (forward)
 // and 1.1-1.25x (backward) at up to 128 workgroups, 15 % at 320, 3-6 % (forward) at 384 .. 1152;
 // they lose 3-6 % where the rounds are full, and the gain fades as the rounds grow in number.
-// Calls with block flags keep the list-driven kernels.
 std::atomic<int> g_kernel_family{0};            // burst_set_kernel_family
 bool use_plain128(const burst_params* p, const KParams& k) {
-  if (!use_mfma(p, k) || p->block_mask != nullptr) return false;
+  if (!use_mfma(p, k)) return false;
+  const bool flags = p->block_mask != nullptr;
+  if (flags && p->Nc > 4096 * 32) return false;    // their tile lists hold 4096 entries (32-key tiles in dQ)
   const int family = g_kernel_family.load(std::memory_order_relaxed);
   if (family != 0) return family == 2;
+  // Block flags finer than the 256-row workgroups of the list-driven kernels: the plain kernels
+  // skip per wavefront (32 rows x 64 or 32 keys), which is what such patterns need.
+  if (flags) return p->block < 256;
   const long long wgs = (long long)p->B * p->H * ((p->Nq + 255) / 256);
   const long long last = wgs % 256;                // workgroups of the last round (0 = full)
   return last != 0 && last <= 128 && wgs <= 1536;

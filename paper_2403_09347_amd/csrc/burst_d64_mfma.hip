@@ -217,6 +217,7 @@ burst_fwd_d64_kernel(FwdArgsLite a) {
     __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0), lgkmcnt(0): the tile landed, reads of the one before are done
     __builtin_amdgcn_s_barrier();
     if (j + 1 < ntiles) dma_tile(entry_at(j + 1) & 0xfffff, (j + 1) & 1);
+    if (!mine) continue;                           // block flags hide the tile from this wavefront's rows
     const char* kl = smem + (j & 1) * SF_TILE;
     const char* vl = smem + (2 + (j & 1)) * SF_TILE;
     // S^T = K Q^T: register r of key block kb = key kt*64 + kb*32 + 8*(r/4) + 4h + r%4
@@ -233,13 +234,12 @@ burst_fwd_d64_kernel(FwdArgsLite a) {
     const long long tile_first_k = k_off + (long long)kt * SF_BC;
     const bool need_mask = (a.causal && tile_first_k + SF_BC - 1 > wave_first_q) ||
                            (a.window > 0 && tile_first_k < wave_last_q - a.window + 1) ||
-                           ((kt + 1) * SF_BC > Nc) || !mine;
+                           ((kt + 1) * SF_BC > Nc);
     if (need_mask) {
       const long long dd = (a.q_off - k_off) + (q0 + lr) - ((long long)kt * SF_BC + 4 * h);
       const int tail = Nc - 1 - (kt * SF_BC + 4 * h);
       int lim = a.causal ? (int)(dd < -1 ? -1 : (dd > 64 ? 64 : dd)) : 64;
       lim = lim < tail ? lim : tail;
-      if (!mine) lim = -1;
       const long long dl = dd - a.window + 1;
       const int lim_lo = a.window > 0 ? (int)(dl < -1 ? -1 : (dl > 64 ? 64 : dl)) : -1;
 #pragma unroll
@@ -427,6 +427,7 @@ burst_bwd_dq_d64_kernel(BwdArgs a) {
       __builtin_amdgcn_s_waitcnt(0x0070);
       __builtin_amdgcn_s_barrier();
       if (j + 1 < ntiles) dma_tile(entry_at(j + 1) & 0xfffff, (j + 1) & 1);
+      if (!mine) continue;                         // block flags hide the tile from this wavefront's rows
       const char* kl = smem + (j & 1) * SQ_TILE;
       const char* vl = smem + (2 + (j & 1)) * SQ_TILE;
       // S^T = K Q^T, dP^T = V dO^T: register r = key kt*32 + 8*(r/4) + 4h + r%4
@@ -441,13 +442,12 @@ burst_bwd_dq_d64_kernel(BwdArgs a) {
       const long long tile_first_k = k_off + (long long)kt * SQ_BC;
       const bool need_mask = (a.causal && tile_first_k + SQ_BC - 1 > wave_first_q) ||
                              (a.window > 0 && tile_first_k < wave_first_q + 31 - a.window + 1) ||
-                             ((kt + 1) * SQ_BC > Nc) || !mine;
+                             ((kt + 1) * SQ_BC > Nc);
       if (need_mask) {
         const long long dd = (a.q_off - k_off) + (q0 + lr) - ((long long)kt * SQ_BC + 4 * h);
         const int tail = Nc - 1 - (kt * SQ_BC + 4 * h);
         int lim = a.causal ? (int)(dd < -1 ? -1 : (dd > 64 ? 64 : dd)) : 64;
         lim = lim < tail ? lim : tail;
-        if (!mine) lim = -1;
         const long long dl = dd - a.window + 1;
         const int lim_lo = a.window > 0 ? (int)(dl < -1 ? -1 : (dl > 64 ? 64 : dl)) : -1;
 #pragma unroll
@@ -615,54 +615,56 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
       const char* gl = smem + (2 + buf) * SK_TILE;
       int g_unused, t;
       const bool mine = ((locate(n, g_unused, t) >> wu) & 1) != 0;
-      // S = Q K^T, dP = dO V^T: lane = key lr, register r = row t*32 + 8*(r/4) + 4h + r%4
-      f32x16 s, dp;
+      if (mine) {                                  // (else: block flags hide this wavefront's keys from the tile)
+        // S = Q K^T, dP = dO V^T: lane = key lr, register r = row t*32 + 8*(r/4) + 4h + r%4
+        f32x16 s, dp;
 #pragma unroll
-      for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+        for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
-      for (int ks = 0; ks < S_KS; ks++) {
-        s = mfma32(lds_read_b128(ql, qaddr[ks]), kf[ks], s);
-        dp = mfma32(lds_read_b128(gl, qaddr[ks]), vf[ks], dp);
-      }
-      const long long tile_first_q = a.q_off + (long long)t * SK_BR;
-      const bool need_mask = (a.causal && wave_last_k > tile_first_q) ||
-                             (a.window > 0 && tile_first_q + SK_BR - 1 >= wave_first_k + a.window) || !mine;
-      if (need_mask) {
-        // visible iff key position <= row position (constant part >= lim) and row position <
-        // key position + window (constant part <= lim2)
-        const long long d = kpos - (tile_first_q + 4 * h);
-        const int lim = !mine ? 65 : a.causal ? (int)(d < -1 ? -1 : (d > 64 ? 64 : d)) : -1;
-        const long long d2 = d + a.window - 1;
-        const int lim2 = a.window > 0 ? (int)(d2 < -1 ? -1 : (d2 > 64 ? 64 : d2)) : 64;
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-          const int cpart = 8 * (r >> 2) + (r & 3);
-          if (!(cpart >= lim && cpart <= lim2)) s[r] = BURST_NEG_INF;
+        for (int ks = 0; ks < S_KS; ks++) {
+          s = mfma32(lds_read_b128(ql, qaddr[ks]), kf[ks], s);
+          dp = mfma32(lds_read_b128(gl, qaddr[ks]), vf[ks], dp);
         }
-      }
-      bf16x8 pf[2], dsf[2];                        // per 16-row group: A operands of dV, dK
+        const long long tile_first_q = a.q_off + (long long)t * SK_BR;
+        const bool need_mask = (a.causal && wave_last_k > tile_first_q) ||
+                               (a.window > 0 && tile_first_q + SK_BR - 1 >= wave_first_k + a.window);
+        if (need_mask) {
+          // visible iff key position <= row position (constant part >= lim) and row position <
+          // key position + window (constant part <= lim2)
+          const long long d = kpos - (tile_first_q + 4 * h);
+          const int lim = a.causal ? (int)(d < -1 ? -1 : (d > 64 ? 64 : d)) : -1;
+          const long long d2 = d + a.window - 1;
+          const int lim2 = a.window > 0 ? (int)(d2 < -1 ? -1 : (d2 > 64 ? 64 : d2)) : 64;
 #pragma unroll
-      for (int q4 = 0; q4 < 4; q4++) {
-        const f32x4 nl = *reinterpret_cast<const f32x4*>(stat + buf * 64 + 8 * q4 + 4 * h);
-        const f32x4 dr = *reinterpret_cast<const f32x4*>(stat + buf * 64 + 32 + 8 * q4 + 4 * h);
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-          const int r = 4 * q4 + j;
-          const float p = fast_exp2(__builtin_fmaf(s[r], a.c, nl[j]));
-          pf[r >> 3][r & 7] = (bf16)p;
-          dsf[r >> 3][r & 7] = (bf16)(p * (dp[r] - dr[j]));
+          for (int r = 0; r < 16; r++) {
+            const int cpart = 8 * (r >> 2) + (r & 3);
+            if (!(cpart >= lim && cpart <= lim2)) s[r] = BURST_NEG_INF;
+          }
         }
-      }
-      // dV += P^T dO, dK += dS^T Q (dO and Q through transposing reads)
+        bf16x8 pf[2], dsf[2];                        // per 16-row group: A operands of dV, dK
 #pragma unroll
-      for (int u = 0; u < 2; u++)
+        for (int q4 = 0; q4 < 4; q4++) {
+          const f32x4 nl = *reinterpret_cast<const f32x4*>(stat + buf * 64 + 8 * q4 + 4 * h);
+          const f32x4 dr = *reinterpret_cast<const f32x4*>(stat + buf * 64 + 32 + 8 * q4 + 4 * h);
 #pragma unroll
-        for (int db = 0; db < S_DB; db++) {
-          const bf16x8 bg = cat4(lds_read_tr(gl, u * 16 * S_ROWB + taddr[db][0]), lds_read_tr(gl, u * 16 * S_ROWB + taddr[db][1]));
-          const bf16x8 bq = cat4(lds_read_tr(ql, u * 16 * S_ROWB + taddr[db][0]), lds_read_tr(ql, u * 16 * S_ROWB + taddr[db][1]));
-          dv[db] = mfma32(pf[u], bg, dv[db]);
-          dk[db] = mfma32(dsf[u], bq, dk[db]);
+          for (int j = 0; j < 4; j++) {
+            const int r = 4 * q4 + j;
+            const float p = fast_exp2(__builtin_fmaf(s[r], a.c, nl[j]));
+            pf[r >> 3][r & 7] = (bf16)p;
+            dsf[r >> 3][r & 7] = (bf16)(p * (dp[r] - dr[j]));
+          }
         }
+        // dV += P^T dO, dK += dS^T Q (dO and Q through transposing reads)
+#pragma unroll
+        for (int u = 0; u < 2; u++)
+#pragma unroll
+          for (int db = 0; db < S_DB; db++) {
+            const bf16x8 bg = cat4(lds_read_tr(gl, u * 16 * S_ROWB + taddr[db][0]), lds_read_tr(gl, u * 16 * S_ROWB + taddr[db][1]));
+            const bf16x8 bq = cat4(lds_read_tr(ql, u * 16 * S_ROWB + taddr[db][0]), lds_read_tr(ql, u * 16 * S_ROWB + taddr[db][1]));
+            dv[db] = mfma32(pf[u], bg, dv[db]);
+            dk[db] = mfma32(dsf[u], bq, dk[db]);
+          }
+      }
       if (n + 1 < nwalk) stat_commit((n + 1) & 1);
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -686,9 +688,24 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
   }
 }
 
+
 #endif  // BURST_SMALL_NO_DKV
 
 // ------------------------------------------------------------------------------- launchers
+// Tile lists are dynamic LDS behind up to 64 KB of static tiles: the kernels that take one opt
+// in to the larger total once per device.
+template <typename K>
+static int allow_list(K kernel, bool* done) {
+  const int dev = current_device_slot();
+  if (dev < 0) return BURST_ERR_LAUNCH;
+  if (!done[dev]) {
+    if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (S_MAX_LIST + 4) * 4) != hipSuccess)
+      return BURST_ERR_LAUNCH;
+    done[dev] = true;
+  }
+  return BURST_OK;
+}
+
 int launch_fwd(const KParams& p, const void* Q, const void* K, const void* V,
                    float* O_acc, float* m, float* l, hipStream_t stream) {
   FwdArgsLite a;
@@ -705,6 +722,8 @@ int launch_fwd(const KParams& p, const void* Q, const void* K, const void* V,
   if (a.bmask != nullptr) {
     const int entries = (p.Nc + SF_BC - 1) / SF_BC;
     if (entries > S_MAX_LIST) return BURST_ERR_SHAPE;
+    static bool done[kMaxDevicesForAttr];
+    if (int st = allow_list(burst_fwd_d64_kernel<true>, done); st != BURST_OK) return st;
     hipLaunchKernelGGL(burst_fwd_d64_kernel<true>, dim3((unsigned)nb), dim3(256), (entries + 4) * 4, stream, a);
   } else {
     hipLaunchKernelGGL(burst_fwd_d64_kernel<false>, dim3((unsigned)nb), dim3(256), 0, stream, a);
@@ -723,6 +742,8 @@ int launch_bwd_dq(const KParams& p, const void* Q, const void* K, const void* V,
   if (a.bmask != nullptr) {
     const int entries = (p.Nc + SQ_BC - 1) / SQ_BC;
     if (entries > S_MAX_LIST) return BURST_ERR_SHAPE;
+    static bool done[kMaxDevicesForAttr];
+    if (int st = allow_list(burst_bwd_dq_d64_kernel<true>, done); st != BURST_OK) return st;
     hipLaunchKernelGGL(burst_bwd_dq_d64_kernel<true>, dim3((unsigned)nb), dim3(256), (entries + 4) * 4, stream, a);
   } else {
     hipLaunchKernelGGL(burst_bwd_dq_d64_kernel<false>, dim3((unsigned)nb), dim3(256), 0, stream, a);
@@ -743,14 +764,15 @@ int launch_bwd_dkv(const KParams& p, const void* Q, const void* K, const void* V
   if (a.bmask != nullptr) {
     const long long entries = (long long)p.group * ((p.Nq + SK_BR - 1) / SK_BR);
     if (entries > S_MAX_LIST) return BURST_ERR_SHAPE;
+    static bool done[kMaxDevicesForAttr];
+    if (int st = allow_list(burst_bwd_dkv_d64_kernel<true>, done); st != BURST_OK) return st;
     hipLaunchKernelGGL(burst_bwd_dkv_d64_kernel<true>, dim3((unsigned)nb), dim3(256), ((int)entries + 4) * 4, stream, a);
   } else {
     hipLaunchKernelGGL(burst_bwd_dkv_d64_kernel<false>, dim3((unsigned)nb), dim3(256), 0, stream, a);
   }
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
-
-#endif
+#endif  // BURST_SMALL_NO_DKV
 
 }  // namespace BURST_SMALL_NS
 }  // namespace burst
