@@ -203,6 +203,11 @@ int burst_local_bwd_materialized(const void* Q, const void* K_chunk, const void*
  * results of the two families agree within the tolerance, not bitwise.  Returns
  * BURST_ERR_SHAPE for another value. */
 int burst_set_kernel_family(int family);
+/* Which family would serve burst_local_fwd / the dQ half of burst_local_bwd for these parameters
+ * under the current setting: 1 or 2 as above, 0 = neither (another head dimension or type, or a
+ * shape only the generic kernels take); a negative burst_status for an invalid block.  Host
+ * logic only, no device call. */
+int burst_kernel_family_for(const burst_params* p);
 
 /* Timing helper for harnesses that cannot create HIP events themselves:
  * records/queries events on the same stream the kernels are launched on.

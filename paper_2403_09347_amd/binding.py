@@ -20,6 +20,7 @@ EXPORTS = [
     "burst_event_elapsed_ms", "burst_event_destroy", "burst_strerror", "burst_version",
     "burst_materialized_workspace_bytes", "burst_local_fwd_materialized", "burst_workspace_bytes",
     "burst_materialized_bwd_workspace_bytes", "burst_local_bwd_materialized", "burst_set_kernel_family",
+    "burst_kernel_family_for",
 ]
 
 
@@ -198,6 +199,13 @@ def burst_set_kernel_family(family):
     lib.burst_set_kernel_family.argtypes = [ctypes.c_int]
     lib.burst_set_kernel_family.restype = ctypes.c_int
     _check(lib.burst_set_kernel_family(int(family)), "burst_set_kernel_family")
+
+
+def burst_kernel_family_for(p):
+    lib = load()
+    lib.burst_kernel_family_for.argtypes = [ctypes.POINTER(BurstParams)]
+    lib.burst_kernel_family_for.restype = ctypes.c_int
+    return int(lib.burst_kernel_family_for(ctypes.byref(p)))
 
 
 def burst_workspace_bytes(p):

@@ -228,6 +228,14 @@ int burst_set_kernel_family(int family) {
   return BURST_OK;
 }
 
+int burst_kernel_family_for(const burst_params* p) {
+  KParams k;
+  const int st = check_params(p, &k);
+  if (st != BURST_OK) return st;
+  if (use_plain128(p, k)) return 2;
+  return use_mfma(p, k) && (p->block_mask == nullptr || p->Nc <= kMaxMaskedRows) ? 1 : 0;
+}
+
 size_t burst_workspace_bytes(const burst_params* p) {
   KParams k;
   if (check_params(p, &k) != BURST_OK) return 0;
@@ -454,6 +462,6 @@ const char* burst_strerror(int status) {
   }
 }
 
-int burst_version(void) { return 107; }
+int burst_version(void) { return 108; }
 
 }  // extern "C"

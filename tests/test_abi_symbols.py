@@ -95,3 +95,34 @@ def test_materialized_workspace_size_without_gpu():
     lib = binding.load()
     null = ctypes.c_void_p(0)
     assert lib.burst_local_fwd_materialized(null, null, null, null, null, null, null, 0, ctypes.byref(bad), null) == -3
+
+
+def test_kernel_family_choice_follows_how_the_workgroups_fill_the_chip():
+    """Host logic of the per-call choice between the two d = 128 kernel families (no device call):
+    256-row workgroups in rounds of 256; the plain 128-row kernels when the last round is at most
+    half full (up to six rounds) and for block flags finer than 256."""
+    from paper_2403_09347_amd import binding
+    fam = lambda H, Nq, Nc=4096, d=128, dtype="bf16", **kw: binding.burst_kernel_family_for(
+        binding.params(1, H, Nq, Nc, d, dtype, 0.1, **kw))
+    assert fam(32, 4096) == 1            # the benchmark shape: 512 workgroups, two full rounds
+    assert fam(32, 1024) == 2            # 128 workgroups: half a round
+    assert fam(32, 256) == 2 and fam(8, 4096) == 2
+    assert fam(40, 1024) == 1            # 160: more than half
+    assert fam(40, 2048) == 2 and fam(40, 4096) == 2      # 320, 640: a last round of 64 / 128
+    assert fam(28, 4096) == 1            # 448: last round three quarters full
+    assert fam(40, 16384) == 1           # 2560: ten full rounds
+    assert fam(33, 16384) == 1           # 2112 = 8 rounds + 64, but more than six rounds
+    assert fam(32, 4096, d=64) == 0 and fam(32, 4096, dtype="f32") == 0
+    bad = binding.params(1, 6, 16, 16, 128, "bf16", 0.5, kv_heads=4)
+    assert binding.burst_kernel_family_for(bad) == -3
+    for forced in (1, 2):
+        binding.burst_set_kernel_family(forced)
+        assert fam(32, 4096) == forced and fam(32, 1024) == forced and fam(32, 4096, d=64) == 0
+    binding.burst_set_kernel_family(0)
+    with __import__("pytest").raises(binding.BurstError):
+        binding.burst_set_kernel_family(3)
+    p = binding.params(1, 32, 4096, 4096, 128, "bf16", 0.1)
+    p.block_mask = 4096                   # any non-NULL address: host logic only
+    for block, want in ((64, 2), (128, 2), (256, 1), (512, 1)):
+        p.block = block
+        assert binding.burst_kernel_family_for(p) == want
