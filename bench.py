@@ -293,6 +293,10 @@ def main():
             for k in avg}
     dom = max(avg, key=lambda k: avg[k])
     names = {"fwd": "burst_fwd_mfma_kernel", "dq": "burst_bwd_dq_kernel", "dkv": "burst_bwd_dkv_kernel"}
+    if w.d == 64:
+        names = {"fwd": "d64::burst_fwd_d64_kernel", "dq": "d64::burst_bwd_dq_d64_kernel", "dkv": "d64::burst_bwd_dkv_d64_kernel"}
+    elif B.burst_kernel_family_for(walk.params(w.Nc, 0)) == 2:     # the 128-row kernels serve this shape
+        names.update(fwd="d128p::burst_fwd_d64_kernel", dq="d128p::burst_bwd_dq_d64_kernel")
     roofline = {"bound": "mfma", "kernel": names[dom], "achieved": kern[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": kern[dom]["tflops"] / PEAK_BF16_TFLOPS,
                 "traffic": measured_traffic(names[dom], w.name),

@@ -78,6 +78,9 @@ EXTRA_WORKLOADS = [
     # the single-device point of the latency-vs-devices experiment (Sec. 4, batch 1, 65,536 tokens,
     # LLaMA-13B): with G = 1 there is one chunk and the method is plain tiled attention (Sec. 2.4)
     Workload("llama13b_64k_G1", 1, 40, 128, 65536, 1, 65536, "bf16", False, 0, 1005),
+    # LLaMA-13B heads at the 32K / G = 8 share (the 13B counterpart of configuration 1): 40 heads x 16
+    # blocks of 256 rows = 640 forward workgroups, two and a half rounds on 256 CUs
+    Workload("llama13b_32k_G8", 1, 40, 128, 4096, 8, 4096, "bf16", False, 0, 1006),
 ]
 
 

@@ -228,3 +228,17 @@ def test_llama7b_32k_G8_sequence_major_tensors_match_the_contiguous_run_bitwise(
     assert O2.stride() == seq["Q"].stride()
     assert torch.equal(O, O2) and torch.equal(lse, lse2) and torch.equal(dQ, dQ2)
     assert all(torch.equal(a, b) for a, b in zip(dKs + dVs, dKs2 + dVs2))
+
+
+def test_llama13b_32k_G8_share_runs_on_the_128_row_kernels():
+    """40 heads x 4096 rows give the 256-row forward / dQ kernels 640 workgroups, a last round half
+    empty: the call is served by the 128-row kernels (automatic choice).  One complete head, sampled
+    rows elsewhere, the size-independent identities."""
+    from paper_2403_09347_amd import binding
+    w = workloads.by_name("llama13b_32k_G8")
+    assert binding.burst_kernel_family_for(binding.params(w.B, w.H, w.Nq, w.Nc, w.d, "bf16", w.scale)) == 2
+    inp, k_offs, walk, O, lse, dQ, dKs, dVs = run_workload(w)
+    check_complete_head(w, inp, 39, O, lse, dQ, dKs, dVs)
+    for h in (0, 20):
+        check_sampled_rows(w, inp, h, O, lse, dQ)
+    check_identities(w, inp, 7, dQ, dKs, dVs)
