@@ -581,6 +581,19 @@ def test_zigzag_rank_against_the_oracle(rank):
         check(f"dV[h{h}]", np.concatenate([f64(x[0, h]) for x in dVs]), dV_ref, "bf16")
 
 
+def test_autograd_wrapper_with_block_flags():
+    from paper_2403_09347_amd.autograd import burst_attention
+    case = workloads.make_case(B=1, H=2, d=128, Nq=300, chunk_rows=[256, 200], dtype="bf16", seed=61, device=DEV,
+                               block=64, pattern="random", density=0.5, causal=True, q_off=200)
+    q = case["Q"].clone().requires_grad_(True)
+    ks = [k.clone().requires_grad_(True) for k in case["K"]]
+    vs = [v.clone().requires_grad_(True) for v in case["V"]]
+    O, lse = burst_attention(q, ks, vs, causal=True, q_off=200, block_masks=case["masks"], block=64)
+    (O.float() * case["dO"].float()).sum().backward()
+    torch.cuda.synchronize()
+    compare_all_heads(case, "bf16", O.detach(), lse, q.grad.float(), [k.grad.float() for k in ks], [v.grad.float() for v in vs])
+
+
 @pytest.mark.parametrize("layout", ["head", "seq"])
 def test_autograd_wrapper_against_the_oracle(layout):
     """The differentiable torch call (chunk walk forward, Alg. 2 walk backward) on a causal, grouped-head
