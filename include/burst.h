@@ -35,7 +35,15 @@
  *     kernels run: keep it unchanged until they have finished.
  *     A row that sees no key keeps its state.
  *   - Return value: 0 on success, a negative burst_status otherwise.  On error
- *     nothing is enqueued and no output is written.
+ *     nothing is enqueued and no output is written (entry points that enqueue
+ *     several kernels check every kernel's limits before the first launch; only
+ *     a launch failure reported by the HIP runtime itself, BURST_ERR_LAUNCH, can
+ *     leave earlier kernels of the same call enqueued).
+ *   - Thread safety: entry points may be called from several host threads.  The first
+ *     call of a kernel family on a device sets that family's shared-memory function
+ *     attributes (once per device, whichever thread comes first); that call cannot be
+ *     recorded into a HIP graph, so run each entry point once eagerly on a device
+ *     before capturing it.
  *   - Supported shapes: B, H >= 1; Nq, Nc >= 0 (0 = nothing to do); 1 <= d <= 128
  *     for the generic kernels; the bf16 MFMA kernels are used when dtype = bf16
  *     and d = 128.  Any Nq, Nc (ragged tails) are accepted.
@@ -130,8 +138,14 @@ int burst_bwd_prepare(const void* O, const void* dO, float* D, const burst_param
  * S = scale Q K_chunk^T and P = exp(S - lse); dV += P^T dO; dP = dO V^T;
  * dS = P o (dP - D); dK += scale dS^T Q; dQ += scale dS K.
  * D may be NULL: it is then computed from O and dO into a scratch buffer that
- * the library owns (allocated on first use, kept until process exit); with a
- * non-NULL D, O is not read and may be NULL.
+ * the library owns, one per (device, stream), allocated with hipMalloc on the first
+ * such call (and again when a later call needs a larger one: the old block is kept,
+ * never freed, since enqueued kernels may still read it) and kept until process
+ * exit.  Such a call therefore may allocate (never under stream capture: pass D
+ * there), but it never frees or synchronises.  Calls with D == NULL are serialised
+ * by a library lock from the buffer lookup to the last enqueue; consecutive calls
+ * on one stream reuse the buffer in stream order.  With a non-NULL D nothing is
+ * allocated or locked, O is not read and may be NULL.
  * dQ [B,H,Nq,d], dK_chunk and dV_chunk [B,H,Nc,d], all fp32.
  * accumulate_dq / accumulate_dkv: 1 = add to what the buffer holds (the caller
  * zero-fills before the first block pair), 0 = the buffer is overwritten with
@@ -143,10 +157,12 @@ int burst_local_bwd(const void* Q, const void* K_chunk, const void* V_chunk,
                     int accumulate_dq, int accumulate_dkv,
                     const burst_params* p, void* stream);
 
-/* Device memory the library itself holds on behalf of calls with these parameters: 0 for every
- * entry point that is given all its buffers (the tiled steps keep S and P in registers, Sec. 2.4,
- * and need no workspace); B*H*Nq*4 bytes for burst_local_bwd with D == NULL (the buffer described
- * above).  Returns 0 for an invalid parameter block. */
+/* Size in bytes of the D buffer a burst_local_bwd call with these parameters and D == NULL needs
+ * (B*H*Nq*4; the library's own buffer may be larger).  It is the only device memory the library
+ * ever holds for a call: every other entry point, and burst_local_bwd with D given, is handed all
+ * its buffers (the tiled steps keep S and P in registers, Sec. 2.4, and need no workspace).  A
+ * caller that wants no library allocation allocates this many bytes, calls burst_bwd_prepare and
+ * passes D.  Returns 0 for an invalid parameter block. */
 size_t burst_workspace_bytes(const burst_params* p);
 
 /* The two halves of burst_local_bwd on their own, for callers that need only one side

@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstring>
 #include <mutex>
+#include <vector>
 #include "burst_common.h"
 
 namespace burst {
@@ -42,15 +43,28 @@ int launch_fwd_materialized(const KParams&, int, bool, const void*, const void*,
                             void*, hipStream_t);
 }  // namespace burst
 
+namespace burst {
+thread_local bool t_validate_only = false;
+}
+
 namespace {
 
 using burst::KParams;
 
 constexpr int kMaxDevices = 64;
 int g_arch_ok[kMaxDevices];                 // 0 = unknown, 1 = gfx950, -1 = other
-float* g_d_scratch[kMaxDevices];            // library-owned D buffer for burst_local_bwd(D = NULL)
-size_t g_d_scratch_elems[kMaxDevices];
 std::mutex g_mutex;
+
+// Library-owned D buffers for burst_local_bwd(D = NULL): one per (device, stream), so that calls on
+// different streams never share one.  A buffer that has become too small is replaced by one of at
+// least twice its size and is NOT freed: kernels already enqueued may still read it, and hipFree
+// would synchronise the device.  The retired blocks stay allocated until the process ends (less
+// than the final size in total).  Calls with D = NULL hold g_bwd_mutex from the lookup to the last
+// enqueue, so two host threads that share a stream cannot interleave their kernels around the
+// shared buffer.
+struct DScratch { int dev; hipStream_t stream; float* ptr; size_t elems; };
+std::vector<DScratch> g_d_scratch;
+std::mutex g_bwd_mutex;
 
 int check_arch() {
   int dev = 0;
@@ -173,22 +187,36 @@ bool dkv_mfma_ok(const burst_params* p, const KParams& k) {
   return p->block_mask == nullptr || p->Nq <= kMaxMaskedRows;
 }
 
-int get_d_scratch(size_t elems, float** out) {
+// Entry points that enqueue several kernels: one pass over the launchers in validate-only mode
+// (shape limits, function attributes), so that an error is reported with nothing enqueued, then
+// the real pass.
+template <typename F>
+int validated(F&& enqueue) {
+  burst::t_validate_only = true;
+  const int e = enqueue();
+  burst::t_validate_only = false;
+  return e != BURST_OK ? e : enqueue();
+}
+
+// Caller holds g_bwd_mutex.
+int get_d_scratch(hipStream_t stream, size_t elems, float** out) {
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return BURST_ERR_ALLOC;
-  std::lock_guard<std::mutex> lock(g_mutex);
-  if (g_d_scratch_elems[dev] < elems) {
-    if (g_d_scratch[dev] != nullptr) {
-      if (hipFree(g_d_scratch[dev]) != hipSuccess) return BURST_ERR_ALLOC;   // waits for users of the old buffer
-      g_d_scratch[dev] = nullptr;
-      g_d_scratch_elems[dev] = 0;
-    }
-    float* ptr = nullptr;
-    if (hipMalloc(&ptr, elems * sizeof(float)) != hipSuccess) return BURST_ERR_ALLOC;
-    g_d_scratch[dev] = ptr;
-    g_d_scratch_elems[dev] = elems;
+  if (hipGetDevice(&dev) != hipSuccess) return BURST_ERR_ALLOC;
+  DScratch* slot = nullptr;
+  for (DScratch& e : g_d_scratch)
+    if (e.dev == dev && e.stream == stream) slot = &e;
+  if (slot == nullptr) {
+    g_d_scratch.push_back(DScratch{dev, stream, nullptr, 0});
+    slot = &g_d_scratch.back();
   }
-  *out = g_d_scratch[dev];
+  if (slot->elems < elems) {
+    const size_t want = elems > 2 * slot->elems ? elems : 2 * slot->elems;
+    float* ptr = nullptr;
+    if (hipMalloc(&ptr, want * sizeof(float)) != hipSuccess) return BURST_ERR_ALLOC;
+    slot->ptr = ptr;                               // the old block, if any, is retired, not freed
+    slot->elems = want;
+  }
+  *out = slot->ptr;
   return BURST_OK;
 }
 
@@ -262,8 +290,10 @@ int burst_local_fwd_materialized(const void* Q, const void* K_chunk, const void*
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return BURST_ERR_ALIGN;
   if (workspace_bytes < burst::materialized_workspace_bytes(k, p->dtype)) return BURST_ERR_SHAPE;
   if ((st = check_arch()) != BURST_OK) return st;
-  return burst::launch_fwd_materialized(k, p->dtype, use_mfma(p, k), Q, K_chunk, V_chunk, O_acc, m, l, workspace,
-                                        (hipStream_t)stream);
+  return validated([&] {
+    return burst::launch_fwd_materialized(k, p->dtype, use_mfma(p, k), Q, K_chunk, V_chunk, O_acc, m, l, workspace,
+                                          (hipStream_t)stream);
+  });
 }
 
 size_t burst_materialized_bwd_workspace_bytes(const burst_params* p) {
@@ -299,8 +329,10 @@ int burst_local_bwd_materialized(const void* Q, const void* K_chunk, const void*
   REQUIRE_PTR(workspace);
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return BURST_ERR_ALIGN;
   if (workspace_bytes < burst::materialized_bwd_workspace_bytes(k, p->dtype)) return BURST_ERR_SHAPE;
-  return burst::launch_bwd_materialized(k, p->dtype, use_mfma(p, k), Q, K_chunk, V_chunk, dO, lse, D, dQ, dK_chunk,
-                                        dV_chunk, accumulate_dq != 0, accumulate_dkv != 0, workspace, s);
+  return validated([&] {
+    return burst::launch_bwd_materialized(k, p->dtype, use_mfma(p, k), Q, K_chunk, V_chunk, dO, lse, D, dQ, dK_chunk,
+                                          dV_chunk, accumulate_dq != 0, accumulate_dkv != 0, workspace, s);
+  });
 }
 
 int burst_finalize(const float* O_acc, const float* m, const float* l,
@@ -368,40 +400,35 @@ static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const v
     }
     return BURST_OK;
   }
-  const float* Duse = D;
-  if (Duse == nullptr) {
-    float* scratch = nullptr;
-    if ((st = get_d_scratch((size_t)(bh * k.Nq), &scratch)) != BURST_OK) return st;
-    if ((st = burst::launch_bwd_prepare(k, p->dtype, O, dO, scratch, s)) != BURST_OK) return st;
-    Duse = scratch;
-  }
+  // The kernels of this call: D (when it is not given), then the dQ half, then the dK/dV half.
   const bool mfma_dq = use_mfma(p, k) && (p->block_mask == nullptr || p->Nc <= kMaxMaskedRows);
   const bool mfma_dkv = use_mfma(p, k) && dkv_mfma_ok(p, k);
-  if (use_d64(p, k)) {
-    if (want_dq &&
-        (st = burst::d64::launch_bwd_dq(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)) != BURST_OK)
-      return st;
-    if (want_dkv &&
-        (st = burst::d64::launch_bwd_dkv(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk,
-                                        accumulate_dkv != 0, s)) != BURST_OK)
-      return st;
+  const bool d64 = use_d64(p, k), plain128 = use_plain128(p, k);
+  const bool adq = accumulate_dq != 0, adkv = accumulate_dkv != 0;
+  auto enqueue = [&](const float* Duse, float* Dwrite) -> int {
+    int e;
+    if (Dwrite != nullptr && (e = burst::launch_bwd_prepare(k, p->dtype, O, dO, Dwrite, s)) != BURST_OK) return e;
+    if (want_dq) {
+      e = d64 ? burst::d64::launch_bwd_dq(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, adq, s)
+        : plain128 ? burst::d128p::launch_bwd_dq(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, adq, s)
+        : mfma_dq ? burst::launch_bwd_dq_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, adq, s)
+                  : burst::launch_bwd_dq_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, adq, s);
+      if (e != BURST_OK) return e;
+    }
+    if (want_dkv) {
+      e = d64 ? burst::d64::launch_bwd_dkv(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk, adkv, s)
+        : mfma_dkv ? burst::launch_bwd_dkv_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk, adkv, s)
+                   : burst::launch_bwd_dkv_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk,
+                                                   dV_chunk, adkv, s);
+      if (e != BURST_OK) return e;
+    }
     return BURST_OK;
-  }
-  if (want_dq) {
-    st = use_plain128(p, k) ? burst::d128p::launch_bwd_dq(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)
-       : mfma_dq ? burst::launch_bwd_dq_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dQ, accumulate_dq != 0, s)
-              : burst::launch_bwd_dq_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dQ,
-                                             accumulate_dq != 0, s);
-    if (st != BURST_OK) return st;
-  }
-  if (want_dkv) {
-    st = mfma_dkv ? burst::launch_bwd_dkv_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk,
-                                           accumulate_dkv != 0, s)
-              : burst::launch_bwd_dkv_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk,
-                                              dV_chunk, accumulate_dkv != 0, s);
-    if (st != BURST_OK) return st;
-  }
-  return BURST_OK;
+  };
+  if (D != nullptr) return validated([&] { return enqueue(D, nullptr); });
+  std::lock_guard<std::mutex> lock(g_bwd_mutex);
+  float* scratch = nullptr;
+  if ((st = get_d_scratch(s, (size_t)(bh * k.Nq), &scratch)) != BURST_OK) return st;
+  return validated([&] { return enqueue(scratch, scratch); });
 }
 
 int burst_local_bwd(const void* Q, const void* K_chunk, const void* V_chunk,
@@ -462,6 +489,6 @@ const char* burst_strerror(int status) {
   }
 }
 
-int burst_version(void) { return 108; }
+int burst_version(void) { return 109; }
 
 }  // extern "C"

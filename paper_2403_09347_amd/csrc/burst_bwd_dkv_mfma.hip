@@ -443,16 +443,14 @@ int launch_bwd_dkv_mfma(const KParams& p, const void* Q, const void* K, const vo
                         const void* dO, const float* lse, const float* D, float* dK, float* dV,
                         int acc_dkv, hipStream_t stream) {
   if (p.Nc <= 0) return BURST_OK;
-  static bool attr_set[kMaxDevicesForAttr];
-  const int dev = current_device_slot();
-  if (dev < 0) return BURST_ERR_LAUNCH;
-  if (!attr_set[dev]) {
-    if (hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            DKV_LDS_BYTES) != hipSuccess ||
-        hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            DKV_LDS_BYTES + DKV_LIST_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
-    attr_set[dev] = true;
-  }
+  static DeviceOnce lds_opt_in;
+  const int st = lds_opt_in.run([] {
+    return hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               DKV_LDS_BYTES) == hipSuccess &&
+           hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               DKV_LDS_BYTES + DKV_LIST_BYTES) == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+  });
+  if (st != BURST_OK) return st;
   BwdArgs a = make_bwd_args(p, Q, K, V, dO, lse, D, nullptr, dK, dV, 0, acc_dkv);
   a.H = p.B * p.H / p.group;                       // workgroups are laid out over key/value heads
   int heads8 = ((a.H + 7) / 8) * 8;
@@ -462,11 +460,11 @@ int launch_bwd_dkv_mfma(const KParams& p, const void* Q, const void* K, const vo
   if (a.bmask != nullptr || a.group > 1) {
     if ((long long)a.group * ((p.Nq + DKV_BR - 1) / DKV_BR) > DKV_MAX_LIST) return BURST_ERR_SHAPE;
     if (a.group > 1 && p.Nq % DKV_BR != 0) return BURST_ERR_SHAPE;
-    hipLaunchKernelGGL(burst_bwd_dkv_kernel<true>, dim3((unsigned)nb), dim3(256), DKV_LDS_BYTES + DKV_LIST_BYTES, stream, a);
+    BURST_LAUNCH(burst_bwd_dkv_kernel<true>, dim3((unsigned)nb), dim3(256), DKV_LDS_BYTES + DKV_LIST_BYTES, stream, a);
   } else {
-    hipLaunchKernelGGL(burst_bwd_dkv_kernel<false>, dim3((unsigned)nb), dim3(256), DKV_LDS_BYTES, stream, a);
+    BURST_LAUNCH(burst_bwd_dkv_kernel<false>, dim3((unsigned)nb), dim3(256), DKV_LDS_BYTES, stream, a);
   }
-  return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+  return launch_status();
 }
 
 }  // namespace burst

@@ -463,27 +463,25 @@ int launch_bwd_dq_mfma(const KParams& p, const void* Q, const void* K, const voi
   a.blocks_per_head = (p.Nq + DQ_BR - 1) / DQ_BR;
   long long nb = (long long)heads8 * a.blocks_per_head;
   if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;
-  static bool attr_set[kMaxDevicesForAttr];
-  const int dev = current_device_slot();
-  if (dev < 0) return BURST_ERR_LAUNCH;
-  if (!attr_set[dev]) {
-    if (hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            DQ_LDS_BYTES) != hipSuccess ||
-        hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            DQ_LDS_BYTES) != hipSuccess ||
-        hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            DQ_LDS_BYTES + DQ_LIST_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
-    attr_set[dev] = true;
-  }
+  static DeviceOnce lds_opt_in;
+  const int st = lds_opt_in.run([] {
+    return hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               DQ_LDS_BYTES) == hipSuccess &&
+           hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               DQ_LDS_BYTES) == hipSuccess &&
+           hipFuncSetAttribute((const void*)burst_bwd_dq_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               DQ_LDS_BYTES + DQ_LIST_BYTES) == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+  });
+  if (st != BURST_OK) return st;
   if (a.bmask != nullptr) {
     if ((p.Nc + DQ_BC - 1) / DQ_BC > DQ_MAX_LIST) return BURST_ERR_SHAPE;
-    hipLaunchKernelGGL(burst_bwd_dq_kernel<2>, dim3((unsigned)nb), dim3(256), DQ_LDS_BYTES + DQ_LIST_BYTES, stream, a);
+    BURST_LAUNCH(burst_bwd_dq_kernel<2>, dim3((unsigned)nb), dim3(256), DQ_LDS_BYTES + DQ_LIST_BYTES, stream, a);
   } else if (a.window > 0) {
-    hipLaunchKernelGGL(burst_bwd_dq_kernel<1>, dim3((unsigned)nb), dim3(256), DQ_LDS_BYTES, stream, a);
+    BURST_LAUNCH(burst_bwd_dq_kernel<1>, dim3((unsigned)nb), dim3(256), DQ_LDS_BYTES, stream, a);
   } else {
-    hipLaunchKernelGGL(burst_bwd_dq_kernel<0>, dim3((unsigned)nb), dim3(256), DQ_LDS_BYTES, stream, a);
+    BURST_LAUNCH(burst_bwd_dq_kernel<0>, dim3((unsigned)nb), dim3(256), DQ_LDS_BYTES, stream, a);
   }
-  return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+  return launch_status();
 }
 
 }  // namespace burst

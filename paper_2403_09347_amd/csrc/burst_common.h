@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <mutex>
 #include "../../include/burst.h"
 
 namespace burst {
@@ -69,12 +70,37 @@ struct KParams {
 };
 
 // The opt-in to more than 64 KB of dynamic LDS is a per-device function attribute: launchers
-// keep one flag per device (index = current device, or -1 if it cannot be determined).
+// set it once per device (index = current device, or -1 if it cannot be determined), whichever
+// host thread comes first.
 constexpr int kMaxDevicesForAttr = 64;
 inline int current_device_slot() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevicesForAttr) return -1;
   return dev;
+}
+struct DeviceOnce {
+  std::once_flag flag[kMaxDevicesForAttr];
+  int status[kMaxDevicesForAttr];
+  template <typename F>
+  int run(F&& setup) {                       // setup() returns a burst_status; it runs once per device
+    const int dev = current_device_slot();
+    if (dev < 0) return BURST_ERR_LAUNCH;
+    std::call_once(flag[dev], [&] { status[dev] = setup(); });
+    return status[dev];
+  }
+};
+
+// An entry point that enqueues several kernels first walks its launchers with this flag set: they
+// validate, set their function attributes and return without launching, so that an error can
+// still be reported with nothing enqueued.
+extern thread_local bool t_validate_only;
+#define BURST_LAUNCH(...)                                          \
+  do {                                                             \
+    if (!::burst::t_validate_only) hipLaunchKernelGGL(__VA_ARGS__); \
+  } while (0)
+inline int launch_status() {
+  if (t_validate_only) return BURST_OK;
+  return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

@@ -695,15 +695,11 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
 // Tile lists are dynamic LDS behind up to 64 KB of static tiles: the kernels that take one opt
 // in to the larger total once per device.
 template <typename K>
-static int allow_list(K kernel, bool* done) {
-  const int dev = current_device_slot();
-  if (dev < 0) return BURST_ERR_LAUNCH;
-  if (!done[dev]) {
-    if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (S_MAX_LIST + 4) * 4) != hipSuccess)
-      return BURST_ERR_LAUNCH;
-    done[dev] = true;
-  }
-  return BURST_OK;
+static int allow_list(K kernel, DeviceOnce& once) {
+  return once.run([kernel] {
+    return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (S_MAX_LIST + 4) * 4) ==
+                   hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+  });
 }
 
 int launch_fwd(const KParams& p, const void* Q, const void* K, const void* V,
@@ -722,13 +718,13 @@ int launch_fwd(const KParams& p, const void* Q, const void* K, const void* V,
   if (a.bmask != nullptr) {
     const int entries = (p.Nc + SF_BC - 1) / SF_BC;
     if (entries > S_MAX_LIST) return BURST_ERR_SHAPE;
-    static bool done[kMaxDevicesForAttr];
+    static DeviceOnce done;
     if (int st = allow_list(burst_fwd_d64_kernel<true>, done); st != BURST_OK) return st;
-    hipLaunchKernelGGL(burst_fwd_d64_kernel<true>, dim3((unsigned)nb), dim3(256), (entries + 4) * 4, stream, a);
+    BURST_LAUNCH(burst_fwd_d64_kernel<true>, dim3((unsigned)nb), dim3(256), (entries + 4) * 4, stream, a);
   } else {
-    hipLaunchKernelGGL(burst_fwd_d64_kernel<false>, dim3((unsigned)nb), dim3(256), 0, stream, a);
+    BURST_LAUNCH(burst_fwd_d64_kernel<false>, dim3((unsigned)nb), dim3(256), 0, stream, a);
   }
-  return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+  return launch_status();
 }
 
 int launch_bwd_dq(const KParams& p, const void* Q, const void* K, const void* V,
@@ -742,13 +738,13 @@ int launch_bwd_dq(const KParams& p, const void* Q, const void* K, const void* V,
   if (a.bmask != nullptr) {
     const int entries = (p.Nc + SQ_BC - 1) / SQ_BC;
     if (entries > S_MAX_LIST) return BURST_ERR_SHAPE;
-    static bool done[kMaxDevicesForAttr];
+    static DeviceOnce done;
     if (int st = allow_list(burst_bwd_dq_d64_kernel<true>, done); st != BURST_OK) return st;
-    hipLaunchKernelGGL(burst_bwd_dq_d64_kernel<true>, dim3((unsigned)nb), dim3(256), (entries + 4) * 4, stream, a);
+    BURST_LAUNCH(burst_bwd_dq_d64_kernel<true>, dim3((unsigned)nb), dim3(256), (entries + 4) * 4, stream, a);
   } else {
-    hipLaunchKernelGGL(burst_bwd_dq_d64_kernel<false>, dim3((unsigned)nb), dim3(256), 0, stream, a);
+    BURST_LAUNCH(burst_bwd_dq_d64_kernel<false>, dim3((unsigned)nb), dim3(256), 0, stream, a);
   }
-  return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+  return launch_status();
 }
 
 #ifndef BURST_SMALL_NO_DKV
@@ -764,13 +760,13 @@ int launch_bwd_dkv(const KParams& p, const void* Q, const void* K, const void* V
   if (a.bmask != nullptr) {
     const long long entries = (long long)p.group * ((p.Nq + SK_BR - 1) / SK_BR);
     if (entries > S_MAX_LIST) return BURST_ERR_SHAPE;
-    static bool done[kMaxDevicesForAttr];
+    static DeviceOnce done;
     if (int st = allow_list(burst_bwd_dkv_d64_kernel<true>, done); st != BURST_OK) return st;
-    hipLaunchKernelGGL(burst_bwd_dkv_d64_kernel<true>, dim3((unsigned)nb), dim3(256), ((int)entries + 4) * 4, stream, a);
+    BURST_LAUNCH(burst_bwd_dkv_d64_kernel<true>, dim3((unsigned)nb), dim3(256), ((int)entries + 4) * 4, stream, a);
   } else {
-    hipLaunchKernelGGL(burst_bwd_dkv_d64_kernel<false>, dim3((unsigned)nb), dim3(256), 0, stream, a);
+    BURST_LAUNCH(burst_bwd_dkv_d64_kernel<false>, dim3((unsigned)nb), dim3(256), 0, stream, a);
   }
-  return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+  return launch_status();
 }
 #endif  // BURST_SMALL_NO_DKV
 

@@ -185,17 +185,16 @@ static inline unsigned grid_for(long long work_items, int per_block = 256, unsig
   return (unsigned)b;
 }
 
-static inline int launch_status() { return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH; }
 
 int launch_state_init(const KParams& p, float* O_acc, float* m, float* l, hipStream_t s) {
   long long rows = (long long)p.B * p.H * p.Nq;
   long long n_o = rows * p.d;
   if (rows == 0) return BURST_OK;
   if (n_o % 4 != 0) {  // odd sizes: scalar fill through the generic zero kernel + row init
-    hipLaunchKernelGGL(zero_fill_kernel, dim3(grid_for(n_o)), dim3(256), 0, s, O_acc, n_o);
-    hipLaunchKernelGGL(state_init_kernel, dim3(grid_for(rows)), dim3(256), 0, s, O_acc, m, l, 0LL, rows);
+    BURST_LAUNCH(zero_fill_kernel, dim3(grid_for(n_o)), dim3(256), 0, s, O_acc, n_o);
+    BURST_LAUNCH(state_init_kernel, dim3(grid_for(rows)), dim3(256), 0, s, O_acc, m, l, 0LL, rows);
   } else {
-    hipLaunchKernelGGL(state_init_kernel, dim3(grid_for(n_o / 4)), dim3(256), 0, s, O_acc, m, l, n_o / 4, rows);
+    BURST_LAUNCH(state_init_kernel, dim3(grid_for(n_o / 4)), dim3(256), 0, s, O_acc, m, l, n_o / 4, rows);
   }
   return launch_status();
 }
@@ -207,11 +206,11 @@ int launch_finalize(const KParams& p, int dtype, const float* O_acc, const float
   bool vec = (p.d % 4) == 0;
   unsigned g = grid_for(rows * (vec ? p.d / 4 : p.d));
   if (dtype == BURST_BF16) {
-    if (vec) hipLaunchKernelGGL((finalize_kernel<bf16, 4>), dim3(g), dim3(256), 0, s, O_acc, m, l, (bf16*)O_out, lse, rows, p.d, p.q_rows());
-    else hipLaunchKernelGGL((finalize_kernel<bf16, 1>), dim3(g), dim3(256), 0, s, O_acc, m, l, (bf16*)O_out, lse, rows, p.d, p.q_rows());
+    if (vec) BURST_LAUNCH((finalize_kernel<bf16, 4>), dim3(g), dim3(256), 0, s, O_acc, m, l, (bf16*)O_out, lse, rows, p.d, p.q_rows());
+    else BURST_LAUNCH((finalize_kernel<bf16, 1>), dim3(g), dim3(256), 0, s, O_acc, m, l, (bf16*)O_out, lse, rows, p.d, p.q_rows());
   } else {
-    if (vec) hipLaunchKernelGGL((finalize_kernel<float, 4>), dim3(g), dim3(256), 0, s, O_acc, m, l, (float*)O_out, lse, rows, p.d, p.q_rows());
-    else hipLaunchKernelGGL((finalize_kernel<float, 1>), dim3(g), dim3(256), 0, s, O_acc, m, l, (float*)O_out, lse, rows, p.d, p.q_rows());
+    if (vec) BURST_LAUNCH((finalize_kernel<float, 4>), dim3(g), dim3(256), 0, s, O_acc, m, l, (float*)O_out, lse, rows, p.d, p.q_rows());
+    else BURST_LAUNCH((finalize_kernel<float, 1>), dim3(g), dim3(256), 0, s, O_acc, m, l, (float*)O_out, lse, rows, p.d, p.q_rows());
   }
   return launch_status();
 }
@@ -221,10 +220,10 @@ int launch_merge_state(const KParams& p, float* O_a, float* m_a, float* l_a,
   long long rows = (long long)p.B * p.H * p.Nq;
   if (rows == 0) return BURST_OK;
   if (p.d % 4 == 0 && 64 % (p.d / 4) == 0) {
-    hipLaunchKernelGGL(merge_state_packed_kernel, dim3(grid_for(rows * (p.d / 4))), dim3(256), 0, s,
+    BURST_LAUNCH(merge_state_packed_kernel, dim3(grid_for(rows * (p.d / 4))), dim3(256), 0, s,
                        O_a, m_a, l_a, O_b, m_b, l_b, rows, p.d);
   } else {
-    hipLaunchKernelGGL(merge_state_row_kernel, dim3(grid_for(rows * 64)), dim3(256), 0, s,
+    BURST_LAUNCH(merge_state_row_kernel, dim3(grid_for(rows * 64)), dim3(256), 0, s,
                        O_a, m_a, l_a, O_b, m_b, l_b, rows, p.d);
   }
   return launch_status();
@@ -235,19 +234,19 @@ int launch_bwd_prepare(const KParams& p, int dtype, const void* O, const void* d
   if (rows == 0) return BURST_OK;
   if (p.d == 128) {
     unsigned g = grid_for(rows * 32);
-    if (dtype == BURST_BF16) hipLaunchKernelGGL((bwd_prepare_d128_kernel<bf16>), dim3(g), dim3(256), 0, s, (const bf16*)O, (const bf16*)dO, D, rows, p.q_rows());
-    else hipLaunchKernelGGL((bwd_prepare_d128_kernel<float>), dim3(g), dim3(256), 0, s, (const float*)O, (const float*)dO, D, rows, p.q_rows());
+    if (dtype == BURST_BF16) BURST_LAUNCH((bwd_prepare_d128_kernel<bf16>), dim3(g), dim3(256), 0, s, (const bf16*)O, (const bf16*)dO, D, rows, p.q_rows());
+    else BURST_LAUNCH((bwd_prepare_d128_kernel<float>), dim3(g), dim3(256), 0, s, (const float*)O, (const float*)dO, D, rows, p.q_rows());
   } else {
     unsigned g = grid_for(rows * 64);
-    if (dtype == BURST_BF16) hipLaunchKernelGGL((bwd_prepare_kernel<bf16>), dim3(g), dim3(256), 0, s, (const bf16*)O, (const bf16*)dO, D, rows, p.d, p.q_rows());
-    else hipLaunchKernelGGL((bwd_prepare_kernel<float>), dim3(g), dim3(256), 0, s, (const float*)O, (const float*)dO, D, rows, p.d, p.q_rows());
+    if (dtype == BURST_BF16) BURST_LAUNCH((bwd_prepare_kernel<bf16>), dim3(g), dim3(256), 0, s, (const bf16*)O, (const bf16*)dO, D, rows, p.d, p.q_rows());
+    else BURST_LAUNCH((bwd_prepare_kernel<float>), dim3(g), dim3(256), 0, s, (const float*)O, (const float*)dO, D, rows, p.d, p.q_rows());
   }
   return launch_status();
 }
 
 int launch_zero_fill(float* ptr, long long n, hipStream_t s) {
   if (n <= 0) return BURST_OK;
-  hipLaunchKernelGGL(zero_fill_kernel, dim3(grid_for(n / 4 + 1)), dim3(256), 0, s, ptr, n);
+  BURST_LAUNCH(zero_fill_kernel, dim3(grid_for(n / 4 + 1)), dim3(256), 0, s, ptr, n);
   return launch_status();
 }
 

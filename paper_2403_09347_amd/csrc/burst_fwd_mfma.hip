@@ -552,25 +552,23 @@ int launch_fwd_mfma(const KParams& p, const void* Q, const void* K, const void* 
   int heads8 = ((a.H + 7) / 8) * 8;                // pad the head count to a multiple of 8 ids
   long long nblocks = (long long)heads8 * a.q_blocks;
   if (nblocks > 0x7fffffffLL) return BURST_ERR_SHAPE;
-  static bool attr_set[kMaxDevicesForAttr];
-  const int dev = current_device_slot();
-  if (dev < 0) return BURST_ERR_LAUNCH;
-  if (!attr_set[dev]) {
-    if (hipFuncSetAttribute((const void*)burst_fwd_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            2 * FWD_NBUF * FWD_TILE_BYTES) != hipSuccess ||
-        hipFuncSetAttribute((const void*)burst_fwd_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            2 * FWD_NBUF * FWD_TILE_BYTES + FWD_LIST_BYTES) != hipSuccess) return BURST_ERR_LAUNCH;
-    attr_set[dev] = true;
-  }
+  static DeviceOnce lds_opt_in;
+  const int st = lds_opt_in.run([] {
+    return hipFuncSetAttribute((const void*)burst_fwd_mfma_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               2 * FWD_NBUF * FWD_TILE_BYTES) == hipSuccess &&
+           hipFuncSetAttribute((const void*)burst_fwd_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               2 * FWD_NBUF * FWD_TILE_BYTES + FWD_LIST_BYTES) == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+  });
+  if (st != BURST_OK) return st;
   if (a.bmask != nullptr) {
     if ((p.Nc + FWD_BC - 1) / FWD_BC > FWD_MAX_LIST) return BURST_ERR_SHAPE;
-    hipLaunchKernelGGL(burst_fwd_mfma_kernel<true>, dim3((unsigned)nblocks), dim3(256),
+    BURST_LAUNCH(burst_fwd_mfma_kernel<true>, dim3((unsigned)nblocks), dim3(256),
                        2 * FWD_NBUF * FWD_TILE_BYTES + FWD_LIST_BYTES, stream, a);
   } else {
-    hipLaunchKernelGGL(burst_fwd_mfma_kernel<false>, dim3((unsigned)nblocks), dim3(256),
+    BURST_LAUNCH(burst_fwd_mfma_kernel<false>, dim3((unsigned)nblocks), dim3(256),
                        2 * FWD_NBUF * FWD_TILE_BYTES, stream, a);
   }
-  return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+  return launch_status();
 }
 
 }  // namespace burst

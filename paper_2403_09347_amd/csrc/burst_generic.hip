@@ -230,7 +230,6 @@ static GenArgs make_args(const KParams& p) {
   a.lay = p.lay;
   return a;
 }
-static inline int launch_status() { return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH; }
 
 int launch_fwd_generic(const KParams& p, int dtype, const void* Q, const void* K, const void* V,
                        float* O_acc, float* m, float* l, hipStream_t s) {
@@ -240,8 +239,8 @@ int launch_fwd_generic(const KParams& p, int dtype, const void* Q, const void* K
   if (blocks > 0x7fffffffLL) return BURST_ERR_SHAPE;
   GenArgs a = make_args(p);
   a.Q = Q; a.K = K; a.V = V; a.O_acc = O_acc; a.m = m; a.l = l;
-  if (dtype == BURST_BF16) hipLaunchKernelGGL((fwd_generic_kernel<bf16>), dim3((unsigned)blocks), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL((fwd_generic_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, s, a);
+  if (dtype == BURST_BF16) BURST_LAUNCH((fwd_generic_kernel<bf16>), dim3((unsigned)blocks), dim3(256), 0, s, a);
+  else BURST_LAUNCH((fwd_generic_kernel<float>), dim3((unsigned)blocks), dim3(256), 0, s, a);
   return launch_status();
 }
 
@@ -253,8 +252,8 @@ int launch_bwd_dq_generic(const KParams& p, int dtype, const void* Q, const void
   if (wq == 0) return BURST_OK;
   if ((wq + 3) / 4 > 0x7fffffffLL) return BURST_ERR_SHAPE;
   unsigned blocks = (unsigned)((wq + 3) / 4);
-  if (dtype == BURST_BF16) hipLaunchKernelGGL((bwd_dq_generic_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL((bwd_dq_generic_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
+  if (dtype == BURST_BF16) BURST_LAUNCH((bwd_dq_generic_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
+  else BURST_LAUNCH((bwd_dq_generic_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
   return launch_status();
 }
 
@@ -267,8 +266,8 @@ int launch_bwd_dkv_generic(const KParams& p, int dtype, const void* Q, const voi
   if (wk == 0) return BURST_OK;
   if ((wk + 3) / 4 > 0x7fffffffLL) return BURST_ERR_SHAPE;
   unsigned blocks = (unsigned)((wk + 3) / 4);
-  if (dtype == BURST_BF16) hipLaunchKernelGGL((bwd_dkv_generic_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL((bwd_dkv_generic_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
+  if (dtype == BURST_BF16) BURST_LAUNCH((bwd_dkv_generic_kernel<bf16>), dim3(blocks), dim3(256), 0, s, a);
+  else BURST_LAUNCH((bwd_dkv_generic_kernel<float>), dim3(blocks), dim3(256), 0, s, a);
   return launch_status();
 }
 

@@ -549,21 +549,21 @@ int launch_fwd_materialized(const KParams& p, int dtype, bool mfma, const void* 
   if (mfma) {
     const long long kb = (a.Ncp + 127) / 128, qb = (a.Nq + 31) / 32, qb128 = (a.Nq + 127) / 128;
     if (qb > 65535 || a.BH > 65535 || kb > 0x7fffffffLL) return BURST_ERR_SHAPE;
-    hipLaunchKernelGGL(mat_scores_mfma_kernel, dim3((unsigned)kb, (unsigned)qb, (unsigned)a.BH), dim3(256), 0, s, a);
-    hipLaunchKernelGGL((mat_softmax_kernel<bf16>), dim3((unsigned)row_blocks), dim3(256), 0, s, a);
-    hipLaunchKernelGGL(mat_pv_merge_mfma_kernel<0>, dim3((unsigned)qb128, (unsigned)a.BH), dim3(256), 0, s, a);
+    BURST_LAUNCH(mat_scores_mfma_kernel, dim3((unsigned)kb, (unsigned)qb, (unsigned)a.BH), dim3(256), 0, s, a);
+    BURST_LAUNCH((mat_softmax_kernel<bf16>), dim3((unsigned)row_blocks), dim3(256), 0, s, a);
+    BURST_LAUNCH(mat_pv_merge_mfma_kernel<0>, dim3((unsigned)qb128, (unsigned)a.BH), dim3(256), 0, s, a);
   } else if (dtype == BURST_BF16) {
-    hipLaunchKernelGGL((mat_scores_generic_kernel<bf16>), dim3(grid1d((long long)rows * a.Ncp)), dim3(256), 0, s, a);
-    hipLaunchKernelGGL((mat_softmax_kernel<bf16>), dim3((unsigned)row_blocks), dim3(256), 0, s, a);
-    hipLaunchKernelGGL((mat_pv_merge_generic_kernel<bf16>), dim3(grid1d((long long)rows * a.d)), dim3(256), 0, s, a);
-    hipLaunchKernelGGL(mat_ml_merge_kernel, dim3((unsigned)(((long long)rows + 255) / 256)), dim3(256), 0, s, a);
+    BURST_LAUNCH((mat_scores_generic_kernel<bf16>), dim3(grid1d((long long)rows * a.Ncp)), dim3(256), 0, s, a);
+    BURST_LAUNCH((mat_softmax_kernel<bf16>), dim3((unsigned)row_blocks), dim3(256), 0, s, a);
+    BURST_LAUNCH((mat_pv_merge_generic_kernel<bf16>), dim3(grid1d((long long)rows * a.d)), dim3(256), 0, s, a);
+    BURST_LAUNCH(mat_ml_merge_kernel, dim3((unsigned)(((long long)rows + 255) / 256)), dim3(256), 0, s, a);
   } else {
-    hipLaunchKernelGGL((mat_scores_generic_kernel<float>), dim3(grid1d((long long)rows * a.Ncp)), dim3(256), 0, s, a);
-    hipLaunchKernelGGL((mat_softmax_kernel<float>), dim3((unsigned)row_blocks), dim3(256), 0, s, a);
-    hipLaunchKernelGGL((mat_pv_merge_generic_kernel<float>), dim3(grid1d((long long)rows * a.d)), dim3(256), 0, s, a);
-    hipLaunchKernelGGL(mat_ml_merge_kernel, dim3((unsigned)(((long long)rows + 255) / 256)), dim3(256), 0, s, a);
+    BURST_LAUNCH((mat_scores_generic_kernel<float>), dim3(grid1d((long long)rows * a.Ncp)), dim3(256), 0, s, a);
+    BURST_LAUNCH((mat_softmax_kernel<float>), dim3((unsigned)row_blocks), dim3(256), 0, s, a);
+    BURST_LAUNCH((mat_pv_merge_generic_kernel<float>), dim3(grid1d((long long)rows * a.d)), dim3(256), 0, s, a);
+    BURST_LAUNCH(mat_ml_merge_kernel, dim3((unsigned)(((long long)rows + 255) / 256)), dim3(256), 0, s, a);
   }
-  return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+  return launch_status();
 }
 
 // Bytes of workspace one backward call needs: S / dP (fp32), P and dS (input type), Nq x Ncp
@@ -604,34 +604,34 @@ int launch_bwd_materialized(const KParams& p, int dtype, bool mfma, const void* 
   // X^T Y into `out` (dV_j or dK_j), X = what a.P points at
   auto xty = [&](MatArgs b, const void* X, const void* Y, float* out, float alpha) {
     b.P = const_cast<void*>(X); b.Q = Y; b.out = out; b.alpha = alpha; b.acc = acc_dkv;
-    if (mfma) hipLaunchKernelGGL(mat_xty_mfma_kernel, dim3((unsigned)kb128, (unsigned)kvh), dim3(256), 0, s, b);
-    else if (dtype == BURST_BF16) hipLaunchKernelGGL((mat_xty_generic_kernel<bf16>), dim3(grid1d(kvh * a.Nc * a.d)), dim3(256), 0, s, b);
-    else hipLaunchKernelGGL((mat_xty_generic_kernel<float>), dim3(grid1d(kvh * a.Nc * a.d)), dim3(256), 0, s, b);
+    if (mfma) BURST_LAUNCH(mat_xty_mfma_kernel, dim3((unsigned)kb128, (unsigned)kvh), dim3(256), 0, s, b);
+    else if (dtype == BURST_BF16) BURST_LAUNCH((mat_xty_generic_kernel<bf16>), dim3(grid1d(kvh * a.Nc * a.d)), dim3(256), 0, s, b);
+    else BURST_LAUNCH((mat_xty_generic_kernel<float>), dim3(grid1d(kvh * a.Nc * a.d)), dim3(256), 0, s, b);
   };
   // scale * A B^T into a.S
   auto scores = [&](MatArgs b, const void* A, const void* Bm, float scale) {
     b.Q = A; b.K = Bm; b.scale = scale;
-    if (mfma) hipLaunchKernelGGL(mat_scores_mfma_kernel, dim3((unsigned)kb, (unsigned)qb, (unsigned)a.BH), dim3(256), 0, s, b);
-    else if (dtype == BURST_BF16) hipLaunchKernelGGL((mat_scores_generic_kernel<bf16>), dim3(grid1d((long long)rows * a.Ncp)), dim3(256), 0, s, b);
-    else hipLaunchKernelGGL((mat_scores_generic_kernel<float>), dim3(grid1d((long long)rows * a.Ncp)), dim3(256), 0, s, b);
+    if (mfma) BURST_LAUNCH(mat_scores_mfma_kernel, dim3((unsigned)kb, (unsigned)qb, (unsigned)a.BH), dim3(256), 0, s, b);
+    else if (dtype == BURST_BF16) BURST_LAUNCH((mat_scores_generic_kernel<bf16>), dim3(grid1d((long long)rows * a.Ncp)), dim3(256), 0, s, b);
+    else BURST_LAUNCH((mat_scores_generic_kernel<float>), dim3(grid1d((long long)rows * a.Ncp)), dim3(256), 0, s, b);
   };
 
   scores(a, Q, K, p.scale);                                                        // 1
-  if (dtype == BURST_BF16) hipLaunchKernelGGL((mat_bwd_p_kernel<bf16>), dim3((unsigned)row_blocks), dim3(256), 0, s, a);   // 2
-  else hipLaunchKernelGGL((mat_bwd_p_kernel<float>), dim3((unsigned)row_blocks), dim3(256), 0, s, a);
+  if (dtype == BURST_BF16) BURST_LAUNCH((mat_bwd_p_kernel<bf16>), dim3((unsigned)row_blocks), dim3(256), 0, s, a);   // 2
+  else BURST_LAUNCH((mat_bwd_p_kernel<float>), dim3((unsigned)row_blocks), dim3(256), 0, s, a);
   if (dV != nullptr) xty(a, a.P, dO, dV, 1.0f);                                    // 3
   scores(a, dO, V, 1.0f);                                                          // 4
-  if (dtype == BURST_BF16) hipLaunchKernelGGL((mat_bwd_ds_kernel<bf16>), dim3((unsigned)row_blocks), dim3(256), 0, s, a, (bf16*)dS);   // 5
-  else hipLaunchKernelGGL((mat_bwd_ds_kernel<float>), dim3((unsigned)row_blocks), dim3(256), 0, s, a, (float*)dS);
+  if (dtype == BURST_BF16) BURST_LAUNCH((mat_bwd_ds_kernel<bf16>), dim3((unsigned)row_blocks), dim3(256), 0, s, a, (bf16*)dS);   // 5
+  else BURST_LAUNCH((mat_bwd_ds_kernel<float>), dim3((unsigned)row_blocks), dim3(256), 0, s, a, (float*)dS);
   if (dQ != nullptr) {                                                             // 6
     MatArgs b = a;
     b.P = dS; b.V = K; b.out = dQ; b.alpha = p.scale; b.acc = acc_dq;
-    if (mfma) hipLaunchKernelGGL(mat_pv_merge_mfma_kernel<1>, dim3((unsigned)qb128, (unsigned)a.BH), dim3(256), 0, s, b);
-    else if (dtype == BURST_BF16) hipLaunchKernelGGL((mat_xy_generic_kernel<bf16>), dim3(grid1d((long long)rows * a.d)), dim3(256), 0, s, b);
-    else hipLaunchKernelGGL((mat_xy_generic_kernel<float>), dim3(grid1d((long long)rows * a.d)), dim3(256), 0, s, b);
+    if (mfma) BURST_LAUNCH(mat_pv_merge_mfma_kernel<1>, dim3((unsigned)qb128, (unsigned)a.BH), dim3(256), 0, s, b);
+    else if (dtype == BURST_BF16) BURST_LAUNCH((mat_xy_generic_kernel<bf16>), dim3(grid1d((long long)rows * a.d)), dim3(256), 0, s, b);
+    else BURST_LAUNCH((mat_xy_generic_kernel<float>), dim3(grid1d((long long)rows * a.d)), dim3(256), 0, s, b);
   }
   if (dK != nullptr) xty(a, dS, Q, dK, p.scale);                                   // 7
-  return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+  return launch_status();
 }
 
 }  // namespace burst

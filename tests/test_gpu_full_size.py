@@ -66,6 +66,39 @@ def check_sampled_rows(w, inp, h, O, lse, dQ, n_rows=64, seed=0, pattern=None):
         check(f"dQ[h{h},rows]", f64(dQ[0, h])[rows], dQ_ref, w.dtype)
 
 
+def check_complete_head_by_row_slabs(w, inp, h, O, lse, dQ, dKs, dVs, slab=512, workers=4, forward_every=4):
+    """A complete head where the score matrix of the whole head does not fit in host memory: the
+    oracle runs on slabs of query rows against all keys.  dQ (like O and lse) of a row depends on
+    that row alone; dK and dV are sums over query rows, so the slabs' dK / dV are added up.  Only
+    oracle calls; slabs run on a few threads (numpy releases the interpreter lock)."""
+    from concurrent.futures import ThreadPoolExecutor
+    Q, K, V, dO = head_arrays(inp, h)
+    kp = np.arange(K.shape[0])
+    n_slabs = -(-w.Nq // slab)
+
+    def one(i):
+        rows = slice(i * slab, min(w.Nq, (i + 1) * slab))
+        qp = w.q_off + np.arange(rows.start, rows.stop)
+        fwd = orc.full_forward(Q[rows], K, V, w.scale, w.causal, qp, kp, window=w.window) \
+            if i % forward_every == 0 or i == n_slabs - 1 else None
+        return rows, fwd, orc.full_backward(Q[rows], K, V, dO[rows], w.scale, w.causal, qp, kp, window=w.window)
+
+    dQ_ref = np.zeros_like(Q)
+    dK_ref, dV_ref = np.zeros_like(K), np.zeros_like(V)
+    O_got, lse_got = f64(O[0, h]), f64(lse[0, h])
+    with ThreadPoolExecutor(workers) as pool:
+        for rows, fwd, (dq, dk, dv) in pool.map(one, range(n_slabs)):
+            dQ_ref[rows] = dq
+            dK_ref += dk
+            dV_ref += dv
+            if fwd is not None:
+                check(f"O[h{h},{rows.start}:{rows.stop}]", O_got[rows], fwd[0], w.dtype)
+                check(f"lse[h{h},{rows.start}:{rows.stop}]", lse_got[rows], fwd[1], w.dtype, "lse")
+    check(f"dQ[h{h}]", f64(dQ[0, h]), dQ_ref, w.dtype)
+    check(f"dK[h{h}]", np.concatenate([f64(x[0, h]) for x in dKs]), dK_ref, w.dtype)
+    check(f"dV[h{h}]", np.concatenate([f64(x[0, h]) for x in dVs]), dV_ref, w.dtype)
+
+
 def check_identities(w, inp, h, dQ, dKs, dVs):
     Q, K, V, dO = head_arrays(inp, h)
     dV_sum = sum(f64(x[0, h]).sum(axis=0) for x in dVs)
@@ -105,8 +138,11 @@ def test_llama13b_128k_G8_sampled_rows_and_identities():
         check_sampled_rows(w, inp, h, O, lse, dQ)
     for h in (0, w.H - 1):
         check_identities(w, inp, h, dQ, dKs, dVs)
-    # dK / dV element by element on a reduced query slice of the same shape class:
-    # the first 256 query rows against all 128K keys, complete oracle on one head
+    # one complete head at the full 16384 x 131072 size: dQ, dK, dV element by element (O and lse on
+    # every fourth slab of rows), the oracle evaluated on slabs of query rows
+    check_complete_head_by_row_slabs(w, inp, 23, O, lse, dQ, dKs, dVs)
+    del inp, O, lse, dQ, dKs, dVs
+    # and the first 256 query rows against all 128K keys, complete oracle on one head
     small = workloads.Workload("llama13b_128k_G8_nq256", 1, 2, 128, 256, w.G, w.Nc, "bf16", False, 0, 2003)
     inp, k_offs, walk, O, lse, dQ, dKs, dVs = run_workload(small)
     check_complete_head(small, inp, 1, O, lse, dQ, dKs, dVs)
@@ -118,6 +154,13 @@ def test_llama7b_1m_G32_streaming_sampled_rows_and_identities():
     for h in (0, w.H - 1):
         check_sampled_rows(w, inp, h, O, lse, dQ, n_rows=32)
     check_identities(w, inp, 0, dQ, dKs, dVs)
+    del inp, O, lse, dQ, dKs, dVs
+    # the same kernels on a reduced query slice: 256 query rows against all 32 chunks of 32768 keys,
+    # complete oracle on both heads, all five outputs (dK and dV of every one of the 1M keys)
+    small = workloads.Workload("llama7b_1m_G32_nq256", 1, 2, 128, 256, w.G, w.Nc, "bf16", False, 0, 2004)
+    inp, k_offs, walk, O, lse, dQ, dKs, dVs = run_workload(small)
+    for h in (0, 1):
+        check_complete_head(small, inp, h, O, lse, dQ, dKs, dVs)
 
 
 def test_llama13b_64k_single_device_point():

@@ -407,6 +407,8 @@ def test_double_buffered_walk_is_bitwise_the_plain_walk(source):
         assert torch.equal(O1, O0) and torch.equal(lse1, lse0) and torch.equal(dQ1, dQ0)
         for a, b in zip(dKs1 + dVs1, dKs0 + dVs0):
             assert torch.equal(a, b)
+        # and the double-buffered results themselves against the oracle, every head, all five outputs
+        compare_all_heads(case, "bf16", O1, lse1, dQ1, dKs1, dVs1)
 
 
 def test_backward_without_D_and_accumulate_flags():
