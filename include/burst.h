@@ -68,7 +68,8 @@ enum burst_status {
   BURST_ERR_DTYPE = -4,     /* unknown dtype */
   BURST_ERR_ARCH = -5,      /* current device is not gfx950 */
   BURST_ERR_LAUNCH = -6,    /* the HIP runtime reported a launch error */
-  BURST_ERR_ALLOC = -7      /* internal scratch allocation failed */
+  BURST_ERR_ALLOC = -7,     /* internal scratch allocation failed */
+  BURST_ERR_TOO_LARGE = -8  /* burst_local_bwd_static: B*H*Nq > BURST_STATIC_MAX_ROWS */
 };
 
 typedef struct burst_params {
@@ -156,6 +157,26 @@ int burst_local_bwd(const void* Q, const void* K_chunk, const void* V_chunk,
                     float* dQ, float* dK_chunk, float* dV_chunk,
                     int accumulate_dq, int accumulate_dkv,
                     const burst_params* p, void* stream);
+
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, conventions and results as
+ * burst_local_bwd with D == NULL (D = rowsum(dO o O) is computed by the call), except that D lives
+ * in a static device array inside the library (BURST_STATIC_MAX_ROWS floats = 8 MiB per GPU, held
+ * until the process ends) instead of an allocated buffer: this entry point calls no hipMalloc, no
+ * hipFree and no allocating library routine, ever.  Its first call on a device looks up that
+ * device's address of the array and sets the kernels' function attributes: run it once eagerly
+ * on a device before capturing it.
+ * Limit: B*H*Nq <= BURST_STATIC_MAX_ROWS, else BURST_ERR_TOO_LARGE (nothing enqueued).
+ * All calls on one GPU share the array, which keeps the last call's D: nothing in it has to start
+ * at zero (each call rewrites the B*H*Nq entries it reads), but two calls whose kernels can overlap
+ * on one GPU (different streams without an event between them) race on it.  Calls on one stream,
+ * from any number of host threads, are safe. */
+#define BURST_STATIC_MAX_ROWS (2 * 1024 * 1024)
+int burst_local_bwd_static(const void* Q, const void* K_chunk, const void* V_chunk,
+                           const void* O, const void* dO, const float* lse,
+                           float* dQ, float* dK_chunk, float* dV_chunk,
+                           int accumulate_dq, int accumulate_dkv,
+                           const burst_params* p, void* stream);
 
 /* Size in bytes of the D buffer a burst_local_bwd call with these parameters and D == NULL needs
  * (B*H*Nq*4; the library's own buffer may be larger).  It is the only device memory the library

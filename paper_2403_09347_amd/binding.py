@@ -20,7 +20,7 @@ EXPORTS = [
     "burst_event_elapsed_ms", "burst_event_destroy", "burst_strerror", "burst_version",
     "burst_materialized_workspace_bytes", "burst_local_fwd_materialized", "burst_workspace_bytes",
     "burst_materialized_bwd_workspace_bytes", "burst_local_bwd_materialized", "burst_set_kernel_family",
-    "burst_kernel_family_for",
+    "burst_kernel_family_for", "burst_local_bwd_static",
 ]
 
 
@@ -71,6 +71,8 @@ def load():
     lib.burst_merge_state.argtypes = [fp, fp, fp, fp, fp, fp, pp, vp]
     lib.burst_bwd_prepare.argtypes = [vp, vp, fp, pp, vp]
     lib.burst_local_bwd.argtypes = [vp, vp, vp, vp, vp, fp, fp, fp, fp, fp, ctypes.c_int, ctypes.c_int, pp, vp]
+    lib.burst_local_bwd_static.argtypes = [vp, vp, vp, vp, vp, fp, fp, fp, fp, ctypes.c_int, ctypes.c_int, pp, vp]
+    lib.burst_local_bwd_static.restype = ctypes.c_int
     lib.burst_local_bwd_dq.argtypes = [vp, vp, vp, vp, fp, fp, fp, ctypes.c_int, pp, vp]
     lib.burst_local_bwd_dkv.argtypes = [vp, vp, vp, vp, fp, fp, fp, fp, ctypes.c_int, pp, vp]
     for name in ("burst_local_bwd_dq", "burst_local_bwd_dkv", "burst_state_init", "burst_local_fwd", "burst_finalize", "burst_merge_state",
@@ -257,6 +259,18 @@ def burst_local_bwd(Q, K_chunk, V_chunk, O, dO, lse, D, dQ, dK_chunk, dV_chunk, 
                                   _f32(dQ), _f32(dK_chunk), _f32(dV_chunk),
                                   1 if accumulate_dq else 0, 1 if accumulate_dkv else 0,
                                   ctypes.byref(p), _stream()), "burst_local_bwd")
+
+
+BURST_STATIC_MAX_ROWS = 2 * 1024 * 1024
+
+
+def burst_local_bwd_static(Q, K_chunk, V_chunk, O, dO, lse, dQ, dK_chunk, dV_chunk, p,
+                           accumulate_dq=True, accumulate_dkv=False):
+    """burst_local_bwd with D computed into the library's static device scratch: allocates nothing."""
+    _check(load().burst_local_bwd_static(_q(Q, p), _kv(K_chunk, p), _kv(V_chunk, p), _q(O, p), _q(dO, p), _f32(lse),
+                                         _f32(dQ), _f32(dK_chunk), _f32(dV_chunk),
+                                         1 if accumulate_dq else 0, 1 if accumulate_dkv else 0,
+                                         ctypes.byref(p), _stream()), "burst_local_bwd_static")
 
 
 def burst_local_bwd_dq(Q, K_chunk, V_chunk, dO, lse, D, dQ, p, accumulate_dq=True):

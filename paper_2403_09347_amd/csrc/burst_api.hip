@@ -66,6 +66,31 @@ struct DScratch { int dev; hipStream_t stream; float* ptr; size_t elems; };
 std::vector<DScratch> g_d_scratch;
 std::mutex g_bwd_mutex;
 
+// Static device scratch for burst_local_bwd_static (the entry point for callers that cannot
+// allocate): D of one call, BURST_STATIC_MAX_ROWS floats = 8 MiB, held by every GPU the library runs
+// on until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the device address is looked up once per device (each GPU has its own
+// copy) and kept here, and that pointer, never the name, is what kernels are given.
+static __device__ __align__(256) float scratch[BURST_STATIC_MAX_ROWS];
+float* g_static_d[kMaxDevices];
+burst::DeviceOnce g_static_d_once;
+
+int static_d_buffer(float** out) {
+  const int st = g_static_d_once.run([] {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return (int)BURST_ERR_LAUNCH;
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return (int)BURST_ERR_LAUNCH;
+    g_static_d[dev] = static_cast<float*>(ptr);
+    return (int)BURST_OK;
+  });
+  if (st != BURST_OK) return st;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return BURST_ERR_LAUNCH;
+  *out = g_static_d[dev];
+  return BURST_OK;
+}
+
 int check_arch() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return BURST_ERR_ARCH;
@@ -370,11 +395,12 @@ int burst_bwd_prepare(const void* O, const void* dO, float* D, const burst_param
 }
 
 // Shared by the three backward entry points.  which: 1 = dQ, 2 = dK/dV, 3 = both.
+// static_d: D == NULL takes the static device scratch instead of an allocated buffer.
 static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const void* V_chunk,
                           const void* O, const void* dO, const float* lse, const float* D,
                           float* dQ, float* dK_chunk, float* dV_chunk,
                           int accumulate_dq, int accumulate_dkv,
-                          const burst_params* p, void* stream) {
+                          const burst_params* p, void* stream, bool static_d = false) {
   KParams k;
   int st = check_params(p, &k);
   if (st != BURST_OK) return st;
@@ -388,6 +414,7 @@ static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const v
   if (want_dkv && have_k) { REQUIRE_PTR(dK_chunk); REQUIRE_PTR(dV_chunk); }
   if (D != nullptr && !aligned16(D)) return BURST_ERR_ALIGN;
   if (D == nullptr && have_q && have_k) REQUIRE_PTR(O);
+  if (static_d && bh * k.Nq > (long long)BURST_STATIC_MAX_ROWS) return BURST_ERR_TOO_LARGE;
   if ((st = check_arch()) != BURST_OK) return st;
   hipStream_t s = (hipStream_t)stream;
   // Degenerate sides: nothing to contract over, the contribution is zero.
@@ -426,9 +453,9 @@ static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const v
   };
   if (D != nullptr) return validated([&] { return enqueue(D, nullptr); });
   std::lock_guard<std::mutex> lock(g_bwd_mutex);
-  float* scratch = nullptr;
-  if ((st = get_d_scratch(s, (size_t)(bh * k.Nq), &scratch)) != BURST_OK) return st;
-  return validated([&] { return enqueue(scratch, scratch); });
+  float* dbuf = nullptr;
+  if ((st = static_d ? static_d_buffer(&dbuf) : get_d_scratch(s, (size_t)(bh * k.Nq), &dbuf)) != BURST_OK) return st;
+  return validated([&] { return enqueue(dbuf, dbuf); });
 }
 
 int burst_local_bwd(const void* Q, const void* K_chunk, const void* V_chunk,
@@ -438,6 +465,15 @@ int burst_local_bwd(const void* Q, const void* K_chunk, const void* V_chunk,
                     const burst_params* p, void* stream) {
   return local_bwd_impl(3, Q, K_chunk, V_chunk, O, dO, lse, D, dQ, dK_chunk, dV_chunk,
                         accumulate_dq, accumulate_dkv, p, stream);
+}
+
+int burst_local_bwd_static(const void* Q, const void* K_chunk, const void* V_chunk,
+                           const void* O, const void* dO, const float* lse,
+                           float* dQ, float* dK_chunk, float* dV_chunk,
+                           int accumulate_dq, int accumulate_dkv,
+                           const burst_params* p, void* stream) {
+  return local_bwd_impl(3, Q, K_chunk, V_chunk, O, dO, lse, nullptr, dQ, dK_chunk, dV_chunk,
+                        accumulate_dq, accumulate_dkv, p, stream, /*static_d=*/true);
 }
 
 int burst_local_bwd_dq(const void* Q, const void* K_chunk, const void* V_chunk,
@@ -485,10 +521,11 @@ const char* burst_strerror(int status) {
     case BURST_ERR_ARCH: return "current device is not gfx950";
     case BURST_ERR_LAUNCH: return "HIP runtime reported a launch error";
     case BURST_ERR_ALLOC: return "internal scratch allocation failed";
+    case BURST_ERR_TOO_LARGE: return "B*H*Nq exceeds the static scratch of burst_local_bwd_static (BURST_STATIC_MAX_ROWS rows)";
     default: return "unknown status";
   }
 }
 
-int burst_version(void) { return 109; }
+int burst_version(void) { return 110; }
 
 }  // extern "C"

@@ -78,6 +78,13 @@ def test_argument_validation_without_gpu():
     assert lib.burst_state_init(mis, mis, mis, ctypes.byref(ok), null) == -2         # misaligned
     empty = binding.params(1, 1, 0, 16, 128, "bf16", 0.5)      # nothing to do: ok without pointers
     assert lib.burst_state_init(null, null, null, ctypes.byref(empty), null) == 0
+    # the entry point that allocates nothing rejects calls beyond its static scratch before any
+    # device call (the addresses below are never dereferenced)
+    big = binding.params(1, 32, binding.BURST_STATIC_MAX_ROWS // 32 + 1, 64, 128, "bf16", 0.5)
+    a = ctypes.c_void_p(4096)
+    assert lib.burst_local_bwd_static(a, a, a, a, a, a, a, a, a, 1, 0, ctypes.byref(big), null) == -8
+    assert b"static scratch" in lib.burst_strerror(-8)
+    assert lib.burst_local_bwd_static(a, a, a, null, a, a, a, a, a, 1, 0, ctypes.byref(ok), null) == -1   # O is needed
 
 
 def test_materialized_workspace_size_without_gpu():
