@@ -254,6 +254,23 @@ int   burst_event_record(void* event, void* stream);
 int   burst_event_elapsed_ms(void* start, void* stop, float* ms); /* waits for `stop` */
 void  burst_event_destroy(void* event);
 
+/* Micro-benchmarks for the measurement harness (no counterpart in the paper): the rates the
+ * attention kernels are compared with, measured with the instruction forms they use.
+ * burst_probe_mfma: 256 workgroups of 4 * wavefronts_per_simd (1 or 2) wavefronts; each wavefront
+ * issues iters * 16 v_mfma_f32_32x32x16_bf16 (32768 FLOP each) and nothing else.  a_from_lds: 0 =
+ * both operands stay in registers, 1 = the A operand of every MFMA is read fresh from LDS (128-bit
+ * reads), 2 = of every second MFMA.  operands: 64 KiB of bf16 values on the device (their contents
+ * set how many bits toggle, and with that the clock the chip sustains); sink: 256 * 512 floats,
+ * written.  The caller times the launch.
+ * burst_probe_atomic_dq: the atomic traffic of a backward that would compute a block pair once,
+ * keys stationary, and add its dQ partial sums with fp32 atomics: heads * key_blocks workgroups
+ * (heads a multiple of 8), each adding one [64][128] tile per 64 query rows into dQ [heads][Nq][128]
+ * (Nq a multiple of 64); atomic = 0 writes plain stores in the same pattern for comparison.  No
+ * arithmetic: a lower bound on what such a kernel would take. */
+int burst_probe_mfma(int a_from_lds, int wavefronts_per_simd, const void* operands, float* sink, int iters,
+                     void* stream);
+int burst_probe_atomic_dq(float* dQ, int heads, int Nq, int key_blocks, int atomic, void* stream);
+
 const char* burst_strerror(int status);
 int         burst_version(void);
 

@@ -20,7 +20,7 @@ EXPORTS = [
     "burst_event_elapsed_ms", "burst_event_destroy", "burst_strerror", "burst_version",
     "burst_materialized_workspace_bytes", "burst_local_fwd_materialized", "burst_workspace_bytes",
     "burst_materialized_bwd_workspace_bytes", "burst_local_bwd_materialized", "burst_set_kernel_family",
-    "burst_kernel_family_for", "burst_local_bwd_static",
+    "burst_kernel_family_for", "burst_local_bwd_static", "burst_probe_mfma", "burst_probe_atomic_dq",
 ]
 
 
@@ -208,6 +208,29 @@ def burst_kernel_family_for(p):
     lib.burst_kernel_family_for.argtypes = [ctypes.POINTER(BurstParams)]
     lib.burst_kernel_family_for.restype = ctypes.c_int
     return int(lib.burst_kernel_family_for(ctypes.byref(p)))
+
+
+def burst_probe_mfma(a_from_lds, wavefronts_per_simd, operands, sink, iters):
+    """operands: >= 64 KiB of bf16 on the device; sink: >= 256 * 512 float32 (see burst.h)."""
+    lib = load()
+    lib.burst_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                     ctypes.c_void_p]
+    lib.burst_probe_mfma.restype = ctypes.c_int
+    if operands.numel() * operands.element_size() < 65536 or sink.numel() < 256 * 512:
+        raise ValueError("burst_probe_mfma: operands >= 64 KiB and sink >= 131072 floats expected")
+    _check(lib.burst_probe_mfma(int(a_from_lds), int(wavefronts_per_simd), _ptr(operands), _f32(sink), int(iters),
+                                _stream()), "burst_probe_mfma")
+
+
+def burst_probe_atomic_dq(dQ, heads, Nq, key_blocks, atomic):
+    lib = load()
+    lib.burst_probe_atomic_dq.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                          ctypes.c_void_p]
+    lib.burst_probe_atomic_dq.restype = ctypes.c_int
+    if dQ.numel() < heads * Nq * 128:
+        raise ValueError("burst_probe_atomic_dq: dQ too small")
+    _check(lib.burst_probe_atomic_dq(_f32(dQ), int(heads), int(Nq), int(key_blocks), 1 if atomic else 0, _stream()),
+           "burst_probe_atomic_dq")
 
 
 def burst_workspace_bytes(p):

@@ -8,7 +8,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libburst.so")
 SOURCES = ["burst_api.hip", "burst_elementwise.hip", "burst_generic.hip",
            "burst_fwd_mfma.hip", "burst_bwd_dq_mfma.hip", "burst_bwd_dkv_mfma.hip",
-           "burst_materialized.hip", "burst_d64_mfma.hip", "burst_d128_plain.hip"]
+           "burst_materialized.hip", "burst_d64_mfma.hip", "burst_d128_plain.hip", "burst_probe.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-ffast-math", "-fno-finite-math-only", "-fno-honor-nans",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-mllvm", "-amdgpu-mfma-vgpr-form=1", "-Wno-unused-command-line-argument",
