@@ -415,11 +415,12 @@ burst_bwd_dkv_kernel(BwdArgs a) {
       __builtin_amdgcn_s_barrier();
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): no DMA may outlive the loop
+    // wait for the last MFMAs before anything else touches the accumulators (inside the block:
+    // behind the join with the path that skipped the loop the compiler may already move them)
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15"
+                 : "+a"(dk[0]), "+a"(dk[1]), "+a"(dk[2]), "+a"(dk[3]),
+                   "+a"(dv[0]), "+a"(dv[1]), "+a"(dv[2]), "+a"(dv[3]));
   }
-  // wait for the last MFMAs before reading the accumulators
-  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15"
-               : "+a"(dk[0]), "+a"(dk[1]), "+a"(dk[2]), "+a"(dk[3]),
-                 "+a"(dv[0]), "+a"(dv[1]), "+a"(dv[2]), "+a"(dv[3]));
   // epilogue: keys are owned by this wavefront alone. C layout: lane = d column, regs = keys.
   float* dKh = a.dK + (size_t)head * a.Nc * 128;
   float* dVh = a.dV + (size_t)head * a.Nc * 128;

@@ -431,8 +431,11 @@ burst_bwd_dq_kernel(BwdArgs a) {
       });
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): no DMA may outlive the loop
+    // The fence stands here, inside the block, on purpose: behind the join with the path that
+    // skipped the loop the compiler may move the accumulators to other registers, and those moves
+    // are vector instructions that would read them while the last MFMAs are still in flight.
+    mfma_acc_fence(dq);
   }
-  mfma_acc_fence(dq);
   // epilogue: dQ rows are owned by this wavefront alone
 #pragma unroll
   for (int rb = 0; rb < 2; rb++) {
