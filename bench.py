@@ -252,13 +252,16 @@ def fused_backward_floor_measurement(w, dev):
     """Lower bound for a backward that computes each block pair once (five contractions instead of the
     seven of the two-kernel form): with the keys stationary its dQ partial sums leave every
     128-key workgroup through fp32 atomic adds, B*H*Nq*d*(Nc/128) of them per block pair.
-    burst_probe_atomic_dq issues exactly those adds and nothing else."""
+    burst_probe_atomic_dq issues exactly those adds and nothing else; also the same pattern as plain
+    stores and as plain load-add-store (what workgroups that took turns on a tile under a lock would
+    issue: the memory time alone, without the locks, and not reproducible bit for bit)."""
     import torch
     from paper_2403_09347_amd import binding as B
     heads = (w.B * w.H + 7) // 8 * 8
     dq = torch.zeros(heads * w.Nq * 128, device=dev, dtype=torch.float32)
     out = {}
-    for name, atomic in (("atomic_adds_ms", 1), ("plain_stores_same_pattern_ms", 0)):
+    for name, atomic in (("atomic_adds_ms", 1), ("plain_stores_same_pattern_ms", 0),
+                         ("plain_read_modify_write_same_pattern_ms", 2)):
         B.burst_probe_atomic_dq(dq, heads, w.Nq, w.Nc // 128, atomic)
         best = 1e30
         for _ in range(3):

@@ -265,8 +265,9 @@ void  burst_event_destroy(void* event);
  * burst_probe_atomic_dq: the atomic traffic of a backward that would compute a block pair once,
  * keys stationary, and add its dQ partial sums with fp32 atomics: heads * key_blocks workgroups
  * (heads a multiple of 8), each adding one [64][128] tile per 64 query rows into dQ [heads][Nq][128]
- * (Nq a multiple of 64); atomic = 0 writes plain stores in the same pattern for comparison.  No
- * arithmetic: a lower bound on what such a kernel would take. */
+ * (Nq a multiple of 64); atomic = 0 writes plain stores in the same pattern, atomic = 2 plain
+ * load-add-store (racing, timing only), for comparison.  No arithmetic: a lower bound on what such a
+ * kernel would take. */
 int burst_probe_mfma(int a_from_lds, int wavefronts_per_simd, const void* operands, float* sink, int iters,
                      void* stream);
 int burst_probe_atomic_dq(float* dQ, int heads, int Nq, int key_blocks, int atomic, void* stream);

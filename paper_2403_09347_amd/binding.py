@@ -229,7 +229,7 @@ def burst_probe_atomic_dq(dQ, heads, Nq, key_blocks, atomic):
     lib.burst_probe_atomic_dq.restype = ctypes.c_int
     if dQ.numel() < heads * Nq * 128:
         raise ValueError("burst_probe_atomic_dq: dQ too small")
-    _check(lib.burst_probe_atomic_dq(_f32(dQ), int(heads), int(Nq), int(key_blocks), 1 if atomic else 0, _stream()),
+    _check(lib.burst_probe_atomic_dq(_f32(dQ), int(heads), int(Nq), int(key_blocks), int(atomic), _stream()),
            "burst_probe_atomic_dq")
 
 

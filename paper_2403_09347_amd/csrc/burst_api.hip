@@ -34,6 +34,8 @@ namespace d128p {
 int launch_fwd(const KParams&, const void*, const void*, const void*, float*, float*, float*, hipStream_t);
 int launch_bwd_dq(const KParams&, const void*, const void*, const void*, const void*, const float*,
                   const float*, float*, int, hipStream_t);
+int launch_bwd_dkv(const KParams&, const void*, const void*, const void*, const void*, const float*,
+                   const float*, float*, float*, int, hipStream_t);
 }  // namespace d128p
 size_t materialized_workspace_bytes(const KParams&, int);
 size_t materialized_bwd_workspace_bytes(const KParams&, int);
@@ -224,6 +226,19 @@ int validated(F&& enqueue) {
 }
 
 // Caller holds g_bwd_mutex.
+// The dK/dV call of a d = 128 block pair goes to the plain kernel with 64-key workgroups when the
+// call's flags have 64-wide blocks (its time then follows the density; the hand-scheduled kernel's
+// 128-key workgroups cannot skip what only half of their keys need), or when the plain family is
+// forced.  Its tile lists hold 4096 entries of 32 query rows (all heads of a group).
+bool use_plain128_dkv(const burst_params* p, const KParams& k) {
+  if (!use_mfma(p, k)) return false;
+  const bool flags = p->block_mask != nullptr;
+  if (flags && (long long)k.group * ((p->Nq + 31) / 32) > 4096) return false;
+  const int family = g_kernel_family.load(std::memory_order_relaxed);
+  if (family != 0) return family == 2;
+  return flags && p->block < 128;
+}
+
 int get_d_scratch(hipStream_t stream, size_t elems, float** out) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return BURST_ERR_ALLOC;
@@ -430,7 +445,7 @@ static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const v
   // The kernels of this call: D (when it is not given), then the dQ half, then the dK/dV half.
   const bool mfma_dq = use_mfma(p, k) && (p->block_mask == nullptr || p->Nc <= kMaxMaskedRows);
   const bool mfma_dkv = use_mfma(p, k) && dkv_mfma_ok(p, k);
-  const bool d64 = use_d64(p, k), plain128 = use_plain128(p, k);
+  const bool d64 = use_d64(p, k), plain128 = use_plain128(p, k), plain128_dkv = use_plain128_dkv(p, k);
   const bool adq = accumulate_dq != 0, adkv = accumulate_dkv != 0;
   auto enqueue = [&](const float* Duse, float* Dwrite) -> int {
     int e;
@@ -444,6 +459,7 @@ static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const v
     }
     if (want_dkv) {
       e = d64 ? burst::d64::launch_bwd_dkv(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk, adkv, s)
+        : plain128_dkv ? burst::d128p::launch_bwd_dkv(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk, adkv, s)
         : mfma_dkv ? burst::launch_bwd_dkv_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk, adkv, s)
                    : burst::launch_bwd_dkv_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk,
                                                    dV_chunk, adkv, s);
@@ -526,6 +542,6 @@ const char* burst_strerror(int status) {
   }
 }
 
-int burst_version(void) { return 110; }
+int burst_version(void) { return 111; }
 
 }  // extern "C"

@@ -1,12 +1,16 @@
-// The plainly written forward and dQ kernels of burst_plain_mfma.h compiled for d = 128
-// (namespace burst::d128p): 128 query rows per workgroup and two workgroups per CU, for calls
-// whose query slice is too short to give every CU one of the 256-row workgroups of the
-// hand-scheduled kernels, and for calls with block flags finer than those workgroups: here a
-// wavefront skips the tiles the flags hide from its own 32 rows, which the hand-scheduled
-// kernels cannot (their matrix phases admit no branch).  (The dK/dV side needs none: its
-// workgroups own 128 keys either way, and the plain dK/dV kernel at d = 128 spills registers and
-// is slower than the hand-scheduled one even on fine patterns.)
+// The plainly written kernels of burst_plain_mfma.h compiled for d = 128 (namespace burst::d128p).
+// Forward and dQ: 128 query rows per workgroup and two workgroups per CU, for calls whose query
+// slice is too short to give every CU one of the 256-row workgroups of the hand-scheduled kernels,
+// and for calls with block flags finer than those workgroups: here a wavefront skips the tiles the
+// flags hide from its own 32 rows, which the hand-scheduled kernels cannot (their accumulators are
+// pinned to AGPRs through inline assembly, and a branch around the matrix phases makes the
+// register allocator move all of them through VGPRs in every iteration).
+// dK/dV: two wavefronts = 64 keys per workgroup, two workgroups per CU, for calls whose flags have
+// 64-wide blocks: a workgroup's list of visible tiles then holds exactly the tiles its keys are
+// needed for, and the time follows the density of the flags.  (The hand-scheduled dK/dV kernel
+// shares every tile among the 128 keys of its four wavefronts: a tile that only half of them can
+// see costs it the full time.  On dense calls it is the faster one.)
 #define BURST_SMALL_D 128
 #define BURST_SMALL_NS d128p
-#define BURST_SMALL_NO_DKV
+#define BURST_SMALL_DKV_WAVES 2
 #include "burst_plain_mfma.h"

@@ -2,9 +2,10 @@
 // Sec. 2.4) and the two halves of the backward block pair (Alg. 2 loop body), bf16, with the head
 // dimension a compile-time constant.  This header is the source of two kernel families; each is
 // built by a small translation unit that defines BURST_SMALL_D (head dimension), BURST_SMALL_NS
-// (namespace) and, optionally, BURST_SMALL_NO_DKV before including it:
+// (namespace) and, optionally, BURST_SMALL_DKV_WAVES before including it:
 //   burst_d64_mfma.hip    d = 64, namespace burst::d64, all three kernels
-//   burst_d128_plain.hip  d = 128, namespace burst::d128p, forward and dQ only
+//   burst_d128_plain.hip  d = 128, namespace burst::d128p, all three kernels, the dK/dV one with
+//                         two wavefronts (64 keys) per workgroup (BURST_SMALL_DKV_WAVES = 2)
 //
 // Same mathematics, operand orientations and register layouts as the hand-scheduled d = 128
 // kernels (S^T = K Q^T with one query row per lane for the forward and dQ side, S = Q K^T with one
@@ -491,15 +492,23 @@ burst_bwd_dq_d64_kernel(BwdArgs a) {
   }
 }
 
-#ifndef BURST_SMALL_NO_DKV
 // ------------------------------------------------------------------------------- backward, dK / dV
-constexpr int SK_BC = 128;                        // keys per workgroup (4 wavefronts x 32)
+// Wavefronts per dK/dV workgroup, 32 keys each.  Four by default.  With two (BURST_SMALL_DKV_WAVES
+// = 2: the d = 128 build) a workgroup owns 64 keys, the finest block edge a call's flags can have,
+// so its list of visible tiles is exactly the tiles those 64 keys are needed for, and two such
+// workgroups share a CU at one wavefront per SIMD (the kernel needs more than 256 registers at
+// d = 128).
+#ifndef BURST_SMALL_DKV_WAVES
+#define BURST_SMALL_DKV_WAVES 4
+#endif
+constexpr int SK_WAVES = BURST_SMALL_DKV_WAVES;
+constexpr int SK_BC = 32 * SK_WAVES;              // keys per workgroup
 constexpr int SK_BR = 32;                         // query rows per tile
 constexpr int SK_TILE = SK_BR * S_ROWB;
 constexpr int SK_STAT = 4 * SK_TILE;              // per buffer: 32 x (-lse log2 e), 32 x D
 
 template <bool SPARSE>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(64 * SK_WAVES, SK_WAVES == 4 ? 2 : 1)   // (second figure: wavefronts per SIMD)
 burst_bwd_dkv_d64_kernel(BwdArgs a) {
   __shared__ __attribute__((aligned(16))) char smem[4 * SK_TILE + 2 * 64 * 4];   // Q[2], dO[2], statistics[2]
   extern __shared__ int s_list[];
@@ -532,7 +541,7 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
       const uint8_t* mrow = a.bmask + (size_t)(kvhead * a.group + g) * a.bhstride + (size_t)((t * SK_BR) / a.bsize) * a.bpitch;
       int bits = 0;
 #pragma unroll
-      for (int ww = 0; ww < 4; ww++) {
+      for (int ww = 0; ww < SK_WAVES; ww++) {
         const int k0 = key_wg + ww * 32;
         if (k0 < a.Nc && mrow[k0 / a.bsize] != 0) bits |= 1 << ww;
       }
@@ -570,7 +579,8 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
     s_taddr(lane, taddr);
     const int wu = __builtin_amdgcn_readfirstlane(w);
     const unsigned lds0 = lds_addr(smem);
-    constexpr int NL = SK_BR / S_RPL / 4;         // wave-wide loads per wavefront and tile
+    constexpr int NL = SK_BR / S_RPL / SK_WAVES;  // wave-wide loads per wavefront and tile
+    static_assert(NL >= 1 && NL * SK_WAVES * S_RPL == SK_BR, "a tile's rows must divide evenly among the wavefronts");
     int goff[NL];
 #pragma unroll
     for (int il = 0; il < NL; il++) goff[il] = s_dma_off(w * NL + il, lane, qpitch);
@@ -690,7 +700,6 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
 }
 
 
-#endif  // BURST_SMALL_NO_DKV
 
 // ------------------------------------------------------------------------------- launchers
 // Tile lists are dynamic LDS behind up to 64 KB of static tiles: the kernels that take one opt
@@ -748,7 +757,6 @@ int launch_bwd_dq(const KParams& p, const void* Q, const void* K, const void* V,
   return launch_status();
 }
 
-#ifndef BURST_SMALL_NO_DKV
 int launch_bwd_dkv(const KParams& p, const void* Q, const void* K, const void* V,
                        const void* dO, const float* lse, const float* D, float* dK, float* dV,
                        int acc_dkv, hipStream_t stream) {
@@ -763,13 +771,12 @@ int launch_bwd_dkv(const KParams& p, const void* Q, const void* K, const void* V
     if (entries > S_MAX_LIST) return BURST_ERR_SHAPE;
     static DeviceOnce done;
     if (int st = allow_list(burst_bwd_dkv_d64_kernel<true>, done); st != BURST_OK) return st;
-    BURST_LAUNCH(burst_bwd_dkv_d64_kernel<true>, dim3((unsigned)nb), dim3(256), ((int)entries + 4) * 4, stream, a);
+    BURST_LAUNCH(burst_bwd_dkv_d64_kernel<true>, dim3((unsigned)nb), dim3(64 * SK_WAVES), ((int)entries + 4) * 4, stream, a);
   } else {
-    BURST_LAUNCH(burst_bwd_dkv_d64_kernel<false>, dim3((unsigned)nb), dim3(256), 0, stream, a);
+    BURST_LAUNCH(burst_bwd_dkv_d64_kernel<false>, dim3((unsigned)nb), dim3(64 * SK_WAVES), 0, stream, a);
   }
   return launch_status();
 }
-#endif  // BURST_SMALL_NO_DKV
 
 }  // namespace BURST_SMALL_NS
 }  // namespace burst

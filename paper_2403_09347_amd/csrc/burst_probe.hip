@@ -63,7 +63,9 @@ __global__ void __launch_bounds__(512) probe_mfma_kernel(const bf16x8* __restric
 // fp32 tile into dQ for each: wavefront w owns 32 of the 128 columns, a lane one column and 32
 // rows, in the register layout an MFMA accumulator of dQ = dS K would have.  Workgroups of a head
 // start at different tiles so that they do not all hit the same rows at once.
-template <bool ATOMIC>
+// MODE 1: atomic adds; 0: plain stores; 2: plain read-modify-write (load, add, store: what a
+// workgroup that held a tile exclusively would do).
+template <int MODE>
 __global__ void __launch_bounds__(256) probe_atomic_dq_kernel(float* __restrict__ dq, int nq, int key_blocks) {
   const int bid = blockIdx.x, xcd = bid & 7, idx = bid >> 3;
   const int hx = idx / key_blocks, kb = idx - hx * key_blocks, head = hx * 8 + xcd;
@@ -78,7 +80,8 @@ __global__ void __launch_bounds__(256) probe_atomic_dq_kernel(float* __restrict_
       for (int r = 0; r < 16; r++) {
         const int row = qt * 64 + rb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
         float* p = base + (size_t)row * 128 + w * 32 + col;
-        if constexpr (ATOMIC) unsafeAtomicAdd(p, 1.0f);
+        if constexpr (MODE == 1) unsafeAtomicAdd(p, 1.0f);
+        else if constexpr (MODE == 2) __builtin_nontemporal_store(__builtin_nontemporal_load(p) + 1.0f, p);
         else *p = 1.0f;
       }
   }
@@ -111,8 +114,9 @@ int burst_probe_atomic_dq(float* dQ, int heads, int Nq, int key_blocks, int atom
       key_blocks > 4096) return BURST_ERR_SHAPE;
   const dim3 grid((unsigned)(heads * key_blocks)), block(256);
   hipStream_t s = (hipStream_t)stream;
-  if (atomic) hipLaunchKernelGGL(probe_atomic_dq_kernel<true>, grid, block, 0, s, dQ, Nq, key_blocks);
-  else hipLaunchKernelGGL(probe_atomic_dq_kernel<false>, grid, block, 0, s, dQ, Nq, key_blocks);
+  if (atomic == 1) hipLaunchKernelGGL(probe_atomic_dq_kernel<1>, grid, block, 0, s, dQ, Nq, key_blocks);
+  else if (atomic == 2) hipLaunchKernelGGL(probe_atomic_dq_kernel<2>, grid, block, 0, s, dQ, Nq, key_blocks);
+  else hipLaunchKernelGGL(probe_atomic_dq_kernel<0>, grid, block, 0, s, dQ, Nq, key_blocks);
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 

@@ -204,15 +204,17 @@ def test_llama7b_32k_G8_with_scores_stored_in_hbm():
         check_sampled_rows(w, inp, h, O, lse, None)
 
 
-def test_llama7b_32k_G8_block_sparse_band_plus_global():
-    """Block flags (Sec. 2.6) at the benchmark's full size: a band of 128-wide blocks around the
-    diagonal of rank 3's slice plus global first blocks, one flag matrix per chunk.  Lists of
-    visible tiles are longer than one round of the list builder for every kernel.  One complete
-    head (all five outputs) and sampled rows of others against the oracle."""
+@pytest.mark.parametrize("block", [128, 64])
+def test_llama7b_32k_G8_block_sparse_band_plus_global(block):
+    """Block flags (Sec. 2.6) at the benchmark's full size: a band of blocks around the diagonal of
+    rank 3's slice plus global first blocks, one flag matrix per chunk.  Lists of visible tiles are
+    longer than one round of the list builder for every kernel.  One complete head (all five
+    outputs) and sampled rows of others against the oracle.  With 64-wide blocks the forward and
+    dQ calls go to the 128-row kernels and the dK/dV call to the kernel with 64-key workgroups."""
     w = workloads.by_name("llama7b_32k_G8")
     inp = workloads.make_inputs(w, DEV)
     k_offs = [w.k_off(j) for j in range(w.G)]
-    block, q_off = 128, 3 * w.Nq
+    q_off = 3 * w.Nq
     nrb, ncb = w.Nq // block, w.Nc // block
     flags = [workloads.block_flags(nrb, ncb, "band_global", seed=7 + j, diag_shift=(q_off - k_offs[j]) // block)
              for j in range(w.G)]

@@ -411,6 +411,45 @@ def test_double_buffered_walk_is_bitwise_the_plain_walk(source):
         compare_all_heads(case, "bf16", O1, lse1, dQ1, dKs1, dVs1)
 
 
+def test_backward_without_D_on_two_streams_at_once():
+    """burst_local_bwd with D = NULL keeps one library-owned D buffer per (device, stream): two
+    walks with different inputs and sizes, enqueued alternately on two streams with no event
+    between them, must each give the gradients of the walk with D given, bit for bit (a buffer
+    shared by the two streams would be overwritten by the other walk's D); the second, larger
+    round also makes both buffers grow while the first round's kernels may still be running."""
+    streams = [torch.cuda.Stream(device=DEV), torch.cuda.Stream(device=DEV)]
+    for rnd, sizes in enumerate((((2, 200, [150, 170]), (3, 330, [260])), ((2, 900, [512, 300]), (4, 650, [700])))):
+        cases, walks, refs = [], [], []
+        for i, (H, Nq, rows) in enumerate(sizes):
+            case = workloads.make_case(B=1, H=H, d=128, Nq=Nq, chunk_rows=rows, dtype="bf16", seed=70 + 2 * rnd + i,
+                                       device=DEV, causal=bool(i), q_off=100 * i)
+            walk, (O, lse, dQ, dKs, dVs) = run_case(case, "bf16", use_D=True)
+            cases.append(case)
+            walks.append(walk)
+            refs.append((dQ.clone(), [t.clone() for t in dKs], [t.clone() for t in dVs]))
+        torch.cuda.synchronize()
+        outs = []
+        for i, case in enumerate(cases):
+            dQ = torch.zeros_like(refs[i][0])
+            outs.append((dQ, [torch.empty_like(t) for t in refs[i][1]], [torch.empty_like(t) for t in refs[i][2]]))
+        n_chunks = max(len(c["K"]) for c in cases)
+        for j in range(n_chunks):                       # alternate the two streams chunk by chunk
+            for i, case in enumerate(cases):
+                if j >= len(case["K"]):
+                    continue
+                with torch.cuda.stream(streams[i]):
+                    w = walks[i]
+                    B.burst_local_bwd(case["Q"], case["K"][j], case["V"][j], w.O, case["dO"], w.lse, None,
+                                      outs[i][0], outs[i][1][j], outs[i][2][j],
+                                      w.params(case["K"][j].shape[2], case["k_offs"][j], None, case["K"][j]),
+                                      accumulate_dq=True, accumulate_dkv=False)
+        torch.cuda.synchronize()
+        for (dQ, dKs, dVs), (rQ, rKs, rVs) in zip(outs, refs):
+            assert torch.equal(dQ, rQ)
+            for a, b in zip(dKs + dVs, rKs + rVs):
+                assert torch.equal(a, b)
+
+
 def test_backward_without_D_and_accumulate_flags():
     case = workloads.make_case(B=1, H=2, d=128, Nq=200, chunk_rows=[150, 170], dtype="bf16", seed=51, device=DEV)
     walk, (O, lse, dQ, dKs, dVs) = run_case(case, "bf16", use_D=True)
