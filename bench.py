@@ -311,9 +311,11 @@ def measured_traffic(kernel, workload):
     return None
 
 
-def measure_workload(w, dev, steps, warmup, detailed):
+def measure_workload(w, dev, steps, warmup, detailed, zero_inputs=False):
     """Times `steps` steps of workload w (after `warmup` untimed ones).  Returns the figures of the
-    JSON line; with `detailed` also the inputs and the walk for the follow-up measurements."""
+    JSON line; with `detailed` also the inputs and the walk for the follow-up measurements.
+    zero_inputs: the same launches on all-zero Q, K, V, dO (a diagnostic: the instruction stream is
+    the same, the matrix cores' operands toggle no bits)."""
     import statistics
     import torch
     from paper_2403_09347_amd import binding as B
@@ -322,6 +324,9 @@ def measure_workload(w, dev, steps, warmup, detailed):
 
     inp = workloads.make_inputs(w, dev)
     Q, Ks, Vs, dO = inp["Q"], inp["K"], inp["V"], inp["dO"]
+    if zero_inputs:
+        for t in [Q, dO] + Ks + Vs:
+            t.zero_()
     k_offs = [w.k_off(j) for j in range(w.G)]
     walk = RingWalk(Q, w.scale, w.causal, w.q_off)
     dQ = torch.zeros((w.B, w.H, w.Nq, w.d), device=dev, dtype=torch.float32)
@@ -530,6 +535,15 @@ def main():
         out["cpu_baseline"] = cpu_baseline(w, inp)
     del res, walk, inp
     torch.cuda.empty_cache()
+    if not args.brief:
+        # the same steps on all-zero inputs: same instruction stream, operands that toggle no bits
+        # (how much of the step time is the power limit's, i.e. the clock the data allows)
+        r = measure_workload(w, dev, 5, 2, detailed=False, zero_inputs=True)
+        out["same_steps_on_zero_inputs"] = {"ms_per_step_median": round(r["step_ms_median"], 3),
+                                            "speedup_over_normal_inputs": round(out["ms_per_step_median"] / r["step_ms_median"], 3),
+                                            "kernels_avg_launch_ms": {k: round(r["avg"][k], 4) for k in ("fwd", "dq", "dkv")}}
+        del r
+        torch.cuda.empty_cache()
     if not args.brief and args.workload == "llama7b_32k_G8":
         # the benchmark's other configurations, a few steps each (same step definition)
         out["other_workloads"] = []

@@ -52,25 +52,35 @@ __device__ __forceinline__ void mfma32_dp_first(f32x16& acc, bf16x8 a, bf16x8& b
 __device__ __forceinline__ void mfma32_dp(f32x16& acc, bf16x8 a, bf16x8& b_resident) {
   asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %2, %1, %0" : "+v"(acc), "+a"(b_resident) : "v"(a));
 }
-// The same MFMAs with two independent vector instructions of the slice's own work placed in
-// front of them inside one asm statement: whatever register copies the compiler puts before the
-// statement are then at least two instructions away from the MFMA, and no s_nop is needed.
-// t0 = x0 * c + n, t1 = x1 * c + n (the exponents of two scores), then the dP^T MFMA.
-__device__ __forceinline__ void fma2_mfma32_dp(f32x16& acc, bf16x8 a, bf16x8& b_resident, float& t0, float& t1,
-                                               float x0, float x1, float c, float n) {
-  asm volatile("v_fma_f32 %2, %5, %7, %8\n\tv_fma_f32 %3, %6, %7, %8\n\tv_mfma_f32_32x32x16_bf16 %0, %4, %1, %0"
-               : "+v"(acc), "+a"(b_resident), "=&v"(t0), "=&v"(t1) : "v"(a), "v"(x0), "v"(x1), "s"(c), "v"(n));
+// The same MFMAs with the slice's own vector work inside the same asm statement: two independent
+// vector instructions in front (whatever register copies the compiler puts before the statement
+// are then at least two instructions away from the MFMA, and no s_nop is needed), the rest behind.
+// Nothing the compiler can see consumes a result right after the statement, so it adds no wait
+// state of its own either (after an asm statement it cannot look into it assumes the worst: a
+// transcendental result, one wait state before its first use).
+// x0 <- exp2(x0 * c + n), x1 <- exp2(x1 * c + n) in place (two scores become two probabilities), with
+// the dP^T MFMA between the multiply-adds and the exponentials.  The exponentials' results are
+// first read a phase later.
+__device__ __forceinline__ void exp2_mfma32_dp(f32x16& acc, bf16x8 a, bf16x8& b_resident, float& x0, float& x1,
+                                               float c, float n) {
+  asm volatile("v_fma_f32 %2, %2, %5, %6\n\tv_fma_f32 %3, %3, %5, %6\n\tv_mfma_f32_32x32x16_bf16 %0, %4, %1, %0\n\t"
+               "v_exp_f32 %2, %2\n\tv_exp_f32 %3, %3"
+               : "+v"(acc), "+a"(b_resident), "+v"(x0), "+v"(x1) : "v"(a), "s"(c), "v"(n));
 }
-__device__ __forceinline__ void fma2_mfma32_dp_first(f32x16& acc, bf16x8 a, bf16x8& b_resident, const f32x16& start,
-                                                     float& t0, float& t1, float x0, float x1, float c, float n) {
-  asm volatile("v_fma_f32 %2, %6, %8, %9\n\tv_fma_f32 %3, %7, %8, %9\n\tv_mfma_f32_32x32x16_bf16 %0, %4, %1, %5"
-               : "=&v"(acc), "+a"(b_resident), "=&v"(t0), "=&v"(t1) : "v"(a), "v"(start), "v"(x0), "v"(x1), "s"(c), "v"(n));
+__device__ __forceinline__ void exp2_mfma32_dp_first(f32x16& acc, bf16x8 a, bf16x8& b_resident, const f32x16& start,
+                                                     float& x0, float& x1, float c, float n) {
+  asm volatile("v_fma_f32 %2, %2, %6, %7\n\tv_fma_f32 %3, %3, %6, %7\n\tv_mfma_f32_32x32x16_bf16 %0, %4, %1, %5\n\t"
+               "v_exp_f32 %2, %2\n\tv_exp_f32 %3, %3"
+               : "=&v"(acc), "+a"(b_resident), "+v"(x0), "+v"(x1) : "v"(a), "v"(start), "s"(c), "v"(n));
 }
-// d0 = p0 * q0, d1 = p1 * q1 (two dS values), then a dQ^T MFMA on an AGPR accumulator.
-__device__ __forceinline__ void mul2_mfma32_acc(f32x16& acc, bf16x8 a, bf16x8 b, float& d0, float& d1,
-                                                float p0, float q0, float p1, float q1) {
-  asm volatile("v_mul_f32 %1, %5, %6\n\tv_mul_f32 %2, %7, %8\n\tv_mfma_f32_32x32x16_bf16 %0, %3, %4, %0"
-               : "+a"(acc), "=&v"(d0), "=&v"(d1) : "v"(a), "v"(b), "v"(p0), "v"(q0), "v"(p1), "v"(q1));
+// ds = pack_bf16(p0 * q0, p1 * q1) (two dS values), with a dQ^T MFMA on an AGPR accumulator between
+// the products and the conversion.
+__device__ __forceinline__ void ds2_mfma32_acc(f32x16& acc, bf16x8 a, bf16x8 b, unsigned& ds,
+                                               float p0, float q0, float p1, float q1) {
+  float tmp;
+  asm volatile("v_mul_f32 %1, %5, %6\n\tv_mul_f32 %2, %7, %8\n\tv_mfma_f32_32x32x16_bf16 %0, %3, %4, %0\n\t"
+               "v_cvt_pk_bf16_f32 %1, %1, %2"
+               : "+a"(acc), "=&v"(ds), "=&v"(tmp) : "v"(a), "v"(b), "v"(p0), "v"(q0), "v"(p1), "v"(q1));
 }
 __device__ __forceinline__ void mfma_vgpr_fence(f32x16 (&acc)[2]) {
   asm volatile("s_nop 15\n\ts_nop 3" : "+v"(acc[0]), "+v"(acc[1]));
@@ -362,16 +372,14 @@ burst_bwd_dq_kernel(BwdArgs a) {
         const int ks = i >> 1, rb = i & 1;
         if (rb == 0 && ks + 2 < 8) vfq[(ks + 2) % 3] = lds_read_b128(vl, abase ^ ((ks + 2) << 5));
         {
-          // the slice's MFMA with the exponents of score pair i computed right in front of it;
-          // the exponentials follow (the empty asm statement keeps them in this slice: asm
-          // statements keep their order)
+          // the slice's MFMA with the exponents of score pair i computed right in front of it and
+          // the exponentials right behind, all in one asm statement
           const int prb = i >> 3, r = 2 * (i & 7);
-          float t0, t1;
-          if (ks == 0) fma2_mfma32_dp_first(dp[rb], vfq[0], gfr[rb][0], negD[rb], t0, t1, s[prb][r], s[prb][r + 1], a.c, nlse2[prb]);
-          else fma2_mfma32_dp(dp[rb], vfq[ks % 3], gfr[rb][ks], t0, t1, s[prb][r], s[prb][r + 1], a.c, nlse2[prb]);
-          s[prb][r] = fast_exp2(t0);
-          s[prb][r + 1] = fast_exp2(t1);
-          asm volatile("" : "+v"(s[prb]));
+          float x0 = s[prb][r], x1 = s[prb][r + 1];
+          if (ks == 0) exp2_mfma32_dp_first(dp[rb], vfq[0], gfr[rb][0], negD[rb], x0, x1, a.c, nlse2[prb]);
+          else exp2_mfma32_dp(dp[rb], vfq[ks % 3], gfr[rb][ks], x0, x1, a.c, nlse2[prb]);
+          s[prb][r] = x0;
+          s[prb][r + 1] = x1;
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -380,15 +388,11 @@ burst_bwd_dq_kernel(BwdArgs a) {
       // tile kt rides along, and so do the DMA of tile kt + 3 and the first K reads of tile kt + 1
       dq_phase(kl_prev, dsp, [&](int i, f32x16& acc, bf16x8 fa, bf16x8 fb) __attribute__((always_inline)) {
         const int prb = i >> 3, r = 2 * (i & 7), kg = r >> 3, t = r & 7;
-        // the slice's MFMA with the two dS products of score pair i right in front of it; the
-        // conversion follows (the empty asm statement below keeps it in this slice)
-        float d0, d1;
-        mul2_mfma32_acc(acc, fa, fb, d0, d1, s[prb][r], dp[prb][r], s[prb][r + 1], dp[prb][r + 1]);
-        bf16x2 pk;
-        pk[0] = (bf16)d0; pk[1] = (bf16)d1;
-        unsigned pu = __builtin_bit_cast(unsigned, pk);
-        asm volatile("" : "+v"(pu));               // keep the arithmetic in this slice
-        pk = __builtin_bit_cast(bf16x2, pu);
+        // the slice's MFMA with the two dS products of score pair i right in front of it and
+        // their conversion to packed bf16 right behind, all in one asm statement
+        unsigned pu;
+        ds2_mfma32_acc(acc, fa, fb, pu, s[prb][r], dp[prb][r], s[prb][r + 1], dp[prb][r + 1]);
+        const bf16x2 pk = __builtin_bit_cast(bf16x2, pu);
         dsc[prb][kg][t] = pk[0]; dsc[prb][kg][t + 1] = pk[1];
         if ((i & 3) == 1) {
           const int j = i >> 2;                    // 0, 1 -> K of tile kt + 3; 2, 3 -> V of tile kt + 3
