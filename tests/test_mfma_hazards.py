@@ -9,9 +9,14 @@ compiler keeps by itself for its own MFMAs are kept by hand there (csrc/burst_co
   2. nothing but another MFMA may touch an accumulator of such a statement while MFMAs on it may
      still be in flight (readers go through mfma_acc_fence / mfma_vgpr_fence: `s_nop`s that
      cover the MFMA's passes).
+  3. a vector instruction written inside such a statement (the slices' own arithmetic) must not
+     read or overwrite a register that any MFMA, the compiler's included, wrote less than a drained
+     MFMA ago: the compiler waits before the instructions it schedules itself, it cannot before
+     those it does not see.
 A compiler upgrade may place register copies differently.  This test compiles the kernels to
-assembly and checks rule 1 for every MFMA inside an inline-assembly block, and rule 2 for every
-non-MFMA instruction that reads or writes a register an inline-assembly MFMA accumulates into.
+assembly and checks rule 1 for every MFMA inside an inline-assembly block, rule 2 for every
+non-MFMA instruction that reads or writes a register an inline-assembly MFMA accumulates into, and
+rule 3 for every vector instruction inside an inline-assembly block.
 """
 import os
 import re
@@ -93,7 +98,18 @@ def check_kernel(name, body):
                 if is_valu and pops and regs(pops[0]) & sources:
                     problems.append(f"{name}: instruction {i}: {pmn} {pops[0]} feeds an inline-asm MFMA {gap} wait states later")
                 gap += wait_states(pmn, pops)
-        elif not mn.startswith("v_mfma") and asm_acc:
+        if inside and mn.startswith("v_") and not mn.startswith("v_mfma"):      # rule 3
+            touched = set().union(*(regs(o) for o in ops)) if ops else set()
+            gap = 0
+            for pmn, pops, _ in reversed(body[max(0, i - 64):i]):
+                if gap >= DRAIN:
+                    break
+                if pmn.startswith("v_mfma") and regs(pops[0]) & touched:
+                    problems.append(f"{name}: instruction {i}: {mn} inside an asm statement touches "
+                                    f"{sorted(touched & regs(pops[0]))[:2]} {gap} wait states after an MFMA wrote it")
+                    break
+                gap += wait_states(pmn, pops)
+        if not mn.startswith("v_mfma") and asm_acc:
             touched = set().union(*(regs(o) for o in ops)) if ops else set()
             if touched & asm_acc:
                 gap = 0
@@ -138,5 +154,10 @@ def test_checker_finds_planted_hazards():
     assert check_kernel("k", also_ok) == (1, [])
     early_read = [mf, ("s_nop", ["15"], False), ("v_accvgpr_read_b32", ["v1", "a3"], False)]
     assert len(check_kernel("k", early_read)[1]) == 1
+    builtin = ("v_mfma_f32_32x32x16_bf16", ["v[32:47]", "v[4:7]", "v[8:11]", "v[32:47]"], False)
+    hidden_read = [builtin, ("s_nop", ["7"], False), ("v_fma_f32", ["v60", "v33", "s1", "v61"], True)]
+    assert len(check_kernel("k", hidden_read)[1]) == 1
+    late_read = [builtin] + [("s_nop", ["7"], False)] * 3 + [("v_fma_f32", ["v60", "v33", "s1", "v61"], True)]
+    assert check_kernel("k", late_read) == (0, [])
     fenced = [mf, ("s_nop", ["15"], False), ("s_nop", ["15"], False), ("v_accvgpr_read_b32", ["v1", "a3"], False)]
     assert check_kernel("k", fenced) == (1, [])
