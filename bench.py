@@ -81,8 +81,16 @@ def overlap_measurement(w, inp, source, reps):
     t_compute = timed(lambda: plain.forward(Ks, Vs, k_offs))
     t_copy = timed(lambda: db.copies_only(src_K, src_V))
     t_pipe = timed(lambda: db.forward(src_K, src_V, k_offs))
+    # the backward walk with the query slice pinned streams the same chunks through the same buffers
+    dQ = torch.zeros((w.B, w.H, w.Nq, w.d), device=Q.device, dtype=torch.float32)
+    dKs = [torch.empty(K.shape, device=Q.device, dtype=torch.float32) for K in Ks]
+    dVs = [torch.empty(K.shape, device=Q.device, dtype=torch.float32) for K in Ks]
+    t_compute_b = timed(lambda: plain.backward(Ks, Vs, k_offs, inp["dO"], dQ, dKs, dVs))
+    t_pipe_b = timed(lambda: db.backward(src_K, src_V, k_offs, inp["dO"], dQ, dKs, dVs))
     chunk_bytes = 2 * Ks[0].numel() * Ks[0].element_size()
     return {"source": source, "compute_only_ms": t_compute, "copies_only_ms": t_copy, "double_buffered_ms": t_pipe,
+            "backward_compute_only_ms": t_compute_b, "backward_double_buffered_ms": t_pipe_b,
+            "backward_compute_over_total": t_compute_b / t_pipe_b,
             "overlap_efficiency": max(t_compute, t_copy) / t_pipe,
             "compute_over_total": t_compute / t_pipe,
             # with the copies shorter than the attention, what the walk loses is what the attention

@@ -17,6 +17,22 @@ int main() {
   p.Nq = 5; p.Nc = 9; p.d = 8; p.H = 2;
   bad += burst_materialized_workspace_bytes(&p) != 768 + 512 + 2 * 256;
   bad += burst_materialized_workspace_bytes(nullptr) != 0;
+  // the entry point that allocates nothing: over its static scratch, then a missing O
+  {
+    burst_params q; std::memset(&q, 0, sizeof q);
+    q.B = 1; q.H = 32; q.Nq = BURST_STATIC_MAX_ROWS / 32 + 1; q.Nc = 64; q.d = 128; q.dtype = BURST_BF16; q.scale = 0.5f;
+    void* a = reinterpret_cast<void*>(4096);           // never dereferenced: rejected before any device call
+    float* fa = static_cast<float*>(a);
+    bad += burst_local_bwd_static(a, a, a, a, a, fa, fa, fa, fa, 1, 0, &q, nullptr) != BURST_ERR_TOO_LARGE;
+    q.Nq = 64;
+    bad += burst_local_bwd_static(a, a, a, nullptr, a, fa, fa, fa, fa, 1, 0, &q, nullptr) != BURST_ERR_NULL;
+    bad += std::strstr(burst_strerror(BURST_ERR_TOO_LARGE), "static scratch") == nullptr;
+  }
+  // the measurement probes reject bad arguments on the host
+  bad += burst_probe_mfma(3, 1, &p, reinterpret_cast<float*>(&p), 1, nullptr) != BURST_ERR_SHAPE;
+  bad += burst_probe_mfma(0, 1, nullptr, nullptr, 1, nullptr) != BURST_ERR_NULL;
+  bad += burst_probe_atomic_dq(reinterpret_cast<float*>(&p), 7, 64, 1, 1, nullptr) != BURST_ERR_SHAPE;
+  bad += burst_workspace_bytes(&p) != (size_t)1 * 2 * 5 * 4;
   bad += std::strcmp(burst_strerror(0), "ok") != 0;
   bad += burst_version() < 100;
   std::printf("host checks failed: %d\n", bad);
