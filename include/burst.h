@@ -262,15 +262,15 @@ void  burst_event_destroy(void* event);
  * reads), 2 = of every second MFMA.  operands: 64 KiB of bf16 values on the device (their contents
  * set how many bits toggle, and with that the clock the chip sustains); sink: 256 * 512 floats,
  * written.  The caller times the launch.
- * burst_probe_atomic_dq: the atomic traffic of a backward that would compute a block pair once,
- * keys stationary, and add its dQ partial sums with fp32 atomics: heads * key_blocks workgroups
+ * burst_probe_atomic_dq: the memory traffic of a backward that would compute a block pair once,
+ * keys stationary, and get its dQ partial sums out of the workgroups: heads * key_blocks workgroups
  * (heads a multiple of 8), each adding one [64][128] tile per 64 query rows into dQ [heads][Nq][128]
- * (Nq a multiple of 64); atomic = 0 writes plain stores in the same pattern, atomic = 2 plain
- * load-add-store (racing, timing only), for comparison.  No arithmetic: a lower bound on what such a
- * kernel would take. */
+ * (Nq a multiple of 64).  mode 1: fp32 atomic adds; mode 0: plain stores in the same pattern; mode 2:
+ * plain load-add-store in the same pattern (racing: timing only).  No arithmetic: a lower bound on
+ * what such a kernel would take. */
 int burst_probe_mfma(int a_from_lds, int wavefronts_per_simd, const void* operands, float* sink, int iters,
                      void* stream);
-int burst_probe_atomic_dq(float* dQ, int heads, int Nq, int key_blocks, int atomic, void* stream);
+int burst_probe_atomic_dq(float* dQ, int heads, int Nq, int key_blocks, int mode, void* stream);
 
 const char* burst_strerror(int status);
 int         burst_version(void);

@@ -222,14 +222,15 @@ def burst_probe_mfma(a_from_lds, wavefronts_per_simd, operands, sink, iters):
                                 _stream()), "burst_probe_mfma")
 
 
-def burst_probe_atomic_dq(dQ, heads, Nq, key_blocks, atomic):
+def burst_probe_atomic_dq(dQ, heads, Nq, key_blocks, mode):
+    """mode: 1 = fp32 atomic adds, 0 = plain stores, 2 = plain load-add-store (see burst.h)."""
     lib = load()
     lib.burst_probe_atomic_dq.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                           ctypes.c_void_p]
     lib.burst_probe_atomic_dq.restype = ctypes.c_int
     if dQ.numel() < heads * Nq * 128:
         raise ValueError("burst_probe_atomic_dq: dQ too small")
-    _check(lib.burst_probe_atomic_dq(_f32(dQ), int(heads), int(Nq), int(key_blocks), int(atomic), _stream()),
+    _check(lib.burst_probe_atomic_dq(_f32(dQ), int(heads), int(Nq), int(key_blocks), int(mode), _stream()),
            "burst_probe_atomic_dq")
 
 

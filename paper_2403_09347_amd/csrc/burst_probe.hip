@@ -107,15 +107,15 @@ int burst_probe_mfma(int a_from_lds, int wavefronts_per_simd, const void* operan
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
 
-int burst_probe_atomic_dq(float* dQ, int heads, int Nq, int key_blocks, int atomic, void* stream) {
+int burst_probe_atomic_dq(float* dQ, int heads, int Nq, int key_blocks, int mode, void* stream) {
   using namespace burst;
   if (dQ == nullptr) return BURST_ERR_NULL;
   if (heads < 8 || heads % 8 != 0 || heads > 4096 || Nq < 64 || Nq % 64 != 0 || Nq > (1 << 20) || key_blocks < 1 ||
-      key_blocks > 4096) return BURST_ERR_SHAPE;
+      key_blocks > 4096 || mode < 0 || mode > 2) return BURST_ERR_SHAPE;
   const dim3 grid((unsigned)(heads * key_blocks)), block(256);
   hipStream_t s = (hipStream_t)stream;
-  if (atomic == 1) hipLaunchKernelGGL(probe_atomic_dq_kernel<1>, grid, block, 0, s, dQ, Nq, key_blocks);
-  else if (atomic == 2) hipLaunchKernelGGL(probe_atomic_dq_kernel<2>, grid, block, 0, s, dQ, Nq, key_blocks);
+  if (mode == 1) hipLaunchKernelGGL(probe_atomic_dq_kernel<1>, grid, block, 0, s, dQ, Nq, key_blocks);
+  else if (mode == 2) hipLaunchKernelGGL(probe_atomic_dq_kernel<2>, grid, block, 0, s, dQ, Nq, key_blocks);
   else hipLaunchKernelGGL(probe_atomic_dq_kernel<0>, grid, block, 0, s, dQ, Nq, key_blocks);
   return hipGetLastError() == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
 }
