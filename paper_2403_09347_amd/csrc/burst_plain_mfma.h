@@ -631,10 +631,22 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
         f32x16 s, dp;
 #pragma unroll
         for (int r = 0; r < 16; r++) { s[r] = 0.f; dp[r] = 0.f; }
+        if constexpr (SK_WAVES == 2) {
+          // One wavefront per SIMD: nobody else hides an LDS read's latency, and left alone the
+          // compiler reads one fragment, waits, multiplies, sixteen times over.  All sixteen
+          // fragments are requested first (the registers are there), then the MFMAs run.
+          bf16x8 qa[S_KS], ga[S_KS];
 #pragma unroll
-        for (int ks = 0; ks < S_KS; ks++) {
-          s = mfma32(lds_read_b128(ql, qaddr[ks]), kf[ks], s);
-          dp = mfma32(lds_read_b128(gl, qaddr[ks]), vf[ks], dp);
+          for (int ks = 0; ks < S_KS; ks++) { qa[ks] = lds_read_b128(ql, qaddr[ks]); ga[ks] = lds_read_b128(gl, qaddr[ks]); }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int ks = 0; ks < S_KS; ks++) { s = mfma32(qa[ks], kf[ks], s); dp = mfma32(ga[ks], vf[ks], dp); }
+        } else {
+#pragma unroll
+          for (int ks = 0; ks < S_KS; ks++) {
+            s = mfma32(lds_read_b128(ql, qaddr[ks]), kf[ks], s);
+            dp = mfma32(lds_read_b128(gl, qaddr[ks]), vf[ks], dp);
+          }
         }
         const long long tile_first_q = a.q_off + (long long)t * SK_BR;
         const bool need_mask = (a.causal && wave_last_k > tile_first_q) ||
@@ -651,6 +663,21 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
             const int cpart = 8 * (r >> 2) + (r & 3);
             if (!(cpart >= lim && cpart <= lim2)) s[r] = BURST_NEG_INF;
           }
+        }
+        // (two wavefronts per workgroup: the transposed dO and Q fragments of the last phase are
+        // requested here, so that they arrive while the exponentials run)
+        bf16x4 tg[2][S_DB][2], tq[2][S_DB][2];
+        if constexpr (SK_WAVES == 2) {
+#pragma unroll
+          for (int u = 0; u < 2; u++)
+#pragma unroll
+            for (int db = 0; db < S_DB; db++)
+#pragma unroll
+              for (int sx = 0; sx < 2; sx++) {
+                tg[u][db][sx] = lds_read_tr(gl, u * 16 * S_ROWB + taddr[db][sx]);
+                tq[u][db][sx] = lds_read_tr(ql, u * 16 * S_ROWB + taddr[db][sx]);
+              }
+          __builtin_amdgcn_sched_barrier(0);
         }
         bf16x8 pf[2], dsf[2];                        // per 16-row group: A operands of dV, dK
 #pragma unroll
@@ -670,8 +697,14 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
         for (int u = 0; u < 2; u++)
 #pragma unroll
           for (int db = 0; db < S_DB; db++) {
-            const bf16x8 bg = cat4(lds_read_tr(gl, u * 16 * S_ROWB + taddr[db][0]), lds_read_tr(gl, u * 16 * S_ROWB + taddr[db][1]));
-            const bf16x8 bq = cat4(lds_read_tr(ql, u * 16 * S_ROWB + taddr[db][0]), lds_read_tr(ql, u * 16 * S_ROWB + taddr[db][1]));
+            bf16x8 bg, bq;
+            if constexpr (SK_WAVES == 2) {
+              bg = cat4(tg[u][db][0], tg[u][db][1]);
+              bq = cat4(tq[u][db][0], tq[u][db][1]);
+            } else {
+              bg = cat4(lds_read_tr(gl, u * 16 * S_ROWB + taddr[db][0]), lds_read_tr(gl, u * 16 * S_ROWB + taddr[db][1]));
+              bq = cat4(lds_read_tr(ql, u * 16 * S_ROWB + taddr[db][0]), lds_read_tr(ql, u * 16 * S_ROWB + taddr[db][1]));
+            }
             dv[db] = mfma32(pf[u], bg, dv[db]);
             dk[db] = mfma32(dsf[u], bq, dk[db]);
           }
