@@ -555,8 +555,13 @@ burst_bwd_dkv_d64_kernel(BwdArgs a) {
       const int e = __builtin_amdgcn_readfirstlane(s_list[1 + j]);
       n = e & 0xfffff; bits = e >> 20;
     }
-    g = n / per_head;
-    t = t_begin + (n - g * per_head);
+    if (a.group == 1) {                            // (no division in the common case: a scalar divide is some forty instructions)
+      g = 0;
+      t = t_begin + n;
+    } else {
+      g = n / per_head;
+      t = t_begin + (n - g * per_head);
+    }
     return bits;
   };
 
