@@ -225,7 +225,6 @@ int validated(F&& enqueue) {
   return e != BURST_OK ? e : enqueue();
 }
 
-// Caller holds g_bwd_mutex.
 // The dK/dV call of a d = 128 block pair goes to the plain kernel with 64-key workgroups when the
 // call's flags have 64-wide blocks (its time then follows the density; the hand-scheduled kernel's
 // 128-key workgroups cannot skip what only half of their keys need), or when the plain family is
@@ -239,6 +238,7 @@ bool use_plain128_dkv(const burst_params* p, const KParams& k) {
   return flags && p->block < 128;
 }
 
+// Caller holds g_bwd_mutex.
 int get_d_scratch(hipStream_t stream, size_t elems, float** out) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return BURST_ERR_ALLOC;
