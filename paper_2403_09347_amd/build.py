@@ -33,7 +33,24 @@ def build(verbose=True, jobs=8):
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
+    build_example(verbose)
     return LIB
+
+
+EXAMPLE_SRC = os.path.join(HERE, "examples", "ring_walk.cpp")
+EXAMPLE_BIN = os.path.join(HERE, "_build", "ring_walk")
+
+
+def build_example(verbose=True):
+    """The plain host program that walks a ring share through the C ABI (no Python on its path),
+    linked against the library just built; run by tests/test_gpu_c_example.py."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-O2", "-std=c++17", "--offload-arch=gfx950", "-I", os.path.join(os.path.dirname(HERE), "include"),
+           EXAMPLE_SRC, "-L", HERE, "-lburst", "-Wl,-rpath,$ORIGIN/..", "-o", EXAMPLE_BIN]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return EXAMPLE_BIN
 
 
 def _drain(procs, verbose):
