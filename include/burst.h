@@ -235,9 +235,10 @@ int burst_local_bwd_materialized(const void* Q, const void* K_chunk, const void*
 
 /* For tests and tuning (no counterpart in the paper): which of the two kernel families serves
  * bf16, d = 128 calls.  0 = chosen per call (the default): forward and dQ from how well the call's
- * workgroups fill the chip and from the flags' block edge, dK/dV plain only for 64-wide block
- * flags; 1 = always the hand-scheduled kernels (256 query rows, 128 keys per workgroup); 2 = always
- * the plainly written ones (128 rows, 64 keys per workgroup).  Process-wide; results of the two
+ * workgroups fill the chip and from the flags' block edge, dK/dV always hand-scheduled, with 64
+ * instead of 128 keys per workgroup for 64-wide block flags; 1 = always the hand-scheduled kernels
+ * (256 query rows, 128 keys per workgroup); 2 = always the plainly written ones (128 rows, 64 keys
+ * per workgroup).  Process-wide; results of the two
  * families agree within the tolerance, not bitwise.  Returns BURST_ERR_SHAPE for another value. */
 int burst_set_kernel_family(int family);
 /* Which family would serve burst_local_fwd / the dQ half of burst_local_bwd for these parameters

@@ -18,7 +18,7 @@ int launch_fwd_generic(const KParams&, int, const void*, const void*, const void
 int launch_bwd_dq_mfma(const KParams&, const void*, const void*, const void*, const void*, const float*,
                        const float*, float*, int, hipStream_t);
 int launch_bwd_dkv_mfma(const KParams&, const void*, const void*, const void*, const void*, const float*,
-                        const float*, float*, float*, int, hipStream_t);
+                        const float*, float*, float*, int, hipStream_t, int key_waves);
 int launch_bwd_dq_generic(const KParams&, int, const void*, const void*, const void*, const void*, const float*,
                           const float*, float*, int, hipStream_t);
 int launch_bwd_dkv_generic(const KParams&, int, const void*, const void*, const void*, const void*, const float*,
@@ -225,17 +225,22 @@ int validated(F&& enqueue) {
   return e != BURST_OK ? e : enqueue();
 }
 
-// The dK/dV call of a d = 128 block pair goes to the plain kernel with 64-key workgroups when the
-// call's flags have 64-wide blocks (its time then follows the density; the hand-scheduled kernel's
-// 128-key workgroups cannot skip what only half of their keys need), or when the plain family is
-// forced.  Its tile lists hold 4096 entries of 32 query rows (all heads of a group).
+// Block flags narrower than the 128 keys of a dK/dV workgroup: the hand-scheduled kernel runs in
+// its shape with 64-key workgroups, whose tile lists hold what 64 keys need (its time then
+// follows the density; a 128-key workgroup cannot skip what only half of its keys need).  Those
+// lists hold 2048 entries of 64 query rows (all heads of a group).
+int dkv_key_waves(const burst_params* p, const KParams& k) {
+  if (p->block_mask == nullptr || p->block >= 128) return 4;
+  if ((long long)k.group * ((p->Nq + 63) / 64) > 2048) return 4;
+  return g_kernel_family.load(std::memory_order_relaxed) == 0 ? 2 : 4;
+}
+// The plainly written dK/dV kernel with 64-key workgroups runs when the plain family is forced.
+// Its tile lists hold 4096 entries of 32 query rows (all heads of a group).
 bool use_plain128_dkv(const burst_params* p, const KParams& k) {
   if (!use_mfma(p, k)) return false;
   const bool flags = p->block_mask != nullptr;
   if (flags && (long long)k.group * ((p->Nq + 31) / 32) > 4096) return false;
-  const int family = g_kernel_family.load(std::memory_order_relaxed);
-  if (family != 0) return family == 2;
-  return flags && p->block < 128;
+  return g_kernel_family.load(std::memory_order_relaxed) == 2;
 }
 
 // Caller holds g_bwd_mutex.
@@ -460,7 +465,8 @@ static int local_bwd_impl(int which, const void* Q, const void* K_chunk, const v
     if (want_dkv) {
       e = d64 ? burst::d64::launch_bwd_dkv(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk, adkv, s)
         : plain128_dkv ? burst::d128p::launch_bwd_dkv(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk, adkv, s)
-        : mfma_dkv ? burst::launch_bwd_dkv_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk, adkv, s)
+        : mfma_dkv ? burst::launch_bwd_dkv_mfma(k, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk, dV_chunk, adkv, s,
+                                                dkv_key_waves(p, k))
                    : burst::launch_bwd_dkv_generic(k, p->dtype, Q, K_chunk, V_chunk, dO, lse, Duse, dK_chunk,
                                                    dV_chunk, adkv, s);
       if (e != BURST_OK) return e;

@@ -18,23 +18,36 @@
 //   1: S, dP of block 0            2: S, dP of block 1   + P, dS of block 0
 //   3: dV, dK of block 0 + P, dS of block 1              4: dV, dK of block 1 + DMA of tile t+2
 // No atomics: every key row is owned by one wavefront, results are bitwise reproducible.
+//
+// A second shape of the same kernel has 2 wavefronts = 64 keys per workgroup and two workgroups
+// per CU (NW = 2), for block flags 64 keys wide (paper Sec. 2.6): a workgroup's tile list then
+// holds what its own 64 keys need and nothing else, which the 128-key shape cannot offer (a tile
+// that half of its keys need costs the full time).  Two workgroups share the CU's LDS, so the
+// tile ring has two slots instead of three and a tile is fetched one step ahead instead of two.
 #include "burst_bwd_common.h"
 
 namespace burst {
 
-constexpr int DKV_BC = 128;           // keys per workgroup (4 wavefronts x 32)
 constexpr int DKV_BR = 64;            // query rows per tile
 constexpr int DKV_TILE_BYTES = DKV_BR * 256;
-constexpr int DKV_SLOTS = 3;
-constexpr int DKV_LDS_Q = 0;
-constexpr int DKV_LDS_G = DKV_SLOTS * DKV_TILE_BYTES;
 constexpr int DKV_STAT_SLOTS = 4;     // row statistics run one tile further ahead than the tiles
-constexpr int DKV_LDS_L = 2 * DKV_SLOTS * DKV_TILE_BYTES;              // -lse / scale per row
-constexpr int DKV_LDS_D = DKV_LDS_L + DKV_STAT_SLOTS * DKV_BR * 4;     // -D per row
-constexpr int DKV_LDS_DUMMY = DKV_LDS_D + DKV_STAT_SLOTS * DKV_BR * 4; // sink of the padding DMA (256 B)
-constexpr int DKV_LDS_BYTES = DKV_LDS_DUMMY + 256;
-constexpr int DKV_MAX_LIST = 8192;    // block-sparse calls: most query tiles of one slice (512K rows)
-constexpr int DKV_LIST_BYTES = (DKV_MAX_LIST + 8) * 4;
+// Sizes and LDS layout for NW wavefronts per workgroup.
+template <int NW>
+struct DkvShape {
+  static constexpr int BC = 32 * NW;                 // keys per workgroup
+  static constexpr int SLOTS = NW == 4 ? 3 : 2;      // tile ring
+  static constexpr int LPW = 16 / NW;                // DMA wave-loads per tensor and tile that a wavefront issues
+  static constexpr int LDS_Q = 0;
+  static constexpr int LDS_G = SLOTS * DKV_TILE_BYTES;
+  static constexpr int LDS_L = 2 * SLOTS * DKV_TILE_BYTES;             // -lse / scale per row
+  static constexpr int LDS_D = LDS_L + DKV_STAT_SLOTS * DKV_BR * 4;    // -D per row
+  static constexpr int LDS_DUMMY = LDS_D + DKV_STAT_SLOTS * DKV_BR * 4;  // sink of the padding DMA (256 B)
+  static constexpr int LDS_BYTES = LDS_DUMMY + 256;
+  // block-sparse calls: most query tiles of one slice (512K rows; 128K rows where two workgroups
+  // share the LDS)
+  static constexpr int MAX_LIST = NW == 4 ? 8192 : 2048;
+  static constexpr int LIST_BYTES = (MAX_LIST + 8) * 4;
+};
 
 // SPARSE: the call carries block flags (paper Sec. 2.6) or several query heads share a key/value
 // head (a.group > 1: the tiles of all heads of the group are walked, `head` is then the key/value
@@ -44,9 +57,13 @@ constexpr int DKV_LIST_BYTES = (DKV_MAX_LIST + 8) * 4;
 // wavefront) into LDS and then walks that list instead of t_begin, t_begin + 1, ...; a wavefront
 // whose bit is clear hides the whole tile in the masking path.  Entries past the end name a tile
 // beyond the slice: its Q, dO and statistics read as zeros and contribute nothing.
-template <bool SPARSE>
-__global__ void __launch_bounds__(256, 1)
+template <bool SPARSE, int NW>
+__global__ void __launch_bounds__(64 * NW, 1)
 burst_bwd_dkv_kernel(BwdArgs a) {
+  using Shape = DkvShape<NW>;
+  constexpr int DKV_BC = Shape::BC, DKV_SLOTS = Shape::SLOTS, LPW = Shape::LPW;
+  constexpr int DKV_LDS_Q = Shape::LDS_Q, DKV_LDS_G = Shape::LDS_G, DKV_LDS_L = Shape::LDS_L, DKV_LDS_D = Shape::LDS_D;
+  constexpr int DKV_LDS_DUMMY = Shape::LDS_DUMMY, DKV_LDS_BYTES = Shape::LDS_BYTES;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int tid = threadIdx.x;
   const int w = tid >> 6, lane = tid & 63, lr = lane & 31, h = lane >> 5;
@@ -91,6 +108,20 @@ burst_bwd_dkv_kernel(BwdArgs a) {
 #pragma unroll
     for (int r = 0; r < 16; r++) { dk[db][r] = 0.f; dv[db][r] = 0.f; }
 
+  // K, V fragments (B operands: lane = key lr, 8 consecutive d), requested before the tile list is
+  // built so that the two latencies overlap
+  bf16x8 kf[8], vf[8];
+  {
+    const int key = key0 + lr;
+#pragma unroll
+    for (int ks = 0; ks < 8; ks++) {
+      bf16x8 z;
+#pragma unroll
+      for (int t = 0; t < 8; t++) z[t] = (bf16)0.0f;
+      kf[ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Kh + (size_t)key * a.lay.ks_r + ks * 16 + h * 8) : z;
+      vf[ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Vh + (size_t)key * a.lay.ks_r + ks * 16 + h * 8) : z;
+    }
+  }
   int nwalk = ntiles_all - t_begin;                // tiles to walk
   // SPARSE: the list of visible tiles, built by wavefront 0 (64 candidate tiles per round).
   // list[0] = number of entries, list[1 + j] = tile | (wavefront bits << 16), then 4 end entries.
@@ -106,11 +137,11 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           int bits = 0;
           if (t < ntiles_all) {
             if (a.bmask == nullptr) {
-              bits = 0xf;
+              bits = (1 << NW) - 1;
             } else {
               const uint8_t* mrow = a.bmask + (size_t)(head * group + g) * a.bhstride + (size_t)((t * DKV_BR) / a.bsize) * a.bpitch;
 #pragma unroll
-              for (int ww = 0; ww < 4; ww++) {
+              for (int ww = 0; ww < NW; ww++) {
                 const int k0 = key_wg + ww * 32;
                 if (k0 < a.Nc && mrow[k0 / a.bsize] != 0) bits |= 1 << ww;
               }
@@ -141,19 +172,6 @@ burst_bwd_dkv_kernel(BwdArgs a) {
   };
 
   if (nwalk > 0) {
-    // K, V fragments (B operands: lane = key lr, 8 consecutive d)
-    bf16x8 kf[8], vf[8];
-    {
-      const int key = key0 + lr;
-#pragma unroll
-      for (int ks = 0; ks < 8; ks++) {
-        bf16x8 z;
-#pragma unroll
-        for (int t = 0; t < 8; t++) z[t] = (bf16)0.0f;
-        kf[ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Kh + (size_t)key * a.lay.ks_r + ks * 16 + h * 8) : z;
-        vf[ks] = key < a.Nc ? *reinterpret_cast<const bf16x8*>(Vh + (size_t)key * a.lay.ks_r + ks * 16 + h * 8) : z;
-      }
-    }
     // LDS addressing inside a 64-row tile.  A operands (128-bit): row rb*32 + lr, granule
     // 2*ks + h -> rb*8192 + (abase ^ (ks << 5)).  B operands through transposing reads:
     // rows = query rows rb*32 + u*16 + ..., cols = d.
@@ -167,7 +185,7 @@ burst_bwd_dkv_kernel(BwdArgs a) {
         for (int sx = 0; sx < 2; sx++)
           taddr[db][sx] = tile_off(8 * sx + 4 * h + (j16 >> 2), db * 4 + 2 * dh + ((j16 & 3) >> 1)) + (j16 & 1) * 8;
     }
-    // DMA: a 64-row tile is 16 wave-loads of 4 rows; wavefront w issues loads 4w .. 4w+3
+    // DMA: a 64-row tile is 16 wave-loads of 4 rows; wavefront w issues loads LPW*w .. LPW*w + LPW-1
     // (the rows of the group's heads lie (head stride) apart: a tile of head g of the group starts
     // g * gfix bytes away from where it would in one tensor of group * Nq rows)
     const unsigned hbytes = (unsigned)a.lay.qs_h * 2u;
@@ -177,17 +195,17 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     const __amdgpu_buffer_rsrc_t grs = make_rsrc(Gh, qbytes);
     const int wu = __builtin_amdgcn_readfirstlane(w);
     const unsigned lds0 = lds_addr(smem);
-    int goff[4];
+    int goff[LPW];
 #pragma unroll
-    for (int il = 0; il < 4; il++) {
-      int row = 16 * w + 4 * il + (lane >> 4);
+    for (int il = 0; il < LPW; il++) {
+      int row = 4 * LPW * w + 4 * il + (lane >> 4);
       goff[il] = (int)(row * qpitch + (((lane & 15) ^ row_code(row)) << 4));
     }
     // `e`: an entry (see entry_at)
     auto dma_tile = [&](__amdgpu_buffer_rsrc_t rs, unsigned lds_tile, int il, int e) __attribute__((always_inline)) {
       unsigned tile = (unsigned)tile_of(e) * qtile;
       if constexpr (SPARSE) tile += (unsigned)((e >> 20) & 0xff) * gfix;
-      dma_b128_to_lds(rs, lds_tile + (unsigned)(wu * 4 + il) * 1024u, (int)tile + goff[il]);
+      dma_b128_to_lds(rs, lds_tile + (unsigned)(wu * LPW + il) * 1024u, (int)tile + goff[il]);
     };
     // Per-row statistics of a tile travel like the tiles: wavefront 0 DMAs the 64 lse values,
     // wavefront 1 the 64 D values (rows past Nq read as 0; their Q and dO rows are 0 too, so they
@@ -233,13 +251,14 @@ burst_bwd_dkv_kernel(BwdArgs a) {
       }
     };
 
-    // ---- prologue: tiles t_begin, t_begin + 1 into tile slots 0, 1; the statistics of tiles
-    // t_begin .. t_begin + 2 into statistic slots 0 .. 2, the first two scaled right away
+    // ---- prologue: tiles t_begin, t_begin + 1 into tile slots 0, 1 (two slots: the first tile
+    // alone); the statistics of tiles t_begin .. t_begin + 2 into statistic slots 0 .. 2, the
+    // first two scaled right away
 #pragma unroll
-    for (int t = 0; t < 2; t++) {
+    for (int t = 0; t < DKV_SLOTS - 1; t++) {
       const int src = entry_at(t);
 #pragma unroll
-      for (int il = 0; il < 4; il++) {
+      for (int il = 0; il < LPW; il++) {
         dma_tile(qrs, lds0 + DKV_LDS_Q + t * DKV_TILE_BYTES, il, src);
         dma_tile(grs, lds0 + DKV_LDS_G + t * DKV_TILE_BYTES, il, src);
       }
@@ -279,18 +298,19 @@ burst_bwd_dkv_kernel(BwdArgs a) {
     int slot = 0;
     for (int n = 0; n < nwalk; n++) {                  // n = walk position; statistic slot n & 3 holds its tile
       // this tile, the entry of the tile whose rows are fetched now, the tile whose statistics are
-      int t = t_begin + n, t2 = t + 2, t3 = t + 3, t_in_head = t;
+      int t = t_begin + n, t2 = t + DKV_SLOTS - 1, t3 = t + 3, t_in_head = t;
       bool mine = true;                                // SPARSE: this wavefront's keys are visible to the tile
       if constexpr (SPARSE) {
         const int e = __builtin_amdgcn_readfirstlane(list[1 + n]);
         t = e & 0xffff;
         t_in_head = t - ((e >> 20) & 0xff) * tiles_per_head;
         mine = ((e >> (16 + wu)) & 1) != 0;
-        t2 = entry_at(n + 2);
+        t2 = entry_at(n + DKV_SLOTS - 1);
         t3 = tile_of(entry_at(n + 3));
       }
       const int slot1 = (slot == DKV_SLOTS - 1) ? 0 : slot + 1;
-      const int slot2 = (slot1 == DKV_SLOTS - 1) ? 0 : slot1 + 1;
+      // where the tile fetched in this step goes: the slot after the next tile's, or (two slots) the next tile's
+      const int slot2 = DKV_SLOTS == 2 ? slot1 : (slot1 == DKV_SLOTS - 1) ? 0 : slot1 + 1;
       const char* ql = smem + DKV_LDS_Q + slot * DKV_TILE_BYTES;
       const char* gl = smem + DKV_LDS_G + slot * DKV_TILE_BYTES;
       const float* lp = reinterpret_cast<const float*>(smem + DKV_LDS_L) + (n & 3) * DKV_BR;
@@ -375,6 +395,15 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           if (i + LEAD < 32) issue_read(i + LEAD);
           if (i + TLEAD >= 32) issue_tread(i + TLEAD - 32);
           if (i == 2) load_init(1, lp, dp_);
+          if constexpr (DKV_SLOTS == 2) {
+            // two slots: the slot of tile t - 1 is free since the last barrier; tile t + 1 and the
+            // statistics of tile t + 3 are requested here and awaited at the end of the step
+            if (i == 0) dma_rowstat(t3, (n + 3) & 3);
+            if (i < 2 * LPW) {
+              if (i & 1) dma_tile(grs, lds0 + DKV_LDS_G + slot2 * DKV_TILE_BYTES, i >> 1, t2);
+              else dma_tile(qrs, lds0 + DKV_LDS_Q + slot2 * DKV_TILE_BYTES, i >> 1, t2);
+            }
+          }
           if (isg) dp[rb] = mfma32(fq[i % RING], vf[ks], dp[rb]);
           else s[rb] = mfma32(fq[i % RING], kf[ks], s[rb]);
           if (i >= 16) { if (i & 1) pds_half1(0, (i - 16) >> 1); else pds_half0(0, (i - 16) >> 1); }
@@ -391,12 +420,13 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           // the loads of the previous step (tile t + 1, statistics of tile t + 2) are most of a
           // step old: wait for them here, before this step's loads are issued, and rewrite those
           // statistics (fetch now, store a few slices later)
-          if (i == 12) { __builtin_amdgcn_s_waitcnt(0x0F70); rowstat_fetch((n + 2) & 3); }
+          // (two slots: they were awaited at the end of the previous step)
+          if (i == 12) { if constexpr (DKV_SLOTS == 3) __builtin_amdgcn_s_waitcnt(0x0F70); rowstat_fetch((n + 2) & 3); }
           if (i == 22) rowstat_store((n + 2) & 3);
           // phase 4 has no vector work: the DMA of tile t + 2 (into the slot of tile t - 1, free
           // since the last barrier) and of the statistics of tile t + 3 is issued here
-          if (i == 16) dma_rowstat(t3, (n + 3) & 3);
-          if (i > 16 && (i & 1)) {
+          if (DKV_SLOTS == 3 && i == 16) dma_rowstat(t3, (n + 3) & 3);
+          if (DKV_SLOTS == 3 && i > 16 && (i & 1)) {
             const int j = (i - 17) >> 1;                  // 0..7: Q rows, then dO rows
             if (j < 4) dma_tile(qrs, lds0 + DKV_LDS_Q + slot2 * DKV_TILE_BYTES, j, t2);
             else dma_tile(grs, lds0 + DKV_LDS_G + slot2 * DKV_TILE_BYTES, j - 4, t2);
@@ -408,10 +438,12 @@ burst_bwd_dkv_kernel(BwdArgs a) {
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-      // ---- the 9 loads of this step stay in flight across the barrier; the LDS stores of the
-      // rewritten statistics must be done
+      // ---- three slots: the 9 loads of this step stay in flight across the barrier; two: the 17
+      // loads, issued most of a step ago, must have landed.  The LDS stores of the rewritten
+      // statistics must be done.
       slot = slot1;
-      __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
+      if constexpr (DKV_SLOTS == 3) __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0)
+      else __builtin_amdgcn_s_waitcnt(0x0070);                                   // vmcnt(0), lgkmcnt(0)
       __builtin_amdgcn_s_barrier();
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): no DMA may outlive the loop
@@ -440,30 +472,42 @@ burst_bwd_dkv_kernel(BwdArgs a) {
   }
 }
 
+// key_waves: 4 (128-key workgroups) or 2 (64-key workgroups, calls with block flags only).
 int launch_bwd_dkv_mfma(const KParams& p, const void* Q, const void* K, const void* V,
                         const void* dO, const float* lse, const float* D, float* dK, float* dV,
-                        int acc_dkv, hipStream_t stream) {
+                        int acc_dkv, hipStream_t stream, int key_waves) {
   if (p.Nc <= 0) return BURST_OK;
   static DeviceOnce lds_opt_in;
   const int st = lds_opt_in.run([] {
-    return hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               DKV_LDS_BYTES) == hipSuccess &&
-           hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               DKV_LDS_BYTES + DKV_LIST_BYTES) == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
+    return hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel<false, 4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               DkvShape<4>::LDS_BYTES) == hipSuccess &&
+           hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel<true, 4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               DkvShape<4>::LDS_BYTES + DkvShape<4>::LIST_BYTES) == hipSuccess &&
+           hipFuncSetAttribute((const void*)burst_bwd_dkv_kernel<true, 2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               DkvShape<2>::LDS_BYTES + DkvShape<2>::LIST_BYTES) == hipSuccess ? BURST_OK : BURST_ERR_LAUNCH;
   });
   if (st != BURST_OK) return st;
   BwdArgs a = make_bwd_args(p, Q, K, V, dO, lse, D, nullptr, dK, dV, 0, acc_dkv);
   a.H = p.B * p.H / p.group;                       // workgroups are laid out over key/value heads
   int heads8 = ((a.H + 7) / 8) * 8;
-  a.blocks_per_head = (p.Nc + DKV_BC - 1) / DKV_BC;
+  const bool listed = a.bmask != nullptr || a.group > 1;
+  if (key_waves != 4 && !(key_waves == 2 && listed)) return BURST_ERR_SHAPE;
+  const int bc = 32 * key_waves;
+  a.blocks_per_head = (p.Nc + bc - 1) / bc;
   long long nb = (long long)heads8 * a.blocks_per_head;
   if (nb > 0x7fffffffLL) return BURST_ERR_SHAPE;
-  if (a.bmask != nullptr || a.group > 1) {
-    if ((long long)a.group * ((p.Nq + DKV_BR - 1) / DKV_BR) > DKV_MAX_LIST) return BURST_ERR_SHAPE;
+  if (listed) {
+    const int max_list = key_waves == 4 ? DkvShape<4>::MAX_LIST : DkvShape<2>::MAX_LIST;
+    if ((long long)a.group * ((p.Nq + DKV_BR - 1) / DKV_BR) > max_list) return BURST_ERR_SHAPE;
     if (a.group > 1 && p.Nq % DKV_BR != 0) return BURST_ERR_SHAPE;
-    BURST_LAUNCH(burst_bwd_dkv_kernel<true>, dim3((unsigned)nb), dim3(256), DKV_LDS_BYTES + DKV_LIST_BYTES, stream, a);
+    if (key_waves == 4)
+      BURST_LAUNCH((burst_bwd_dkv_kernel<true, 4>), dim3((unsigned)nb), dim3(256),
+                   DkvShape<4>::LDS_BYTES + DkvShape<4>::LIST_BYTES, stream, a);
+    else
+      BURST_LAUNCH((burst_bwd_dkv_kernel<true, 2>), dim3((unsigned)nb), dim3(128),
+                   DkvShape<2>::LDS_BYTES + DkvShape<2>::LIST_BYTES, stream, a);
   } else {
-    BURST_LAUNCH(burst_bwd_dkv_kernel<false>, dim3((unsigned)nb), dim3(256), DKV_LDS_BYTES, stream, a);
+    BURST_LAUNCH((burst_bwd_dkv_kernel<false, 4>), dim3((unsigned)nb), dim3(256), DkvShape<4>::LDS_BYTES, stream, a);
   }
   return launch_status();
 }

@@ -316,3 +316,18 @@ def test_slices_and_chunks_around_the_largest_size_the_tiled_kernels_take(long_s
     # dK, dV of the long-query cases sum 4 Mi rows into 40 / 64 keys and reach the hundreds: they are
     # held to 1e-2 of the largest reference entry, not to the absolute 2e-2 (see gpu_util.check)
     compare_all_heads(case, "bf16", O, lse, dQ, dKs, dVs, dkv_kind="abs" if long_side == "keys" else "rel")
+
+
+@pytest.mark.parametrize("tiles", [2048, 2049])
+def test_narrow_block_flags_around_the_longest_tile_list_of_the_64_key_workgroups(tiles):
+    """64-wide block flags (Sec. 2.6): the dK/dV half runs with 64-key workgroups whose tile lists
+    hold 2048 query tiles of 64 rows; one tile more and the call goes to the 128-key workgroups.
+    Few keys, so that the oracle evaluates the whole pair: all five outputs, every element."""
+    from gpu_util import compare_all_heads
+    spec = dict(B=1, H=2, d=128, Nq=64 * tiles, chunk_rows=[322, 200], block=64, pattern="random", density=0.7)
+    case = workloads.make_case(dtype="bf16", seed=2200 + tiles, device=DEV, **spec)
+    walk = RingWalk(case["Q"], case["scale"], case["causal"], case["q_off"], 0, 64)
+    O, lse = walk.forward(case["K"], case["V"], case["k_offs"], masks=case["masks"])
+    dQ, dKs, dVs = walk.backward(case["K"], case["V"], case["k_offs"], case["dO"], masks=case["masks"])
+    torch.cuda.synchronize()
+    compare_all_heads(case, "bf16", O, lse, dQ, dKs, dVs, dkv_kind="rel")

@@ -93,6 +93,19 @@ def test_bf16_block_sparse_forward_backward(spec):
     compare_all_heads(case, "bf16", O, lse, dQ, dKs, dVs)
 
 
+@pytest.mark.parametrize("spec", [s for s in SPARSE_CASES if s["d"] == 128 and s["block"] == 64],
+                         ids=lambda s: "-".join(f"{k}{v}" for k, v in s.items() if k != "d"))
+def test_narrow_block_flags_with_the_kernels_chosen_per_call(spec, kernel_family):
+    """Left to the per-call choice, 64-wide flags send the dK/dV half to the hand-scheduled kernel's
+    shape with 64-key workgroups (the forced families above never take it)."""
+    if kernel_family != 1:
+        pytest.skip("one run is enough: the test sets the family itself")
+    B.burst_set_kernel_family(0)
+    case = workloads.make_case(dtype="bf16", seed=31, device=DEV, **spec)
+    _, (O, lse, dQ, dKs, dVs) = run_case(case, "bf16")
+    compare_all_heads(case, "bf16", O, lse, dQ, dKs, dVs)
+
+
 @pytest.mark.parametrize("dtype,spec", [
     ("f32", dict(B=1, H=2, d=32, Nq=150, chunk_rows=[100, 90], block=64, pattern="random", density=0.5)),
     ("f32", dict(B=2, H=4, d=32, Nq=150, chunk_rows=[100, 90], block=64, pattern="random", density=0.5,
