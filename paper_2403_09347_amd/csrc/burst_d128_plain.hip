@@ -5,11 +5,10 @@
 // flags hide from its own 32 rows, which the hand-scheduled kernels cannot (their accumulators are
 // pinned to AGPRs through inline assembly, and a branch around the matrix phases makes the
 // register allocator move all of them through VGPRs in every iteration).
-// dK/dV: two wavefronts = 64 keys per workgroup, two workgroups per CU, for calls whose flags have
-// 64-wide blocks: a workgroup's list of visible tiles then holds exactly the tiles its keys are
-// needed for, and the time follows the density of the flags.  (The hand-scheduled dK/dV kernel
-// shares every tile among the 128 keys of its four wavefronts: a tile that only half of them can
-// see costs it the full time.  On dense calls it is the faster one.)
+// dK/dV: two wavefronts = 64 keys per workgroup, two workgroups per CU.  It runs only when this
+// family is forced (burst_set_kernel_family): calls with 64-wide block flags, which it was built
+// for, are served by the hand-scheduled dK/dV kernel's own 64-key shape, which is faster at every
+// density.
 #define BURST_SMALL_D 128
 #define BURST_SMALL_NS d128p
 #define BURST_SMALL_DKV_WAVES 2
