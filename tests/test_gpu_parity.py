@@ -93,7 +93,12 @@ def test_bf16_block_sparse_forward_backward(spec):
     compare_all_heads(case, "bf16", O, lse, dQ, dKs, dVs)
 
 
-@pytest.mark.parametrize("spec", [s for s in SPARSE_CASES if s["d"] == 128 and s["block"] == 64],
+@pytest.mark.parametrize("spec", [s for s in SPARSE_CASES if s["d"] == 128 and s["block"] == 64] + [
+    # grouped heads: the lists of the 64-key workgroups run over the tiles of all heads of a group
+    dict(B=1, H=4, kv_heads=2, d=128, Nq=256, chunk_rows=[256, 192], block=64, pattern="random", density=0.5),
+    dict(B=2, H=6, kv_heads=2, d=128, Nq=448, chunk_rows=[300, 77], block=64, pattern="random", density=0.4,
+         per_head_flags=True, causal=True, q_off=100, layout="seq"),
+],
                          ids=lambda s: "-".join(f"{k}{v}" for k, v in s.items() if k != "d"))
 def test_narrow_block_flags_with_the_kernels_chosen_per_call(spec, kernel_family):
     """Left to the per-call choice, 64-wide flags send the dK/dV half to the hand-scheduled kernel's
