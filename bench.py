@@ -285,6 +285,55 @@ def fused_backward_floor_measurement(w, dev):
     return out
 
 
+def block_sparse_measurement(w, inp, dev):
+    """Sec. 2.6 on the headline block pair: one forward, dQ and dK/dV launch each (first chunk of the
+    workload) under seeded random block flags, ms per launch (best of 3 rounds of 8 launches), dense
+    through the same entry points beside them.  Time that follows the density is the point: tiles
+    that the flags hide are skipped, not masked."""
+    import torch
+    from paper_2403_09347_amd import binding as B
+    from paper_2403_09347_amd import workloads
+    Q, K, V, dO = inp["Q"], inp["K"][0], inp["V"][0], inp["dO"]
+    lse = torch.full((w.B, w.H, w.Nq), 8.0, device=dev)
+    D = torch.zeros((w.B, w.H, w.Nq), device=dev)
+    dQ = torch.zeros((w.B, w.H, w.Nq, w.d), device=dev)
+    dK = torch.empty((w.B, w.H, w.Nc, w.d), device=dev)
+    dV = torch.empty_like(dK)
+    O = torch.zeros_like(dQ)
+    m = torch.full((w.B, w.H, w.Nq), -float("inf"), device=dev)
+    l = torch.zeros((w.B, w.H, w.Nq), device=dev)
+
+    def launches(p):
+        return {"fwd_ms": lambda: B.burst_local_fwd(Q, K, V, O, m, l, p),
+                "dq_ms": lambda: B.burst_local_bwd_dq(Q, K, V, dO, lse, D, dQ, p, False),
+                "dkv_ms": lambda: B.burst_local_bwd_dkv(Q, K, V, dO, lse, D, dK, dV, p)}
+
+    def timed(fn):
+        for _ in range(4):
+            fn()
+        best = 1e30
+        for _ in range(3):
+            a, b = B.Event(), B.Event()
+            a.record()
+            for _ in range(8):
+                fn()
+            b.record()
+            best = min(best, a.elapsed_ms_until(b) / 8)
+        return round(best, 4)
+
+    out = {"note": "per launch, first chunk of the workload; random block flags, seed 3",
+           "dense": {k: timed(fn) for k, fn in launches(
+               B.params(w.B, w.H, w.Nq, w.Nc, w.d, torch.bfloat16, w.scale)).items()}}
+    for block, density in ((64, 0.5), (64, 0.25), (256, 0.5)):
+        flags = workloads.block_flags(w.Nq // block, w.Nc // block, "random", density=density, seed=3)
+        mask = torch.from_numpy(flags).to(dev).contiguous()
+        p = B.params(w.B, w.H, w.Nq, w.Nc, w.d, torch.bfloat16, w.scale, block_mask=mask, block=block)
+        r = {k: timed(fn) for k, fn in launches(p).items()}
+        r["density"] = round(float(flags.mean()), 3)
+        out[f"block{block}_density{density}"] = r
+    return out
+
+
 def graph_measurement(w, inp, reps):
     """The same step recorded once as a HIP graph and replayed (one launch per step) against the
     eager step (one launch per kernel): wall-clock ms per step over `reps` steps each."""
@@ -535,6 +584,8 @@ def main():
             floor["two_kernel_minus_recomputed_contractions_ms"] = round(pair_ms * 5.0 / 7.0, 4)
             out["fused_backward_floor"] = floor
         out["overlap"] = overlap_measurement(w, inp, args.overlap, max(3, args.steps // 2))
+        if w.d == 128 and not w.causal and w.Nq % 256 == 0 and w.Nc % 256 == 0:
+            out["block_sparse"] = block_sparse_measurement(w, inp, dev)
     if args.graph:
         out["graph"] = graph_measurement(w, inp, max(20, args.steps))
     if args.ablation:
