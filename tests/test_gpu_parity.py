@@ -111,6 +111,22 @@ def test_narrow_block_flags_with_the_kernels_chosen_per_call(spec, kernel_family
     compare_all_heads(case, "bf16", O, lse, dQ, dKs, dVs)
 
 
+def test_narrow_block_flags_accumulate_into_dk_dv(kernel_family):
+    """accumulate_dkv = 1 in the 64-key shape of the dK/dV kernel: a second call on the same block
+    pair doubles the first call's result exactly (fp32: x + x)."""
+    if kernel_family != 1:
+        pytest.skip("one run is enough: the test sets the family itself")
+    B.burst_set_kernel_family(0)
+    spec = dict(B=1, H=4, kv_heads=2, d=128, Nq=320, chunk_rows=[200], block=64, pattern="random", density=0.6)
+    case = workloads.make_case(dtype="bf16", seed=33, device=DEV, **spec)
+    walk, (O, lse, dQ, dKs, dVs) = run_case(case, "bf16")
+    p = walk.params(200, case["k_offs"][0], case["masks"][0], case["K"][0])
+    dK2, dV2 = dKs[0].clone(), dVs[0].clone()
+    B.burst_local_bwd_dkv(case["Q"], case["K"][0], case["V"][0], case["dO"], walk.lse, walk.D, dK2, dV2, p, True)
+    torch.cuda.synchronize()
+    assert torch.equal(dK2, 2 * dKs[0]) and torch.equal(dV2, 2 * dVs[0])
+
+
 @pytest.mark.parametrize("dtype,spec", [
     ("f32", dict(B=1, H=2, d=32, Nq=150, chunk_rows=[100, 90], block=64, pattern="random", density=0.5)),
     ("f32", dict(B=2, H=4, d=32, Nq=150, chunk_rows=[100, 90], block=64, pattern="random", density=0.5,
